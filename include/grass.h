@@ -1,0 +1,194 @@
+/*
+ * grass.h - C ABI of the GRASS structured-sparse gradient step for one linear layer
+ *           on one AMD MI355X (gfx950).
+ *
+ * Notation (paper, Sections 2 and 3.1): a linear layer has weight W (m x n), input
+ * activations X (T x n) and output gradient dY (T x m), T being the token batch
+ * (the paper's b).  The full weight gradient is G = dY^T X (m x n).  GRASS uses a
+ * sparse projection P (m x r) with one nonzero per column, stored as
+ * P^T = rho * B: `idx[j]` (the paper's sigma_j) is the row of G that column j of P
+ * selects and `rho[j]` its scale.  One optimisation step (Algorithm 1) is
+ *
+ *     refresh, every K steps:  sumsq = row norms^2 of G;  (idx, rho) = compute_P(sumsq)
+ *     every step:              G_C = P^T G = rho * ((B dY^T) X)          (r x n)
+ *                              (M, V, U) = Adam(M, V, G_C)               (r x n)
+ *                              W += alpha * P * U                        (r rows of W)
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless the
+ *     argument is documented as a host value.  The library allocates no memory and
+ *     keeps no state between calls; scratch memory is sized by the *_workspace
+ *     queries and passed in by the caller.
+ *   - Matrices are row-major with an explicit leading dimension counted in
+ *     ELEMENTS (ld >= number of columns).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it; no call synchronises with the host.
+ *   - Arguments are validated on the host before anything is launched.  A call
+ *     that returns anything but GRASS_OK has launched nothing and written nothing.
+ *   - r = 0, n = 0 or T = 0 are legal where they make sense (see each call) and
+ *     produce the empty / zero result.
+ */
+#ifndef GRASS_H
+#define GRASS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRASS_OK = 0,
+    GRASS_ERR_NULL = 1,      /* a required pointer is NULL                              */
+    GRASS_ERR_SHAPE = 2,     /* negative size, r > m where forbidden, ld too small ...  */
+    GRASS_ERR_DTYPE = 3,     /* dtype / enum value not supported by this call           */
+    GRASS_ERR_WORKSPACE = 4, /* workspace pointer NULL or smaller than the query says   */
+    GRASS_ERR_NONFINITE = 5, /* sumsq holds NaN, Inf or a negative value (select only)  */
+    GRASS_ERR_DEVICE = 6     /* a HIP launch failed                                     */
+} grass_status;
+
+typedef enum { GRASS_F32 = 0, GRASS_BF16 = 1 } grass_dtype;
+
+/* compute_P rules of Section 3.2.  The sampling rules draw sigma_j from
+ * Multinomial(1, q) with q_k = 1/m (UNIFORM), q_k ~ ||G_k|| (MULTI_NORM, Theorem 3.1)
+ * or q_k ~ ||G_k||^2 (MULTI_NORM2); TOPR takes the r rows of largest norm. */
+typedef enum {
+    GRASS_SEL_TOPR = 0,
+    GRASS_SEL_UNIFORM = 1,
+    GRASS_SEL_MULTI_NORM = 2,
+    GRASS_SEL_MULTI_NORM2 = 3
+} grass_method;
+
+/* How rho is set.  PAPER follows Section 3.2: 1/sqrt(r*q_sigma) when sampling
+ * with replacement, 1 for sampling without replacement and for Top-r.  ONE and
+ * INV_SQRT_RQ force one of the two rules whatever the method (INV_SQRT_RQ uses
+ * the q of the initial distribution; with TOPR it is rejected). */
+typedef enum {
+    GRASS_SCALE_PAPER = 0,
+    GRASS_SCALE_ONE = 1,
+    GRASS_SCALE_INV_SQRT_RQ = 2
+} grass_scale;
+
+/* Storage of the output gradient: GRASS_DY_TxM is dY[t*ldy + k] (what a backward
+ * pass produces, Section 3.1), GRASS_DY_MxT is its transpose dY[k*ldy + t]. */
+typedef enum { GRASS_DY_TxM = 0, GRASS_DY_MxT = 1 } grass_dy_layout;
+
+/* Readable name of a status code.  Returns a static string; never NULL. */
+const char* grass_status_string(grass_status s);
+
+/* ---------------------------------------------------------------------------
+ * compute_P, part 1 (Section 3.2; cost "mn" in the FLOP table of Appendix F):
+ *   sumsq[k] = sum_j G[k, j]^2,  the squared 2-norm of row k of G.
+ * G: m x n, dtype `dt`, leading dimension ldg.  sumsq: m floats (fp32
+ * accumulation).  m = 0 is a no-op; n = 0 writes zeros.
+ * Errors: NULL, SHAPE (m, n < 0, ldg < n), DTYPE. */
+grass_status grass_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n, int64_t ldg,
+                             float* sumsq, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * compute_P, part 2 (Section 3.2): choose idx[r] and rho[r] from sumsq[m].
+ *
+ * TOPR: the r rows with the largest sumsq; ties go to the lower row index.
+ * Sampling rules: integer weights wq_k = floor(w_k / max_i w_i * 2^40) + 1 with
+ *   w_k = sqrt(sumsq_k) (MULTI_NORM), sumsq_k (MULTI_NORM2) or 1 (UNIFORM), all in
+ *   IEEE double (if every w_k is 0 all wq_k are 1); q_k = wq_k / sum_i wq_i.
+ *   Draw j uses the 64-bit word x_j = Philox4x32-10(key = seed,
+ *   counter = (j, refresh_id)), low word first, and target = floor(x_j * S / 2^64).
+ *   With replacement (replacement != 0): S = sum wq, sigma_j is the first k whose
+ *   inclusive prefix sum exceeds target.  Without: draws are sequential, S is the
+ *   weight still present, the drawn row's weight is set to 0 afterwards.
+ * Output: idx sorted ascending (duplicates adjacent; only possible with
+ *   replacement); rho per `scale`, rounded from double to float.
+ * Requirements: 0 <= r; r <= m unless sampling with replacement; m < 2^31.
+ * `ws` must hold grass_select_workspace(...) bytes.  Its first 4 bytes are a
+ * device status word the caller may read back after the stream has finished:
+ * GRASS_OK, or GRASS_ERR_NONFINITE when sumsq held NaN / Inf / a negative
+ * value, in which case idx = 0..r-1 (mod m) and rho = 1 are written so that
+ * later calls stay in bounds.
+ * Errors (host, before launch): NULL, SHAPE, DTYPE (bad enum, or
+ * INV_SQRT_RQ with TOPR), WORKSPACE. */
+size_t grass_select_workspace(int64_t m, int64_t r, grass_method method, int replacement);
+grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                               int replacement, grass_scale scale, uint64_t seed,
+                               uint64_t refresh_id, int32_t* idx, float* rho, void* ws,
+                               size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Compressed gradient (Section 3.1, "Efficient Gradient Projection"; Algorithm 1
+ * line "G_C <- P^T grad"):
+ *   GC[j, i] = rho[j] * sum_t dY[t, idx[j]] * X[t, i],   j < r, i < n.
+ * The full m x n gradient is never formed.  dY and X have dtype `dt` (bf16 inputs
+ * are multiplied on the matrix cores with fp32 accumulation); GC is fp32, r x n,
+ * leading dimension ldgc.  idx values must lie in [0, m) (not checked on the
+ * device: idx comes from grass_select_rows); duplicates are allowed.
+ * T = 0 writes zeros.  `ws` must hold grass_cgrad_workspace(...) bytes.
+ * Errors: NULL, SHAPE, DTYPE, WORKSPACE. */
+size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt,
+                             grass_dy_layout layout);
+grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                   const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                   int64_t m, int64_t n, int64_t r, const int32_t* idx,
+                                   const float* rho, float* GC, int64_t ldgc, void* ws,
+                                   size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * opt.update = Adam on the r x n compressed gradient (Appendix A, adam.update):
+ *   M <- b1*M + (1-b1)*g        V <- b2*V + (1-b2)*g^2
+ *   U  = -lr * (M/(1-b1^t)) / (sqrt(V/(1-b2^t)) + eps)
+ * GC (ld ldgc), M, V, U (dense r x n) are fp32; M and V are updated in place.
+ * t >= 1 is the 1-based count of Adam updates since M, V were last zeroed (the
+ * caller resets it together with the state, Section 3.3).  lr, beta1, beta2, eps
+ * and t are host values.
+ * Errors: NULL, SHAPE (also t < 1, beta outside [0,1)). */
+grass_status grass_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                             int64_t n, float lr, float beta1, float beta2, float eps,
+                             int64_t t, float* U, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Sparse weight update (Section 3.1, "Efficient Weight Update"; Algorithm 1 line
+ * "W <- W + alpha P Delta"):
+ *   W[idx[j], :] += alpha * rho[j] * U[j, :]      for j < r.
+ * idx must be sorted ascending (as grass_select_rows writes it).  Rows that occur
+ * several times receive the sum of their updates, accumulated in fp32 in j order
+ * and rounded once (to nearest even) to W's dtype.  Rows not in idx are not
+ * touched.  W: m x n of dtype wdt, leading dimension ldw, updated in place.
+ * U: dense r x n fp32.
+ * Errors: NULL, SHAPE, DTYPE. */
+grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
+                                  const int32_t* idx, const float* rho, float alpha,
+                                  const float* U, int64_t r, void* stream);
+
+/* Fused form of grass_adam_rows followed by grass_scatter_update: same
+ * arithmetic, but U is never written to memory.  This is the call the regular
+ * step uses. */
+grass_status grass_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                                int64_t n, float lr, float beta1, float beta2, float eps,
+                                int64_t t, void* W, grass_dtype wdt, int64_t m, int64_t ldw,
+                                const int32_t* idx, const float* rho, float alpha,
+                                void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Full gradient G = dY^T X (m x n), Section 3.1.  This is what dense-projection
+ * methods compute every step ("mbn" FLOPs, Appendix F) and what GRASS needs on a
+ * refresh step to obtain row norms; it also serves as the naive comparator
+ * (full G followed by a row gather).  G has dtype gdt (fp32 accumulation, one
+ * rounding), leading dimension ldg.
+ * Errors: NULL, SHAPE, DTYPE, WORKSPACE. */
+size_t grass_dense_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                             grass_dy_layout layout);
+grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
+                              int64_t ldx, grass_dtype dt, int64_t T, int64_t m, int64_t n,
+                              void* G, grass_dtype gdt, int64_t ldg, void* ws, size_t ws_bytes,
+                              void* stream);
+
+/* Row gather used by the naive comparator: out[j, :] = rho[j] * G[idx[j], :]
+ * (fp32 out, r x n, leading dimension ldo).  Errors: NULL, SHAPE, DTYPE. */
+grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,
+                               const int32_t* idx, const float* rho, int64_t r, float* out,
+                               int64_t ldo, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRASS_H */
