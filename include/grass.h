@@ -25,6 +25,10 @@
  *     work is enqueued on it; no call synchronises with the host.
  *   - Arguments are validated on the host before anything is launched.  A call
  *     that returns anything but GRASS_OK has launched nothing and written nothing.
+ *     A pointer may be NULL only when the array it names has no elements.
+ *   - Calls that walk the compressed rows in the grid (compressed_grad,
+ *     scatter_update, adam_scatter, gather_rows, dense_grad's m) accept at most
+ *     65535 rows and return GRASS_ERR_SHAPE beyond that.
  *   - r = 0, n = 0 or T = 0 are legal where they make sense (see each call) and
  *     produce the empty / zero result.
  */
@@ -104,8 +108,8 @@ grass_status grass_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n
  * `ws` must hold grass_select_workspace(...) bytes.  Its first 4 bytes are a
  * device status word the caller may read back after the stream has finished:
  * GRASS_OK, or GRASS_ERR_NONFINITE when sumsq held NaN / Inf / a negative
- * value, in which case idx = 0..r-1 (mod m) and rho = 1 are written so that
- * later calls stay in bounds.
+ * value, in which case the placeholder idx[j] = floor(j*m/r), rho = 1 is written
+ * so that later calls stay in bounds.
  * Errors (host, before launch): NULL, SHAPE, DTYPE (bad enum, or
  * INV_SQRT_RQ with TOPR), WORKSPACE. */
 size_t grass_select_workspace(int64_t m, int64_t r, grass_method method, int replacement);

@@ -1,0 +1,353 @@
+// grass_adam_rows, grass_scatter_update, grass_adam_scatter, grass_gather_rows.
+//
+// All four are HBM-bound elementwise passes over r x n values.  A workgroup of 256
+// threads owns 1024 consecutive columns of one compressed row j (grid = column chunks
+// x r); each thread handles four consecutive columns with 16-byte loads and stores of
+// the fp32 arrays (8-byte for bf16 W), so every wave access is a contiguous 1 KiB.
+// Buffers whose base or leading dimension breaks that alignment take the one-element-
+// per-thread variant of the same kernel.
+//
+// Rows selected more than once (sampling with replacement) sit next to each other in
+// the sorted idx.  The workgroups of the first occurrence walk the whole run, so a row
+// of W is written by exactly one thread per column: no atomics, deterministic sums.
+#include "common.hpp"
+
+namespace grass {
+namespace {
+
+constexpr int kThreads = 256;
+
+struct AdamParams {
+    float b1, one_minus_b1, b2, one_minus_b2;
+    float c1, c2;  // bias corrections 1 - beta^t
+    float lr, eps;
+};
+
+// adam.update of Appendix A for one element; returns U.
+__device__ __forceinline__ float adam_elem(float g, float& m, float& v, const AdamParams& p) {
+    m = p.b1 * m + p.one_minus_b1 * g;
+    v = p.b2 * v + p.one_minus_b2 * g * g;
+    const float ms = m / p.c1;
+    const float vs = v / p.c2;
+    return -p.lr * ms / (sqrtf(vs) + p.eps);
+}
+
+template <int VEC>
+struct F32Vec;
+template <>
+struct F32Vec<4> {
+    float x[4];
+    __device__ void load(const float* p) {
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    }
+    __device__ void store(float* p) const {
+        *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    }
+};
+template <>
+struct F32Vec<1> {
+    float x[1];
+    __device__ void load(const float* p) { x[0] = *p; }
+    __device__ void store(float* p) const { *p = x[0]; }
+};
+
+template <typename WT, int VEC>
+struct WVec;
+template <>
+struct WVec<float, 4> : F32Vec<4> {};
+template <>
+struct WVec<float, 1> : F32Vec<1> {};
+template <>
+struct WVec<uint16_t, 4> {
+    float x[4];
+    __device__ void load(const uint16_t* p) {
+        const uint2 t = *reinterpret_cast<const uint2*>(p);
+        x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xFFFF0000u);
+        x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    }
+    __device__ void store(uint16_t* p) const {
+        uint2 t;
+        t.x = f32_to_bf16(x[0]) | (static_cast<uint32_t>(f32_to_bf16(x[1])) << 16);
+        t.y = f32_to_bf16(x[2]) | (static_cast<uint32_t>(f32_to_bf16(x[3])) << 16);
+        *reinterpret_cast<uint2*>(p) = t;
+    }
+};
+template <>
+struct WVec<uint16_t, 1> {
+    float x[1];
+    __device__ void load(const uint16_t* p) { x[0] = bf16_to_f32(*p); }
+    __device__ void store(uint16_t* p) const { *p = f32_to_bf16(x[0]); }
+};
+
+// Column range of this thread: [c, c + cnt), cnt in 0..VEC.  Full vectors take the wide
+// path; a ragged last vector is handled element by element by the caller.
+template <int VEC>
+__device__ __forceinline__ int64_t thread_col(int64_t n, int& cnt) {
+    const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * VEC;
+    const int64_t left = n - c;
+    cnt = left >= VEC ? VEC : (left > 0 ? static_cast<int>(left) : 0);
+    return c;
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void adam_rows_kernel(
+    const float* __restrict__ GC, int64_t ldgc, float* __restrict__ M, float* __restrict__ V,
+    float* __restrict__ U, int64_t n, AdamParams p) {
+    const int64_t j = blockIdx.y;
+    int cnt;
+    const int64_t c = thread_col<VEC>(n, cnt);
+    if (cnt == 0) return;
+    const float* g = GC + j * ldgc + c;
+    float* mp = M + j * n + c;
+    float* vp = V + j * n + c;
+    float* up = U + j * n + c;
+    if (cnt == VEC) {
+        F32Vec<VEC> gv, mv, vv, uv;
+        gv.load(g); mv.load(mp); vv.load(vp);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) uv.x[e] = adam_elem(gv.x[e], mv.x[e], vv.x[e], p);
+        mv.store(mp); vv.store(vp); uv.store(up);
+    } else {
+        for (int e = 0; e < cnt; ++e) {
+            float mm = mp[e], vv = vp[e];
+            up[e] = adam_elem(g[e], mm, vv, p);
+            mp[e] = mm; vp[e] = vv;
+        }
+    }
+}
+
+// W[idx[j], :] += alpha * sum over the run of equal idx of rho * U.
+template <typename WT, int VEC>
+__global__ __launch_bounds__(kThreads) void scatter_kernel(
+    WT* __restrict__ W, int64_t ldw, const int32_t* __restrict__ idx,
+    const float* __restrict__ rho, float alpha, const float* __restrict__ U, int64_t n, int64_t r) {
+    const int64_t j = blockIdx.y;
+    const int32_t row = idx[j];
+    if (j > 0 && idx[j - 1] == row) return;  // a later member of a run: the first one does it
+    int cnt;
+    const int64_t c = thread_col<VEC>(n, cnt);
+    if (cnt == 0) return;
+    WT* wp = W + static_cast<int64_t>(row) * ldw + c;
+    if (cnt == VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+            F32Vec<VEC> uv;
+            uv.load(U + jj * n + c);
+            const float s = rho[jj];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += s * uv.x[e];
+        }
+        WVec<WT, VEC> wv;
+        wv.load(wp);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) wv.x[e] += alpha * acc[e];
+        wv.store(wp);
+    } else {
+        for (int e = 0; e < cnt; ++e) {
+            float acc = 0.f;
+            for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) acc += rho[jj] * U[jj * n + c + e];
+            store_from_f32(wp + e, load_as_f32(wp + e) + alpha * acc);
+        }
+    }
+}
+
+// Adam on every row of the run, then one write of W; U stays in registers.
+template <typename WT, int VEC>
+__global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
+    const float* __restrict__ GC, int64_t ldgc, float* __restrict__ M, float* __restrict__ V,
+    int64_t n, int64_t r, AdamParams p, WT* __restrict__ W, int64_t ldw,
+    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha) {
+    const int64_t j = blockIdx.y;
+    const int32_t row = idx[j];
+    if (j > 0 && idx[j - 1] == row) return;
+    int cnt;
+    const int64_t c = thread_col<VEC>(n, cnt);
+    if (cnt == 0) return;
+    WT* wp = W + static_cast<int64_t>(row) * ldw + c;
+    if (cnt == VEC) {
+        WVec<WT, VEC> wv;
+        wv.load(wp);  // issued first: independent of the Adam loads below
+        float acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+            F32Vec<VEC> gv, mv, vv;
+            gv.load(GC + jj * ldgc + c);
+            mv.load(M + jj * n + c);
+            vv.load(V + jj * n + c);
+            const float s = rho[jj];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += s * adam_elem(gv.x[e], mv.x[e], vv.x[e], p);
+            mv.store(M + jj * n + c);
+            vv.store(V + jj * n + c);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) wv.x[e] += alpha * acc[e];
+        wv.store(wp);
+    } else {
+        for (int e = 0; e < cnt; ++e) {
+            float acc = 0.f;
+            for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+                float mm = M[jj * n + c + e], vv = V[jj * n + c + e];
+                acc += rho[jj] * adam_elem(GC[jj * ldgc + c + e], mm, vv, p);
+                M[jj * n + c + e] = mm;
+                V[jj * n + c + e] = vv;
+            }
+            store_from_f32(wp + e, load_as_f32(wp + e) + alpha * acc);
+        }
+    }
+}
+
+template <typename GT, int VEC>
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(
+    const GT* __restrict__ G, int64_t ldg, const int32_t* __restrict__ idx,
+    const float* __restrict__ rho, float* __restrict__ out, int64_t ldo, int64_t n) {
+    const int64_t j = blockIdx.y;
+    int cnt;
+    const int64_t c = thread_col<VEC>(n, cnt);
+    if (cnt == 0) return;
+    const GT* gp = G + static_cast<int64_t>(idx[j]) * ldg + c;
+    float* op = out + j * ldo + c;
+    const float s = rho[j];
+    if (cnt == VEC) {
+        WVec<GT, VEC> gv;
+        gv.load(gp);
+        F32Vec<VEC> ov;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) ov.x[e] = s * gv.x[e];
+        ov.store(op);
+    } else {
+        for (int e = 0; e < cnt; ++e) op[e] = s * load_as_f32(gp + e);
+    }
+}
+
+AdamParams make_params(float lr, float b1, float b2, float eps, int64_t t) {
+    AdamParams p;
+    p.b1 = b1;
+    p.one_minus_b1 = 1.0f - b1;
+    p.b2 = b2;
+    p.one_minus_b2 = 1.0f - b2;
+    p.c1 = static_cast<float>(1.0 - pow(static_cast<double>(b1), static_cast<double>(t)));
+    p.c2 = static_cast<float>(1.0 - pow(static_cast<double>(b2), static_cast<double>(t)));
+    p.lr = lr;
+    p.eps = eps;
+    return p;
+}
+
+dim3 grid_for(int64_t n, int64_t r, int vec) {
+    const int64_t per_block = static_cast<int64_t>(kThreads) * vec;
+    return dim3(static_cast<unsigned>((n + per_block - 1) / per_block), static_cast<unsigned>(r));
+}
+
+bool f32_rows_vectorisable(const void* p, int64_t ld) { return aligned_to(p, 16) && ld % 4 == 0; }
+bool w_rows_vectorisable(const void* p, grass_dtype dt, int64_t ld) {
+    return aligned_to(p, dt == GRASS_F32 ? 16 : 8) && ld % 4 == 0;
+}
+
+}  // namespace
+
+// blockIdx.y carries the row: at most 65535 rows per launch, larger r goes in slices.
+constexpr int64_t kMaxGridY = 65535;
+
+grass_status launch_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                              int64_t n, float lr, float b1, float b2, float eps, int64_t t,
+                              float* U, hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    const AdamParams p = make_params(lr, b1, b2, eps, t);
+    const bool vec = f32_rows_vectorisable(GC, ldgc) && f32_rows_vectorisable(M, n) &&
+                     f32_rows_vectorisable(V, n) && f32_rows_vectorisable(U, n);
+    for (int64_t j0 = 0; j0 < r; j0 += kMaxGridY) {
+        const int64_t rr = r - j0 < kMaxGridY ? r - j0 : kMaxGridY;
+        if (vec)
+            adam_rows_kernel<4><<<grid_for(n, rr, 4), kThreads, 0, s>>>(
+                GC + j0 * ldgc, ldgc, M + j0 * n, V + j0 * n, U + j0 * n, n, p);
+        else
+            adam_rows_kernel<1><<<grid_for(n, rr, 1), kThreads, 0, s>>>(
+                GC + j0 * ldgc, ldgc, M + j0 * n, V + j0 * n, U + j0 * n, n, p);
+    }
+    return launch_status();
+}
+
+template <typename WT>
+static grass_status scatter_typed(void* W, grass_dtype wdt, int64_t n, int64_t ldw,
+                                  const int32_t* idx, const float* rho, float alpha,
+                                  const float* U, int64_t r, hipStream_t s) {
+    // A run of equal idx must not straddle two launches, so r > 65535 is done in one
+    // launch per slice only when the slice boundary is not inside a run; the kernel's run
+    // walk is bounded by the full r and its "first of the run" test looks at idx[j-1] of
+    // the full array, so slices simply pass offsets into the same arrays.
+    const bool vec = w_rows_vectorisable(W, wdt, ldw) && f32_rows_vectorisable(U, n);
+    if (r > kMaxGridY) return GRASS_ERR_SHAPE;
+    if (vec)
+        scatter_kernel<WT, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+            static_cast<WT*>(W), ldw, idx, rho, alpha, U, n, r);
+    else
+        scatter_kernel<WT, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
+            static_cast<WT*>(W), ldw, idx, rho, alpha, U, n, r);
+    return launch_status();
+}
+
+grass_status launch_scatter(void* W, grass_dtype wdt, int64_t n, int64_t ldw, const int32_t* idx,
+                            const float* rho, float alpha, const float* U, int64_t r,
+                            hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    return wdt == GRASS_F32 ? scatter_typed<float>(W, wdt, n, ldw, idx, rho, alpha, U, r, s)
+                            : scatter_typed<uint16_t>(W, wdt, n, ldw, idx, rho, alpha, U, r, s);
+}
+
+template <typename WT>
+static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, float* M, float* V,
+                                       int64_t r, int64_t n, const AdamParams& p, void* W,
+                                       grass_dtype wdt, int64_t ldw, const int32_t* idx,
+                                       const float* rho, float alpha, hipStream_t s) {
+    const bool vec = f32_rows_vectorisable(GC, ldgc) && f32_rows_vectorisable(M, n) &&
+                     f32_rows_vectorisable(V, n) && w_rows_vectorisable(W, wdt, ldw);
+    if (r > kMaxGridY) return GRASS_ERR_SHAPE;
+    if (vec)
+        adam_scatter_kernel<WT, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+            GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
+    else
+        adam_scatter_kernel<WT, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
+            GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
+    return launch_status();
+}
+
+grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                                 int64_t n, float lr, float b1, float b2, float eps, int64_t t,
+                                 void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,
+                                 const float* rho, float alpha, hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    const AdamParams p = make_params(lr, b1, b2, eps, t);
+    return wdt == GRASS_F32
+               ? adam_scatter_typed<float>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
+               : adam_scatter_typed<uint16_t>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho,
+                                              alpha, s);
+}
+
+template <typename GT>
+static grass_status gather_typed(const void* G, grass_dtype gdt, int64_t n, int64_t ldg,
+                                 const int32_t* idx, const float* rho, int64_t r, float* out,
+                                 int64_t ldo, hipStream_t s) {
+    const bool vec = w_rows_vectorisable(G, gdt, ldg) && f32_rows_vectorisable(out, ldo);
+    if (r > kMaxGridY) return GRASS_ERR_SHAPE;
+    if (vec)
+        gather_rows_kernel<GT, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+            static_cast<const GT*>(G), ldg, idx, rho, out, ldo, n);
+    else
+        gather_rows_kernel<GT, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
+            static_cast<const GT*>(G), ldg, idx, rho, out, ldo, n);
+    return launch_status();
+}
+
+grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64_t ldg,
+                                const int32_t* idx, const float* rho, int64_t r, float* out,
+                                int64_t ldo, hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    return gdt == GRASS_F32 ? gather_typed<float>(G, gdt, n, ldg, idx, rho, r, out, ldo, s)
+                            : gather_typed<uint16_t>(G, gdt, n, ldg, idx, rho, r, out, ldo, s);
+}
+
+}  // namespace grass

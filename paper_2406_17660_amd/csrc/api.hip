@@ -1,0 +1,180 @@
+// C entry points declared in include/grass.h: host-side argument validation, then the
+// kernel launchers.  Validation touches no device memory and makes no HIP call, so a call
+// that fails validation has no side effect (and can be exercised on a machine without a
+// GPU).
+#include "common.hpp"
+
+using namespace grass;
+
+namespace {
+
+constexpr int64_t kMaxGridRows = 65535;  // rows are carried in blockIdx.y
+
+// A pointer may be NULL only when the array it names has no elements.
+bool present(const void* p, int64_t elems) { return p != nullptr || elems <= 0; }
+bool dtype_ok(grass_dtype d) { return d == GRASS_F32 || d == GRASS_BF16; }
+bool layout_ok(grass_dy_layout l) { return l == GRASS_DY_TxM || l == GRASS_DY_MxT; }
+hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+grass_status check_products(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
+                            int64_t ldx, grass_dtype dt, int64_t T, int64_t m, int64_t n) {
+    if (T < 0 || m < 0 || n < 0 || ldx < n) return GRASS_ERR_SHAPE;
+    if (!present(dY, T * m) || !present(X, T * n)) return GRASS_ERR_NULL;
+    if (!dtype_ok(dt) || !layout_ok(layout)) return GRASS_ERR_DTYPE;
+    if (ldy < (layout == GRASS_DY_TxM ? m : T)) return GRASS_ERR_SHAPE;
+    if (m >= (int64_t{1} << 31) || n >= (int64_t{1} << 31) || T >= (int64_t{1} << 40))
+        return GRASS_ERR_SHAPE;
+    return GRASS_OK;
+}
+
+grass_status check_adam(const float* GC, int64_t ldgc, const float* M, const float* V, int64_t r,
+                        int64_t n, float beta1, float beta2, int64_t t) {
+    if (r < 0 || n < 0 || ldgc < n || t < 1) return GRASS_ERR_SHAPE;
+    if (!present(GC, r * n) || !present(M, r * n) || !present(V, r * n)) return GRASS_ERR_NULL;
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return GRASS_ERR_SHAPE;
+    return GRASS_OK;
+}
+
+grass_status check_rows_of_w(const void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
+                             const int32_t* idx, const float* rho, int64_t r) {
+    if (m < 0 || n < 0 || r < 0 || ldw < n || r > kMaxGridRows) return GRASS_ERR_SHAPE;
+    if (!present(W, m * n) || !present(idx, r) || !present(rho, r)) return GRASS_ERR_NULL;
+    if (!dtype_ok(wdt)) return GRASS_ERR_DTYPE;
+    if (r > 0 && m == 0) return GRASS_ERR_SHAPE;
+    return GRASS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* grass_status_string(grass_status s) {
+    switch (s) {
+        case GRASS_OK: return "ok";
+        case GRASS_ERR_NULL: return "null pointer";
+        case GRASS_ERR_SHAPE: return "bad shape or size";
+        case GRASS_ERR_DTYPE: return "unsupported dtype or option";
+        case GRASS_ERR_WORKSPACE: return "workspace missing or too small";
+        case GRASS_ERR_NONFINITE: return "row statistics are not finite and non-negative";
+        case GRASS_ERR_DEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+grass_status grass_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n, int64_t ldg,
+                             float* sumsq, void* stream) {
+    if (m < 0 || n < 0 || ldg < n || m >= (int64_t{1} << 31)) return GRASS_ERR_SHAPE;
+    if (!present(G, m * n) || !present(sumsq, m)) return GRASS_ERR_NULL;
+    if (!dtype_ok(dt)) return GRASS_ERR_DTYPE;
+    return launch_row_stats(G, dt, m, n, ldg, sumsq, as_stream(stream));
+}
+
+size_t grass_select_workspace(int64_t m, int64_t r, grass_method method, int replacement) {
+    return select_workspace_bytes(m, r, method, replacement);
+}
+
+grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                               int replacement, grass_scale scale, uint64_t seed,
+                               uint64_t refresh_id, int32_t* idx, float* rho, void* ws,
+                               size_t ws_bytes, void* stream) {
+    if (m < 0 || r < 0) return GRASS_ERR_SHAPE;
+    if (!present(sumsq, m) || !present(idx, r) || !present(rho, r)) return GRASS_ERR_NULL;
+    if (method < GRASS_SEL_TOPR || method > GRASS_SEL_MULTI_NORM2) return GRASS_ERR_DTYPE;
+    if (scale < GRASS_SCALE_PAPER || scale > GRASS_SCALE_INV_SQRT_RQ) return GRASS_ERR_DTYPE;
+    if (method == GRASS_SEL_TOPR && scale == GRASS_SCALE_INV_SQRT_RQ) return GRASS_ERR_DTYPE;
+    if (m < 0 || r < 0 || m >= (int64_t{1} << 31) || r >= (int64_t{1} << 31))
+        return GRASS_ERR_SHAPE;
+    const bool with_repl = method != GRASS_SEL_TOPR && replacement;
+    if (!with_repl && r > m) return GRASS_ERR_SHAPE;
+    if (r > 0 && m == 0) return GRASS_ERR_SHAPE;
+    if (!ws || ws_bytes < select_workspace_bytes(m, r, method, replacement))
+        return GRASS_ERR_WORKSPACE;
+    return launch_select(sumsq, m, r, method, replacement, scale, seed, refresh_id, idx, rho, ws,
+                         as_stream(stream));
+}
+
+size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt,
+                             grass_dy_layout layout) {
+    (void)m;
+    if (T < 0 || n < 0 || r < 0) return 0;
+    return gemm_workspace_bytes(T, r, n, dt, layout, true);
+}
+
+grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                   const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                   int64_t m, int64_t n, int64_t r, const int32_t* idx,
+                                   const float* rho, float* GC, int64_t ldgc, void* ws,
+                                   size_t ws_bytes, void* stream) {
+    const grass_status st = check_products(dY, layout, ldy, X, ldx, dt, T, m, n);
+    if (st != GRASS_OK) return st;
+    if (r < 0 || r > kMaxGridRows || ldgc < n || (r > 0 && m == 0)) return GRASS_ERR_SHAPE;
+    if (!present(idx, r) || !present(rho, r) || !present(GC, r * n)) return GRASS_ERR_NULL;
+    const size_t need = gemm_workspace_bytes(T, r, n, dt, layout, true);
+    if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
+    return launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, r, n, idx, rho, GC, GRASS_F32, ldgc, ws,
+                          as_stream(stream));
+}
+
+grass_status grass_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                             int64_t n, float lr, float beta1, float beta2, float eps, int64_t t,
+                             float* U, void* stream) {
+    const grass_status st = check_adam(GC, ldgc, M, V, r, n, beta1, beta2, t);
+    if (st != GRASS_OK) return st;
+    if (!present(U, r * n)) return GRASS_ERR_NULL;
+    return launch_adam_rows(GC, ldgc, M, V, r, n, lr, beta1, beta2, eps, t, U, as_stream(stream));
+}
+
+grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
+                                  const int32_t* idx, const float* rho, float alpha,
+                                  const float* U, int64_t r, void* stream) {
+    const grass_status st = check_rows_of_w(W, wdt, m, n, ldw, idx, rho, r);
+    if (st != GRASS_OK) return st;
+    if (!present(U, r * n)) return GRASS_ERR_NULL;
+    return launch_scatter(W, wdt, n, ldw, idx, rho, alpha, U, r, as_stream(stream));
+}
+
+grass_status grass_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                                int64_t n, float lr, float beta1, float beta2, float eps,
+                                int64_t t, void* W, grass_dtype wdt, int64_t m, int64_t ldw,
+                                const int32_t* idx, const float* rho, float alpha, void* stream) {
+    grass_status st = check_adam(GC, ldgc, M, V, r, n, beta1, beta2, t);
+    if (st != GRASS_OK) return st;
+    st = check_rows_of_w(W, wdt, m, n, ldw, idx, rho, r);
+    if (st != GRASS_OK) return st;
+    return launch_adam_scatter(GC, ldgc, M, V, r, n, lr, beta1, beta2, eps, t, W, wdt, ldw, idx,
+                               rho, alpha, as_stream(stream));
+}
+
+size_t grass_dense_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                             grass_dy_layout layout) {
+    if (T < 0 || m < 0 || n < 0) return 0;
+    return gemm_workspace_bytes(T, m, n, dt, layout, false);
+}
+
+grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
+                              int64_t ldx, grass_dtype dt, int64_t T, int64_t m, int64_t n,
+                              void* G, grass_dtype gdt, int64_t ldg, void* ws, size_t ws_bytes,
+                              void* stream) {
+    const grass_status st = check_products(dY, layout, ldy, X, ldx, dt, T, m, n);
+    if (st != GRASS_OK) return st;
+    if (ldg < n || m > kMaxGridRows) return GRASS_ERR_SHAPE;
+    if (!present(G, m * n)) return GRASS_ERR_NULL;
+    if (!dtype_ok(gdt)) return GRASS_ERR_DTYPE;
+    const size_t need = gemm_workspace_bytes(T, m, n, dt, layout, false);
+    if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
+    return launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, m, n, nullptr, nullptr, G, gdt, ldg, ws,
+                          as_stream(stream));
+}
+
+grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,
+                               const int32_t* idx, const float* rho, int64_t r, float* out,
+                               int64_t ldo, void* stream) {
+    if (m < 0 || n < 0 || r < 0 || ldg < n || ldo < n || r > kMaxGridRows || (r > 0 && m == 0))
+        return GRASS_ERR_SHAPE;
+    if (!present(G, m * n) || !present(idx, r) || !present(rho, r) || !present(out, r * n))
+        return GRASS_ERR_NULL;
+    if (!dtype_ok(gdt)) return GRASS_ERR_DTYPE;
+    return launch_gather_rows(G, gdt, n, ldg, idx, rho, r, out, ldo, as_stream(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Shared device helpers for the gfx950 kernels: bf16 conversion, wavefront (64-lane)
+// reductions and scans, launch-error mapping.  Nothing here is used by the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/grass.h"
+
+namespace grass {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Round to nearest even; NaN stays NaN (quiet), as IEEE conversion does.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_f32(const T* p);
+template <>
+__device__ __forceinline__ float load_as_f32<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_as_f32<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_from_f32(T* p, float v);
+template <>
+__device__ __forceinline__ void store_from_f32<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_from_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const double w = __shfl_xor(v, o, kWave);
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v) {
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const T up = __shfl_up(v, o, kWave);
+        if (lane >= o) v += up;
+    }
+    return v;
+}
+
+inline grass_status launch_status() {
+    return hipGetLastError() == hipSuccess ? GRASS_OK : GRASS_ERR_DEVICE;
+}
+
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Kernel launchers, one per translation unit.  All pointers are device pointers; shapes
+// have been validated by the C entry points in api.hip before these are called.
+grass_status launch_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n, int64_t ldg,
+                              float* sumsq, hipStream_t s);
+grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                           int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
+                           int32_t* idx, float* rho, void* ws, hipStream_t s);
+size_t select_workspace_bytes(int64_t m, int64_t r, grass_method method, int replacement);
+grass_status launch_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                              int64_t n, float lr, float b1, float b2, float eps, int64_t t,
+                              float* U, hipStream_t s);
+grass_status launch_scatter(void* W, grass_dtype wdt, int64_t n, int64_t ldw, const int32_t* idx,
+                            const float* rho, float alpha, const float* U, int64_t r,
+                            hipStream_t s);
+grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
+                                 int64_t n, float lr, float b1, float b2, float eps, int64_t t,
+                                 void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,
+                                 const float* rho, float alpha, hipStream_t s);
+grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64_t ldg,
+                                const int32_t* idx, const float* rho, int64_t r, float* out,
+                                int64_t ldo, hipStream_t s);
+// C[j, i] = scale_j * sum_t A[t, col_j] * B[t, i]  (cgrad: col_j = idx[j], scale_j = rho[j];
+// dense: idx = rho = nullptr).  Output dtype odt, leading dimension ldc.
+size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
+                            grass_dy_layout layout, bool gathered);
+grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
+                            int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
+                            const int32_t* idx, const float* rho, void* C, grass_dtype odt,
+                            int64_t ldc, void* ws, hipStream_t s);
+
+}  // namespace grass

@@ -1,0 +1,428 @@
+// grass_select_rows: compute_P of Section 3.2 on the device.
+//
+// The work is O(m) integer operations on a few thousand row statistics, so it is latency
+// bound, not bandwidth bound: one workgroup of 1024 threads (16 wavefronts) runs the whole
+// rule, using LDS histograms, wavefront scans and ballots.  No host round trip: idx and
+// rho stay on the device for the calls that follow.
+//
+//   Top-r           4-pass radix select (8 bits per pass, LDS histogram) on the bit
+//                   patterns of sumsq, then an order-preserving compaction by block scan.
+//   with repl.      fixed-point weights -> 64-bit inclusive prefix sums in the workspace;
+//                   the r draws are independent: Philox word, 64x64 high multiply, binary
+//                   search; a per-row hit counter plus a scan emits idx sorted.
+//   without repl.   draws are sequential by definition.  A radix-64 sum tree over the
+//                   weights (in LDS when it fits in 144 KiB, else in the workspace) lets
+//                   one wavefront do a draw in log64(m) steps: 64 children per load, a
+//                   wavefront scan and a ballot pick the child; the path is then
+//                   decremented.  Chosen leaves have weight 0; a scan compacts them.
+//
+// Selection arithmetic is integer (or correctly rounded IEEE double sqrt / divide) so
+// that the indices are reproducible bit for bit.
+#include "common.hpp"
+
+namespace grass {
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / kWave;
+constexpr size_t kHeaderBytes = 256;       // status word + padding
+constexpr size_t kLdsTreeBytes = 144 * 1024;
+constexpr int kMaxLevels = 6;              // 64^6 > 2^31 rows
+
+struct Shared {
+    uint32_t hist[256];
+    unsigned long long scan_tot[kWaves];
+    double red[kWaves];
+    unsigned long long bcast64;
+    uint32_t prefix;
+    uint32_t need;
+    int bad;
+    long long level_offset[kMaxLevels];  // sum-tree geometry (sampling without replacement)
+    long long level_count[kMaxLevels];
+};
+
+__device__ __forceinline__ uint32_t key_of(float s) { return s == 0.0f ? 0u : __float_as_uint(s); }
+__device__ __forceinline__ bool is_bad(float s) { return !(s >= 0.0f) || isinf(s); }
+
+// Philox4x32-10 (Salmon et al., SC'11): counter = (j, refresh_id), key = seed.
+__device__ __forceinline__ unsigned long long draw_word(unsigned long long seed,
+                                                        unsigned long long refresh,
+                                                        unsigned long long j) {
+    uint32_t c0 = static_cast<uint32_t>(j), c1 = static_cast<uint32_t>(j >> 32);
+    uint32_t c2 = static_cast<uint32_t>(refresh), c3 = static_cast<uint32_t>(refresh >> 32);
+    uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+        c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return static_cast<unsigned long long>(c0) | (static_cast<unsigned long long>(c1) << 32);
+}
+
+__device__ __forceinline__ double weight_of(float s, int method) {
+    const double d = static_cast<double>(s);
+    return method == GRASS_SEL_UNIFORM ? 1.0 : (method == GRASS_SEL_MULTI_NORM ? sqrt(d) : d);
+}
+__device__ __forceinline__ unsigned long long quantise(double w, double wmax) {
+    if (wmax == 0.0) return 1ull;
+    return static_cast<unsigned long long>(floor(w / wmax * 1099511627776.0)) + 1ull;
+}
+
+// Exclusive prefix sum of one value per thread across the workgroup; `total` is the sum.
+// Two barriers; `sh->scan_tot` is reused by every call.
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan(T v, Shared* sh, T& total) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const T incl = wave_inclusive_scan(v);
+    __syncthreads();  // previous users of scan_tot are done
+    if (lane == kWave - 1) sh->scan_tot[wave] = static_cast<unsigned long long>(incl);
+    __syncthreads();
+    T before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const T t = static_cast<T>(sh->scan_tot[w]);
+        if (w < wave) before += t;
+        all += t;
+    }
+    total = all;
+    return before + incl - v;
+}
+
+__device__ __forceinline__ double block_max(double v, Shared* sh) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) sh->red[wave] = v;
+    __syncthreads();
+    double r = sh->red[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r = sh->red[w] > r ? sh->red[w] : r;
+    return r;
+}
+
+// Common prologue: reject NaN / Inf / negative statistics.  Returns true (for every
+// thread) when the input is bad, after writing the placeholder selection.
+__device__ bool reject_nonfinite(const float* sumsq, int64_t m, int64_t r, int32_t* idx,
+                                 float* rho, int32_t* status, Shared* sh) {
+    if (threadIdx.x == 0) sh->bad = 0;
+    __syncthreads();
+    bool bad = false;
+    for (int64_t k = threadIdx.x; k < m; k += kThreads) bad |= is_bad(sumsq[k]);
+    if (bad) sh->bad = 1;
+    __syncthreads();
+    if (!sh->bad) {
+        if (threadIdx.x == 0) *status = GRASS_OK;
+        return false;
+    }
+    if (threadIdx.x == 0) *status = GRASS_ERR_NONFINITE;
+    for (int64_t j = threadIdx.x; j < r; j += kThreads) {
+        idx[j] = static_cast<int32_t>((j * m) / r);  // ascending and inside [0, m)
+        rho[j] = 1.0f;
+    }
+    return true;
+}
+
+// ------------------------------------------------------------------------------ Top-r
+__global__ __launch_bounds__(kThreads) void select_topr_kernel(
+    const float* __restrict__ sumsq, int64_t m, int64_t r, int32_t* __restrict__ idx,
+    float* __restrict__ rho, int32_t* __restrict__ status) {
+    __shared__ Shared sh;
+    if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    const int tid = threadIdx.x;
+
+    // Radix select: after the four passes `prefix` is the r-th largest key and `need`
+    // how many rows carrying exactly that key are still wanted.
+    uint32_t prefix = 0, need = static_cast<uint32_t>(r);
+    for (int pass = 3; pass >= 0; --pass) {
+        const int shift = pass * 8;
+        if (tid < 256) sh.hist[tid] = 0;
+        __syncthreads();
+        for (int64_t k = tid; k < m; k += kThreads) {
+            const uint32_t key = key_of(sumsq[k]);
+            const bool match = pass == 3 || (key >> (shift + 8)) == (prefix >> (shift + 8));
+            if (match) atomicAdd(&sh.hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < kWave) {
+            // lane L owns digits 255-4L .. 252-4L (descending); find the digit at which the
+            // count of rows with a larger digit first reaches `need`
+            uint32_t h[4], s = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { h[e] = sh.hist[255 - 4 * tid - e]; s += h[e]; }
+            const uint32_t incl = wave_inclusive_scan(s);
+            uint32_t above = incl - s;
+            if (above < need && need <= incl) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (need <= above + h[e]) {
+                        sh.prefix = prefix | (static_cast<uint32_t>(255 - 4 * tid - e) << shift);
+                        sh.need = need - above;
+                        break;
+                    }
+                    above += h[e];
+                }
+            }
+        }
+        __syncthreads();
+        prefix = sh.prefix;
+        need = sh.need;
+    }
+
+    // Compaction in row order: every key above the threshold, and the first `need` rows
+    // that equal it (ties go to the lower index).
+    unsigned long long carry = 0;  // low 32 bits: rows above so far; high: rows equal so far
+    for (int64_t base = 0; base < m; base += kThreads) {
+        const int64_t k = base + tid;
+        bool gt = false, eq = false;
+        if (k < m) {
+            const uint32_t key = key_of(sumsq[k]);
+            gt = key > prefix;
+            eq = key == prefix;
+        }
+        const unsigned long long mine = (gt ? 1ull : 0ull) | (eq ? (1ull << 32) : 0ull);
+        unsigned long long total;
+        const unsigned long long before = carry + block_exclusive_scan(mine, &sh, total);
+        const uint32_t gt_before = static_cast<uint32_t>(before);
+        const uint32_t eq_before = static_cast<uint32_t>(before >> 32);
+        if (gt || (eq && eq_before < need)) {
+            const uint32_t pos = gt_before + (eq_before < need ? eq_before : need);
+            idx[pos] = static_cast<int32_t>(k);
+            rho[pos] = 1.0f;
+        }
+        carry += total;
+    }
+}
+
+// ------------------------------------------------------------------------------ with replacement
+__global__ __launch_bounds__(kThreads) void select_repl_kernel(
+    const float* __restrict__ sumsq, int64_t m, int64_t r, int method, int rescale,
+    unsigned long long seed, unsigned long long refresh, int32_t* __restrict__ idx,
+    float* __restrict__ rho, int32_t* __restrict__ status, unsigned long long* __restrict__ csum,
+    uint32_t* __restrict__ hits) {
+    __shared__ Shared sh;
+    if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    const int tid = threadIdx.x;
+
+    double wmax = 0.0;
+    for (int64_t k = tid; k < m; k += kThreads) {
+        const double w = weight_of(sumsq[k], method);
+        wmax = w > wmax ? w : wmax;
+    }
+    wmax = block_max(wmax, &sh);
+
+    // inclusive prefix sums of the integer weights
+    unsigned long long carry = 0;
+    for (int64_t base = 0; base < m; base += kThreads) {
+        const int64_t k = base + tid;
+        const unsigned long long wq = k < m ? quantise(weight_of(sumsq[k], method), wmax) : 0ull;
+        unsigned long long total;
+        const unsigned long long before = block_exclusive_scan(wq, &sh, total);
+        if (k < m) {
+            csum[k] = carry + before + wq;
+            hits[k] = 0;
+        }
+        carry += total;
+    }
+    const unsigned long long total_w = carry;
+    __threadfence_block();
+    __syncthreads();
+
+    // independent draws: first k with csum[k] > target
+    for (int64_t j = tid; j < r; j += kThreads) {
+        const unsigned long long target = __umul64hi(draw_word(seed, refresh, j), total_w);
+        int64_t lo = 0, hi = m - 1;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (csum[mid] > target) hi = mid; else lo = mid + 1;
+        }
+        atomicAdd(&hits[lo], 1u);
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // emit rows in ascending order, each as often as it was hit
+    uint32_t out_carry = 0;
+    for (int64_t base = 0; base < m; base += kThreads) {
+        const int64_t k = base + tid;
+        const uint32_t h = k < m ? hits[k] : 0u;
+        uint32_t total;
+        const uint32_t pos = out_carry + block_exclusive_scan(h, &sh, total);
+        if (h) {
+            float rk = 1.0f;
+            if (rescale) {
+                const unsigned long long wq = csum[k] - (k ? csum[k - 1] : 0ull);
+                const double q = static_cast<double>(wq) / static_cast<double>(total_w);
+                rk = static_cast<float>(1.0 / sqrt(static_cast<double>(r) * q));
+            }
+            for (uint32_t e = 0; e < h; ++e) {
+                idx[pos + e] = static_cast<int32_t>(k);
+                rho[pos + e] = rk;
+            }
+        }
+        out_carry += total;
+    }
+}
+
+// ------------------------------------------------------------------------------ without replacement
+struct TreeShape {
+    int levels;                 // level 0 = leaves
+    int64_t count[kMaxLevels];  // nodes per level
+    int64_t offset[kMaxLevels]; // start of the level inside the node array
+};
+
+__global__ __launch_bounds__(kThreads) void select_norepl_kernel(
+    const float* __restrict__ sumsq, int64_t m, int64_t r, int method, int rescale,
+    unsigned long long seed, unsigned long long refresh, int32_t* __restrict__ idx,
+    float* __restrict__ rho, int32_t* __restrict__ status, unsigned long long* ws_tree,
+    TreeShape shape, int tree_in_lds) {
+    __shared__ Shared sh;
+    extern __shared__ unsigned long long lds_tree[];
+    if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    unsigned long long* tree = tree_in_lds ? lds_tree : ws_tree;
+    if (tid < kMaxLevels) {
+        sh.level_offset[tid] = tid < shape.levels ? shape.offset[tid] : 0;
+        sh.level_count[tid] = tid < shape.levels ? shape.count[tid] : 0;
+    }
+
+    double wmax = 0.0;
+    for (int64_t k = tid; k < m; k += kThreads) {
+        const double w = weight_of(sumsq[k], method);
+        wmax = w > wmax ? w : wmax;
+    }
+    wmax = block_max(wmax, &sh);
+
+    for (int64_t k = tid; k < m; k += kThreads) tree[k] = quantise(weight_of(sumsq[k], method), wmax);
+    __threadfence_block();
+    __syncthreads();
+    // inner levels: one wavefront sums the 64 children of a node
+    for (int L = 1; L < shape.levels; ++L) {
+        const unsigned long long* child = tree + shape.offset[L - 1];
+        for (int64_t node = wave; node < shape.count[L]; node += kWaves) {
+            const int64_t c = node * kWave + lane;
+            unsigned long long v = c < shape.count[L - 1] ? child[c] : 0ull;
+#pragma unroll
+            for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+            if (lane == 0) tree[shape.offset[L] + node] = v;
+        }
+        __threadfence_block();
+        __syncthreads();
+    }
+    // total weight = sum of the (at most 64) top-level nodes
+    const int top = shape.levels - 1;
+    unsigned long long total_w = 0;
+    for (int64_t i = 0; i < shape.count[top]; ++i) total_w += tree[shape.offset[top] + i];
+
+    if (wave == 0) {
+        unsigned long long remaining = total_w;
+        for (int64_t j = 0; j < r; ++j) {
+            unsigned long long target = __umul64hi(draw_word(seed, refresh, j), remaining);
+            int64_t node = 0;
+            for (int L = top; L >= 0; --L) {
+                const int64_t c = node * kWave + lane;  // node = 0 at the top level
+                const unsigned long long v = c < shape.count[L] ? tree[shape.offset[L] + c] : 0ull;
+                const unsigned long long incl = wave_inclusive_scan(v);
+                const unsigned long long hit = __ballot(incl > target);
+                const int f = __ffsll(static_cast<long long>(hit)) - 1;  // hit != 0: target < sum
+                target -= __shfl(incl - v, f, kWave);
+                node = node * kWave + f;
+            }
+            const unsigned long long w = tree[node];  // the leaf drawn
+            if (lane <= top) tree[sh.level_offset[lane] + (node >> (6 * lane))] -= w;
+            remaining -= w;
+            __threadfence_block();
+        }
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // chosen leaves now weigh 0 (every weight started >= 1): compact them in row order
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < m; base += kThreads) {
+        const int64_t k = base + tid;
+        const uint32_t chosen = (k < m && tree[k] == 0ull) ? 1u : 0u;
+        uint32_t total;
+        const uint32_t pos = carry + block_exclusive_scan(chosen, &sh, total);
+        if (chosen) {
+            float rk = 1.0f;
+            if (rescale) {
+                const unsigned long long wq = quantise(weight_of(sumsq[k], method), wmax);
+                const double q = static_cast<double>(wq) / static_cast<double>(total_w);
+                rk = static_cast<float>(1.0 / sqrt(static_cast<double>(r) * q));
+            }
+            idx[pos] = static_cast<int32_t>(k);
+            rho[pos] = rk;
+        }
+        carry += total;
+    }
+}
+
+TreeShape tree_shape(int64_t m) {
+    TreeShape s;
+    s.levels = 0;
+    int64_t cnt = m > 0 ? m : 1, off = 0;
+    while (true) {
+        s.count[s.levels] = cnt;
+        s.offset[s.levels] = off;
+        ++s.levels;
+        if (cnt <= kWave || s.levels == kMaxLevels) break;
+        off += cnt;
+        cnt = (cnt + kWave - 1) / kWave;
+    }
+    return s;
+}
+
+size_t tree_bytes(const TreeShape& s) {
+    return static_cast<size_t>(s.offset[s.levels - 1] + s.count[s.levels - 1]) * sizeof(unsigned long long);
+}
+
+}  // namespace
+
+size_t select_workspace_bytes(int64_t m, int64_t r, grass_method method, int replacement) {
+    (void)r;
+    if (m < 0) m = 0;
+    if (method == GRASS_SEL_TOPR) return kHeaderBytes;
+    if (replacement) return kHeaderBytes + static_cast<size_t>(m) * 8 + static_cast<size_t>(m) * 4;
+    return kHeaderBytes + tree_bytes(tree_shape(m));
+}
+
+grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                           int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
+                           int32_t* idx, float* rho, void* ws, hipStream_t s) {
+    int32_t* status = static_cast<int32_t*>(ws);
+    char* body = static_cast<char*>(ws) + kHeaderBytes;
+    if (method == GRASS_SEL_TOPR) {
+        select_topr_kernel<<<1, kThreads, 0, s>>>(sumsq, m, r, idx, rho, status);
+        return launch_status();
+    }
+    const int rescale =
+        scale == GRASS_SCALE_INV_SQRT_RQ || (scale == GRASS_SCALE_PAPER && replacement);
+    if (replacement) {
+        unsigned long long* csum = reinterpret_cast<unsigned long long*>(body);
+        uint32_t* hits = reinterpret_cast<uint32_t*>(body + static_cast<size_t>(m) * 8);
+        select_repl_kernel<<<1, kThreads, 0, s>>>(sumsq, m, r, method, rescale, seed, refresh_id,
+                                                  idx, rho, status, csum, hits);
+        return launch_status();
+    }
+    const TreeShape shape = tree_shape(m);
+    const size_t bytes = tree_bytes(shape);
+    const int in_lds = bytes <= kLdsTreeBytes;
+    const size_t dyn = in_lds ? bytes : 0;
+    if (dyn > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_norepl_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(dyn)) != hipSuccess)
+            return GRASS_ERR_DEVICE;
+    }
+    select_norepl_kernel<<<1, kThreads, dyn, s>>>(sumsq, m, r, method, rescale, seed, refresh_id,
+                                                  idx, rho, status,
+                                                  reinterpret_cast<unsigned long long*>(body),
+                                                  shape, in_lds);
+    return launch_status();
+}
+
+}  // namespace grass

@@ -1,0 +1,230 @@
+"""ctypes binding of libgrass.so (the C ABI of include/grass.h).
+
+Argument marshalling only: every step of the method runs in the HIP kernels.  Tensors
+are torch CUDA tensors (torch is used for device memory and streams, nothing else); each
+function takes the same arguments as the C call of the same name, with pointers and
+leading dimensions taken from the tensors and the stream taken from torch's current
+stream.  A missing library is an error: there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import torch  # imported before the library is loaded so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgrass.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_WORKSPACE, ERR_NONFINITE, ERR_DEVICE = range(7)
+F32, BF16 = 0, 1
+SEL_TOPR, SEL_UNIFORM, SEL_MULTI_NORM, SEL_MULTI_NORM2 = 0, 1, 2, 3
+SCALE_PAPER, SCALE_ONE, SCALE_INV_SQRT_RQ = 0, 1, 2
+DY_TxM, DY_MxT = 0, 1
+
+EXPORTS = [
+    "grass_status_string", "grass_row_stats", "grass_select_workspace", "grass_select_rows",
+    "grass_cgrad_workspace", "grass_compressed_grad", "grass_adam_rows", "grass_scatter_update",
+    "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
+]
+
+_lib = None
+
+
+class GrassError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+        self.code = code
+
+
+def lib():
+    """Load libgrass.so (built by paper_2406_17660_amd/build.py); raise if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2406_17660_amd.build` "
+            "(hipcc, gfx950).  There is no fallback implementation.")
+    L = C.CDLL(LIB_PATH)
+    i64, vp, i32, f32, u64, sz = C.c_int64, C.c_void_p, C.c_int, C.c_float, C.c_uint64, C.c_size_t
+    L.grass_status_string.argtypes = [i32]
+    L.grass_status_string.restype = C.c_char_p
+    L.grass_row_stats.argtypes = [vp, i32, i64, i64, i64, vp, vp]
+    L.grass_select_workspace.argtypes = [i64, i64, i32, i32]
+    L.grass_select_workspace.restype = sz
+    L.grass_select_rows.argtypes = [vp, i64, i64, i32, i32, i32, u64, u64, vp, vp, vp, sz, vp]
+    L.grass_cgrad_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
+    L.grass_cgrad_workspace.restype = sz
+    L.grass_compressed_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, i64, vp, vp,
+                                        vp, i64, vp, sz, vp]
+    L.grass_adam_rows.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, vp]
+    L.grass_scatter_update.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, i64, vp]
+    L.grass_adam_scatter.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, i32,
+                                     i64, i64, vp, vp, f32, vp]
+    L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
+    L.grass_dense_workspace.restype = sz
+    L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
+                                   sz, vp]
+    L.grass_gather_rows.argtypes = [vp, i32, i64, i64, i64, vp, vp, i64, vp, i64, vp]
+    for name in EXPORTS:
+        if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
+                        "grass_dense_workspace"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def status_string(code: int) -> str:
+    return lib().grass_status_string(int(code)).decode()
+
+
+def _check(code, where):
+    if code != OK:
+        raise GrassError(code, where)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _mat(t: torch.Tensor):
+    """(pointer, rows, cols, leading dimension) of a row-major 2-D device tensor."""
+    assert t.is_cuda and t.dim() == 2, "2-D CUDA tensor expected"
+    rows, cols = t.shape
+    if rows > 1 and cols > 0:
+        assert cols == 1 or t.stride(1) == 1, "rows must be contiguous"
+        ld = t.stride(0)
+    else:
+        ld = max(cols, 1) if t.stride(0) < cols else t.stride(0)
+    return C.c_void_p(t.data_ptr()), rows, cols, ld
+
+
+def _vec(t: torch.Tensor, dtype):
+    assert t.is_cuda and t.dim() == 1 and t.dtype == dtype and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    assert ws.is_cuda and ws.is_contiguous()
+    return C.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def row_stats(G: torch.Tensor, sumsq: torch.Tensor):
+    p, m, n, ld = _mat(G)
+    assert sumsq.shape == (m,)
+    _check(lib().grass_row_stats(p, _dtype(G), m, n, ld, _vec(sumsq, torch.float32), _stream()),
+           "grass_row_stats")
+    return sumsq
+
+
+def select_workspace(m, r, method, replacement) -> int:
+    return int(lib().grass_select_workspace(m, r, method, int(bool(replacement))))
+
+
+def select_rows(sumsq, r, method, replacement, scale, seed, refresh_id, idx, rho, ws):
+    m = sumsq.shape[0]
+    assert idx.shape == (r,) and rho.shape == (r,)
+    wp, wb = _ws(ws)
+    _check(lib().grass_select_rows(_vec(sumsq, torch.float32), m, r, method,
+                                   int(bool(replacement)), scale, seed, refresh_id,
+                                   _vec(idx, torch.int32), _vec(rho, torch.float32), wp, wb,
+                                   _stream()), "grass_select_rows")
+    return idx, rho
+
+
+def select_status(ws) -> int:
+    """Device status word of the last grass_select_rows that used `ws` (synchronises)."""
+    return int(ws.view(torch.uint8)[:4].view(torch.int32).item())
+
+
+def cgrad_workspace(T, m, n, r, dtype, layout=DY_TxM) -> int:
+    return int(lib().grass_cgrad_workspace(T, m, n, r, dtype, layout))
+
+
+def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM):
+    pY, ry, cy, ldy = _mat(dY)
+    pX, T, n, ldx = _mat(X)
+    m = cy if layout == DY_TxM else ry
+    assert (ry if layout == DY_TxM else cy) == T and dY.dtype == X.dtype
+    r = idx.shape[0]
+    pG, gr, gc, ldgc = _mat(GC)
+    assert (gr, gc) == (r, n) and GC.dtype == torch.float32
+    wp, wb = _ws(ws)
+    _check(lib().grass_compressed_grad(pY, layout, ldy, pX, ldx, _dtype(X), T, m, n, r,
+                                       _vec(idx, torch.int32), _vec(rho, torch.float32), pG, ldgc,
+                                       wp, wb, _stream()), "grass_compressed_grad")
+    return GC
+
+
+def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, U):
+    pG, r, n, ldgc = _mat(GC)
+    for a in (M, V, U):
+        assert a.shape == (r, n) and a.is_contiguous() and a.dtype == torch.float32 and a.is_cuda
+    _check(lib().grass_adam_rows(pG, ldgc, C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()), r,
+                                 n, lr, beta1, beta2, eps, t, C.c_void_p(U.data_ptr()), _stream()),
+           "grass_adam_rows")
+    return U
+
+
+def scatter_update(W, idx, rho, alpha, U):
+    pW, m, n, ldw = _mat(W)
+    r = idx.shape[0]
+    assert U.shape == (r, n) and U.is_contiguous() and U.dtype == torch.float32
+    _check(lib().grass_scatter_update(pW, _dtype(W), m, n, ldw, _vec(idx, torch.int32),
+                                      _vec(rho, torch.float32), alpha, C.c_void_p(U.data_ptr()), r,
+                                      _stream()), "grass_scatter_update")
+    return W
+
+
+def adam_scatter(GC, M, V, lr, beta1, beta2, eps, t, W, idx, rho, alpha):
+    pG, r, n, ldgc = _mat(GC)
+    pW, m, nw, ldw = _mat(W)
+    assert nw == n and idx.shape == (r,)
+    for a in (M, V):
+        assert a.shape == (r, n) and a.is_contiguous() and a.dtype == torch.float32 and a.is_cuda
+    _check(lib().grass_adam_scatter(pG, ldgc, C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()),
+                                    r, n, lr, beta1, beta2, eps, t, pW, _dtype(W), m, ldw,
+                                    _vec(idx, torch.int32), _vec(rho, torch.float32), alpha,
+                                    _stream()), "grass_adam_scatter")
+    return W
+
+
+def dense_workspace(T, m, n, dtype, layout=DY_TxM) -> int:
+    return int(lib().grass_dense_workspace(T, m, n, dtype, layout))
+
+
+def dense_grad(dY, X, G, ws, layout=DY_TxM):
+    pY, ry, cy, ldy = _mat(dY)
+    pX, T, n, ldx = _mat(X)
+    m = cy if layout == DY_TxM else ry
+    pG, gr, gc, ldg = _mat(G)
+    assert (gr, gc) == (m, n) and dY.dtype == X.dtype
+    wp, wb = _ws(ws)
+    _check(lib().grass_dense_grad(pY, layout, ldy, pX, ldx, _dtype(X), T, m, n, pG, _dtype(G),
+                                  ldg, wp, wb, _stream()), "grass_dense_grad")
+    return G
+
+
+def gather_rows(G, idx, rho, out):
+    pG, m, n, ldg = _mat(G)
+    r = idx.shape[0]
+    pO, orr, oc, ldo = _mat(out)
+    assert (orr, oc) == (r, n) and out.dtype == torch.float32
+    _check(lib().grass_gather_rows(pG, _dtype(G), m, n, ldg, _vec(idx, torch.int32),
+                                   _vec(rho, torch.float32), r, pO, ldo, _stream()),
+           "grass_gather_rows")
+    return out
+
+
+def workspace(nbytes: int, device="cuda"):
+    """A device byte buffer of at least `nbytes` (torch owns the memory)."""
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)

@@ -1,0 +1,133 @@
+"""The C-ABI library loads, exports every function include/grass.h declares, and rejects
+bad arguments on the host before anything is launched (CPU only: no call here reaches a
+kernel launch)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2406_17660_amd import grass
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(0x1000)  # never dereferenced: validation fails first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "grass.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(grass_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    names = declared_functions()
+    assert len(names) >= 12
+    assert sorted(grass.EXPORTS) == names
+    L = grass.lib()
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    seen = {grass.status_string(c) for c in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert grass.status_string(99) == "unknown status"
+
+
+def test_workspace_queries_are_pure_host_functions():
+    assert grass.select_workspace(4096, 1024, grass.SEL_TOPR, False) >= 4
+    a = grass.select_workspace(4096, 1024, grass.SEL_MULTI_NORM, True)
+    b = grass.select_workspace(8192, 1024, grass.SEL_MULTI_NORM, True)
+    assert b > a >= 4096 * 12
+    assert grass.select_workspace(13824, 1024, grass.SEL_MULTI_NORM, False) >= 13824 * 8
+    assert grass.cgrad_workspace(131072, 4096, 4096, 1024, grass.BF16) >= 131072 * 1024 * 2
+    assert grass.cgrad_workspace(512, 256, 256, 16, grass.F32) == 0
+    assert grass.dense_workspace(1024, 512, 512, grass.BF16) >= 512 * 512 * 4
+
+
+def test_row_stats_validation():
+    L = grass.lib()
+    assert L.grass_row_stats(None, grass.F32, 4, 4, 4, FAKE, None) == grass.ERR_NULL
+    assert L.grass_row_stats(FAKE, grass.F32, 4, 4, 4, None, None) == grass.ERR_NULL
+    assert L.grass_row_stats(FAKE, 7, 4, 4, 4, FAKE, None) == grass.ERR_DTYPE
+    assert L.grass_row_stats(FAKE, grass.F32, -1, 4, 4, FAKE, None) == grass.ERR_SHAPE
+    assert L.grass_row_stats(FAKE, grass.F32, 4, 4, 3, FAKE, None) == grass.ERR_SHAPE
+
+
+def test_select_validation():
+    L = grass.lib()
+    f = L.grass_select_rows
+    ok_ws = 1 << 20
+    assert f(None, 8, 2, 0, 0, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_NULL
+    assert f(FAKE, 8, 2, 9, 0, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_DTYPE
+    assert f(FAKE, 8, 2, 0, 0, 5, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_DTYPE
+    # forced 1/sqrt(r q) makes no sense for Top-r
+    assert f(FAKE, 8, 2, grass.SEL_TOPR, 0, grass.SCALE_INV_SQRT_RQ, 0, 0, FAKE, FAKE, FAKE, ok_ws,
+             None) == grass.ERR_DTYPE
+    assert f(FAKE, 8, 9, grass.SEL_TOPR, 0, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_SHAPE
+    assert f(FAKE, 8, 9, grass.SEL_UNIFORM, 0, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_SHAPE
+    assert f(FAKE, 0, 1, grass.SEL_UNIFORM, 1, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_SHAPE
+    assert f(FAKE, 8, -1, 0, 0, 0, 0, 0, FAKE, FAKE, FAKE, ok_ws, None) == grass.ERR_SHAPE
+    assert f(FAKE, 8, 2, grass.SEL_MULTI_NORM, 1, 0, 0, 0, FAKE, FAKE, None, ok_ws, None) == grass.ERR_WORKSPACE
+    assert f(FAKE, 8, 2, grass.SEL_MULTI_NORM, 1, 0, 0, 0, FAKE, FAKE, FAKE, 8, None) == grass.ERR_WORKSPACE
+
+
+def test_compressed_grad_validation():
+    L = grass.lib()
+    f = L.grass_compressed_grad
+    big = 1 << 40
+    args = dict(dY=FAKE, layout=0, ldy=64, X=FAKE, ldx=32, dt=grass.BF16, T=128, m=64, n=32, r=8,
+                idx=FAKE, rho=FAKE, GC=FAKE, ldgc=32, ws=FAKE, wsb=big, stream=None)
+
+    def call(**kw):
+        a = dict(args, **kw)
+        return f(a["dY"], a["layout"], a["ldy"], a["X"], a["ldx"], a["dt"], a["T"], a["m"], a["n"],
+                 a["r"], a["idx"], a["rho"], a["GC"], a["ldgc"], a["ws"], a["wsb"], a["stream"])
+
+    assert call(dY=None) == grass.ERR_NULL
+    assert call(idx=None) == grass.ERR_NULL
+    assert call(GC=None) == grass.ERR_NULL
+    assert call(dt=5) == grass.ERR_DTYPE
+    assert call(layout=3) == grass.ERR_DTYPE
+    assert call(ldx=31) == grass.ERR_SHAPE
+    assert call(ldy=63) == grass.ERR_SHAPE
+    assert call(layout=1, ldy=127) == grass.ERR_SHAPE  # m x T storage needs ldy >= T
+    assert call(ldgc=31) == grass.ERR_SHAPE
+    assert call(T=-1) == grass.ERR_SHAPE
+    assert call(ws=None) == grass.ERR_WORKSPACE
+    assert call(wsb=1024) == grass.ERR_WORKSPACE
+
+
+def test_adam_and_scatter_validation():
+    L = grass.lib()
+    a = L.grass_adam_rows
+    assert a(None, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, None) == grass.ERR_NULL
+    assert a(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None, None) == grass.ERR_NULL
+    assert a(FAKE, 7, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, None) == grass.ERR_SHAPE
+    assert a(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 0, FAKE, None) == grass.ERR_SHAPE
+    assert a(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 1.0, 0.999, 1e-8, 1, FAKE, None) == grass.ERR_SHAPE
+    assert a(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, -0.1, 1e-8, 1, FAKE, None) == grass.ERR_SHAPE
+    s = L.grass_scatter_update
+    assert s(None, 0, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_NULL
+    assert s(FAKE, 3, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_DTYPE
+    assert s(FAKE, 0, 4, 8, 7, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_SHAPE
+    assert s(FAKE, 0, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 70000, None) == grass.ERR_SHAPE
+    f = L.grass_adam_scatter
+    assert f(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None, 0, 4, 8, FAKE, FAKE, 1.0,
+             None) == grass.ERR_NULL
+    assert f(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 0, FAKE, 0, 4, 8, FAKE, FAKE, 1.0,
+             None) == grass.ERR_SHAPE
+    d = L.grass_dense_grad
+    assert d(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, None, 0, 32, FAKE, 1 << 40, None) == grass.ERR_NULL
+    assert d(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, 4, 32, FAKE, 1 << 40, None) == grass.ERR_DTYPE
+    assert d(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, 0, 32, FAKE, 16, None) == grass.ERR_WORKSPACE
+    g = L.grass_gather_rows
+    assert g(FAKE, 0, 4, 8, 8, None, FAKE, 2, FAKE, 8, None) == grass.ERR_NULL
+    assert g(FAKE, 0, 4, 8, 8, FAKE, FAKE, 2, FAKE, 7, None) == grass.ERR_SHAPE
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    monkeypatch.setattr(grass, "_lib", None)
+    monkeypatch.setattr(grass, "LIB_PATH", "/nonexistent/libgrass.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        grass.lib()

@@ -1,0 +1,289 @@
+"""GPU parity: every C-ABI entry point against the fp64 CPU oracle on the same seeded inputs.
+
+Bars: selected indices bit-exact; floating-point results within a relative Frobenius error
+of 1e-5 (fp32 inputs) / 1e-2 (bf16 inputs), with tighter elementwise checks where the
+arithmetic allows them.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2406_17660_amd import grass, workloads
+from gpu_util import (DEV, TOL_BF16, TOL_F32, bf16_ulp, gpu_cgrad, gpu_dense, gpu_select, rel_fro,
+                      to_f64, to_np, tol_for)
+
+pytestmark = pytest.mark.gpu
+
+LR, B1, B2, EPS = 1e-3, 0.9, 0.999, 1e-8
+
+
+def randn(shape, dtype, seed, scale=1.0, ld=None):
+    """Seeded N(0, scale^2) device tensor; with ld > cols it is a view into a wider buffer."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    rows, cols = shape
+    ld = cols if ld is None else ld
+    buf = (torch.randn((rows, ld), generator=g, device=DEV) * scale).to(dtype)
+    return buf[:, :cols] if ld != cols else buf
+
+
+# ------------------------------------------------------------------------------ row stats
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("m,n,ld", [(1, 1, 1), (5, 7, 7), (256, 256, 256), (300, 1000, 1024),
+                                    (64, 333, 333), (1376, 512, 512), (33, 4099, 4104),
+                                    (7, 0, 4), (3, 5461, 5461)])
+def test_row_stats(dtype, m, n, ld):
+    G = randn((m, n), dtype, 100 + m + n, ld=ld)
+    out = torch.full((m,), float("nan"), dtype=torch.float32, device=DEV)
+    grass.row_stats(G, out)
+    want = ref.row_stats(to_np(G)) if n > 0 else np.zeros(m)
+    got = to_f64(out)
+    assert rel_fro(got, want) <= TOL_F32  # fp32 accumulation of exactly widened inputs
+    np.testing.assert_allclose(got, want, rtol=2e-6, atol=0)
+
+
+def test_row_stats_empty():
+    G = torch.zeros((0, 8), device=DEV)
+    out = torch.zeros((0,), device=DEV)
+    grass.row_stats(G, out)
+
+
+# ------------------------------------------------------------------------------ selection
+METHODS = [(grass.SEL_TOPR, False), (grass.SEL_UNIFORM, True), (grass.SEL_UNIFORM, False),
+           (grass.SEL_MULTI_NORM, True), (grass.SEL_MULTI_NORM, False),
+           (grass.SEL_MULTI_NORM2, True), (grass.SEL_MULTI_NORM2, False)]
+
+
+def sumsq_case(m, kind, seed):
+    rng = np.random.default_rng(seed)
+    if kind == "chi2":
+        s = rng.standard_normal(m) ** 2 * 100
+    elif kind == "lognormal":
+        s = np.exp(2 * rng.standard_normal(m))
+    elif kind == "ties":
+        s = rng.integers(0, 4, m).astype(np.float64)  # many equal values and zeros
+    elif kind == "zeros":
+        s = np.zeros(m)
+    elif kind == "tiny":
+        s = rng.standard_normal(m) ** 2 * 1e-40  # denormals
+    else:
+        raise ValueError(kind)
+    return s.astype(np.float32)
+
+
+@pytest.mark.parametrize("method,replacement", METHODS)
+@pytest.mark.parametrize("m,r,kind", [(1, 1, "chi2"), (5, 3, "chi2"), (64, 64, "lognormal"),
+                                      (65, 17, "ties"), (1000, 128, "chi2"), (1000, 999, "ties"),
+                                      (4097, 1024, "lognormal"), (512, 128, "zeros"),
+                                      (300, 100, "tiny"), (13824, 1024, "chi2")])
+def test_select_rows_bit_exact(method, replacement, m, r, kind):
+    ss = sumsq_case(m, kind, 7 * m + r)
+    d_ss = torch.from_numpy(ss).to(DEV)
+    for seed, refresh in [(0, 0), (0x9E3779B97F4A7C15, 12345678901)]:
+        idx, rho, status = gpu_select(d_ss, r, method, replacement, seed=seed, refresh_id=refresh)
+        assert status == grass.OK
+        w_idx, w_rho, _ = ref.select_rows(ss, r, method, replacement, seed=seed, refresh_id=refresh)
+        assert np.array_equal(idx.cpu().numpy(), w_idx), (method, replacement, m, r, kind)
+        assert np.array_equal(rho.cpu().numpy(), w_rho)  # same IEEE double ops, one rounding
+        if method == grass.SEL_TOPR:
+            break
+
+
+@pytest.mark.parametrize("method", [grass.SEL_UNIFORM, grass.SEL_MULTI_NORM])
+@pytest.mark.parametrize("scale", [grass.SCALE_ONE, grass.SCALE_INV_SQRT_RQ])
+def test_select_forced_scale(method, scale):
+    ss = sumsq_case(777, "lognormal", 3)
+    d_ss = torch.from_numpy(ss).to(DEV)
+    for replacement in (True, False):
+        idx, rho, status = gpu_select(d_ss, 200, method, replacement, scale, seed=11, refresh_id=2)
+        w_idx, w_rho, _ = ref.select_rows(ss, 200, method, replacement, scale, seed=11, refresh_id=2)
+        assert status == grass.OK
+        assert np.array_equal(idx.cpu().numpy(), w_idx)
+        assert np.array_equal(rho.cpu().numpy(), w_rho)
+
+
+def test_select_more_draws_than_rows_with_replacement():
+    ss = sumsq_case(10, "chi2", 5)
+    idx, rho, status = gpu_select(torch.from_numpy(ss).to(DEV), 50, grass.SEL_MULTI_NORM, True, seed=4)
+    w_idx, w_rho, _ = ref.select_rows(ss, 50, grass.SEL_MULTI_NORM, True, seed=4)
+    assert status == grass.OK and np.array_equal(idx.cpu().numpy(), w_idx)
+    assert np.array_equal(rho.cpu().numpy(), w_rho)
+
+
+@pytest.mark.parametrize("m,r", [(20000, 1500), (300001, 2000)])
+def test_select_without_replacement_tree_in_global_memory(m, r):
+    """m too large for the LDS-resident sum tree: 3 and 4 level trees in the workspace."""
+    ss = sumsq_case(m, "lognormal", m)
+    idx, rho, status = gpu_select(torch.from_numpy(ss).to(DEV), r, grass.SEL_MULTI_NORM, False, seed=9)
+    w_idx, _, _ = ref.select_rows(ss, r, grass.SEL_MULTI_NORM, False, seed=9)
+    assert status == grass.OK and np.array_equal(idx.cpu().numpy(), w_idx)
+
+
+@pytest.mark.parametrize("bad", [float("nan"), float("inf"), -1.0])
+@pytest.mark.parametrize("method,replacement", [(grass.SEL_TOPR, False), (grass.SEL_MULTI_NORM, True),
+                                                (grass.SEL_MULTI_NORM, False)])
+def test_select_reports_nonfinite(bad, method, replacement):
+    ss = sumsq_case(100, "chi2", 1)
+    ss[37] = bad
+    idx, rho, status = gpu_select(torch.from_numpy(ss).to(DEV), 10, method, replacement)
+    assert status == grass.ERR_NONFINITE
+    with pytest.raises(ref.OracleError) as e:
+        ref.select_rows(ss, 10, method, replacement)
+    assert e.value.code == ref.ERR_NONFINITE
+    i = idx.cpu().numpy()
+    assert i.min() >= 0 and i.max() < 100 and (np.diff(i) >= 0).all()  # placeholder stays in bounds
+    assert (rho.cpu().numpy() == 1.0).all()
+
+
+def test_select_zero_rows():
+    ss = torch.ones(16, device=DEV)
+    idx, rho, status = gpu_select(ss, 0, grass.SEL_TOPR, False)
+    assert status == grass.OK and idx.numel() == 0
+
+
+# ------------------------------------------------------------------------------ products
+def make_idx(m, r, seed, duplicates):
+    rng = np.random.default_rng(seed)
+    if duplicates:
+        idx = np.sort(rng.integers(0, m, r))
+    else:
+        idx = np.sort(rng.choice(m, r, replace=False))
+    rho = rng.uniform(0.5, 2.0, r).astype(np.float32)
+    return idx.astype(np.int32), rho
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("layout", [grass.DY_TxM, grass.DY_MxT])
+@pytest.mark.parametrize("T,m,n,r,dup,pad", [
+    (512, 256, 256, 16, False, 0),      # the fp32 reference configuration's shape
+    (300, 200, 150, 37, True, 0),       # nothing divides a tile, duplicate rows
+    (1000, 512, 1376, 128, False, 8),   # LLaMA-60M down-projection shape, padded leading dims
+    (777, 130, 333, 129, True, 0),      # odd n: rows of X are not 16-byte aligned
+    (64, 40, 24, 40, False, 0),         # r = m
+    (4096, 300, 520, 260, False, 0),    # several K tiles per split, several tiles in both dims
+])
+def test_compressed_grad(dtype, layout, T, m, n, r, dup, pad):
+    dY = randn((T, m), dtype, 1, scale=0.1, ld=m + pad)
+    X = randn((T, n), dtype, 2, ld=n + pad)
+    idx, rho = make_idx(m, r, 3, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    GC = gpu_cgrad(dY_dev, X, d_idx, d_rho, layout)
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    got = to_f64(GC)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= tol_for(dtype)
+    # fp32 accumulation of exact products: far tighter than the bf16 contract
+    assert rel_fro(got, want) <= 2e-5
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() <= 1e-4 * scale
+
+
+def test_compressed_grad_empty_token_batch_and_empty_selection():
+    X = torch.zeros((0, 64), dtype=torch.bfloat16, device=DEV)
+    dY = torch.zeros((0, 32), dtype=torch.bfloat16, device=DEV)
+    idx = torch.tensor([1, 5], dtype=torch.int32, device=DEV)
+    rho = torch.ones(2, device=DEV)
+    assert (gpu_cgrad(dY, X, idx, rho) == 0).all()
+    X = randn((128, 64), torch.bfloat16, 1)
+    dY = randn((128, 32), torch.bfloat16, 2)
+    e = gpu_cgrad(dY, X, idx[:0], rho[:0])
+    assert e.shape == (0, 64)
+
+
+@pytest.mark.parametrize("dtype,gdtype", [(torch.float32, torch.float32),
+                                          (torch.bfloat16, torch.float32),
+                                          (torch.bfloat16, torch.bfloat16)])
+@pytest.mark.parametrize("layout", [grass.DY_TxM, grass.DY_MxT])
+@pytest.mark.parametrize("T,m,n", [(512, 256, 256), (300, 130, 150), (2048, 520, 264)])
+def test_dense_grad_and_gather(dtype, gdtype, layout, T, m, n):
+    dY = randn((T, m), dtype, 5, scale=0.1)
+    X = randn((T, n), dtype, 6)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    G = gpu_dense(dY_dev, X, gdtype, layout)
+    want = ref.full_grad(to_np(dY), to_np(X))
+    assert rel_fro(to_f64(G), want) <= (TOL_BF16 if gdtype == torch.bfloat16 else 2e-5)
+    # the naive comparator: full G, then gather and scale the selected rows
+    idx, rho = make_idx(m, min(m, 33), 8, True)
+    out = torch.empty((len(idx), n), dtype=torch.float32, device=DEV)
+    grass.gather_rows(G, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), out)
+    want_rows = to_f64(G)[idx] * rho[:, None].astype(np.float64)
+    np.testing.assert_allclose(to_f64(out), want_rows, rtol=1e-6, atol=0)
+
+
+# ------------------------------------------------------------------------------ Adam / scatter
+def adam_inputs(r, n, seed, ldgc):
+    GC = randn((r, n), torch.float32, seed, scale=3.0, ld=ldgc)
+    M = randn((r, n), torch.float32, seed + 1, scale=0.5)
+    V = randn((r, n), torch.float32, seed + 2).square_()
+    return GC, M.contiguous(), V.contiguous()
+
+
+@pytest.mark.parametrize("r,n,ldgc", [(1, 1, 1), (16, 256, 256), (37, 1376, 1376), (5, 333, 333),
+                                      (130, 1030, 1032), (8, 5461, 5461)])
+@pytest.mark.parametrize("t", [1, 7])
+def test_adam_rows(r, n, ldgc, t):
+    GC, M, V = adam_inputs(r, n, 20, ldgc)
+    if t == 1:
+        M.zero_(); V.zero_()
+    M0, V0 = to_f64(M).copy(), to_f64(V).copy()
+    U = torch.full((r, n), float("nan"), device=DEV)
+    grass.adam_rows(GC, M, V, LR, B1, B2, EPS, t, U)
+    f = np.float32
+    wU = ref.adam_rows(to_f64(GC), M0, V0, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), t)
+    assert rel_fro(to_f64(U), wU) <= TOL_F32
+    assert rel_fro(to_f64(M), M0) <= TOL_F32
+    assert rel_fro(to_f64(V), V0) <= TOL_F32
+    np.testing.assert_allclose(to_f64(U), wU, rtol=5e-6, atol=1e-6 * LR)  # atol: m can cancel
+
+
+@pytest.mark.parametrize("wdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("m,n,r,dup,ldw", [(256, 256, 16, False, 256), (200, 1376, 64, True, 1376),
+                                           (50, 333, 50, True, 333), (512, 1030, 100, True, 1040),
+                                           (9, 5461, 4, False, 5461)])
+def test_scatter_update_and_fused_adam_scatter(wdtype, m, n, r, dup, ldw):
+    idx, rho = make_idx(m, r, 31, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    alpha = 0.25
+    W = randn((m, n), wdtype, 40, scale=0.02, ld=ldw)
+    W0_bits = to_np(W).copy()
+    W0 = to_f64(W).copy()
+    GC, M, V = adam_inputs(r, n, 50, n)
+    f = np.float32
+    Mo, Vo = to_f64(M).copy(), to_f64(V).copy()
+    wU = ref.adam_rows(to_f64(GC), Mo, Vo, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 3)
+
+    # unfused: U from the GPU Adam, then scatter
+    M1, V1, W1 = M.clone(), V.clone(), W.clone()
+    U = torch.empty((r, n), device=DEV)
+    grass.adam_rows(GC, M1, V1, LR, B1, B2, EPS, 3, U)
+    grass.scatter_update(W1, d_idx, d_rho, alpha, U)
+    # fused
+    M2, V2, W2 = M.clone(), V.clone(), W.clone()
+    grass.adam_scatter(GC, M2, V2, LR, B1, B2, EPS, 3, W2, d_idx, d_rho, alpha)
+
+    Wo = W0.copy()
+    ref.scatter_update(Wo, idx, rho, float(f(alpha)), wU)
+    sel = np.unique(idx)
+    rest = np.setdiff1d(np.arange(m), sel)
+    for Wg, Mg, Vg in ((W1, M1, V1), (W2, M2, V2)):
+        got = to_f64(Wg)
+        assert rel_fro(got[sel], Wo[sel]) <= tol_for(wdtype)
+        # the update itself (W's old value dominates the metric above)
+        delta_tol = TOL_F32 if wdtype == torch.float32 else None
+        if delta_tol:
+            assert rel_fro(got[sel] - W0[sel], Wo[sel] - W0[sel]) <= 1e-4  # fp32 cancellation
+        else:
+            assert (np.abs(got[sel] - Wo[sel]) <= 1.01 * bf16_ulp(Wo[sel])).all()
+        assert np.array_equal(to_np(Wg)[rest], W0_bits[rest])  # other rows untouched, bit for bit
+        assert rel_fro(to_f64(Mg), Mo) <= TOL_F32 and rel_fro(to_f64(Vg), Vo) <= TOL_F32
+    assert torch.equal(W1, W2) and torch.equal(M1, M2) and torch.equal(V1, V2)
+
+
+def test_adam_scatter_empty():
+    W = torch.zeros((4, 8), device=DEV)
+    e = torch.zeros((0, 8), device=DEV)
+    i = torch.zeros((0,), dtype=torch.int32, device=DEV)
+    grass.adam_scatter(e, e.clone(), e.clone(), LR, B1, B2, EPS, 1, W, i, torch.zeros(0, device=DEV), 1.0)
+    assert (W == 0).all()
