@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the GRASS layer step on one MI355X.
+
+One "step" is one pass of Algorithm 1 for one linear layer over one synthetic token batch
+that is already resident in HBM: on steps with t = 0 (mod K, K = 200 as in the paper's
+pretraining runs) the refresh work (full gradient, row statistics, selection, state reset),
+and on every step the compressed gradient, Adam on r x n, and the scatter into W.  The
+timed region starts at t = 0, so it always contains exactly one refresh per 200 steps.
+
+Prints ONE JSON line (see README / DESIGN for the fields).  Only one GPU is supported.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2406_17660_amd import grass, workloads  # noqa: E402
+from paper_2406_17660_amd.layer import AdamHyper, GrassLayer  # noqa: E402
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0  # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0
+REFRESH_EVERY = 200  # the paper's K
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--config", type=int, default=5)
+    p.add_argument("--layer", type=int, default=0, help="index into the config's layer list")
+    p.add_argument("--tokens", type=int, default=None, help="override T (debug)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
+    p.add_argument("--cpu-seconds", type=float, default=15.0)
+    return p.parse_args()
+
+
+def ev():
+    e = torch.cuda.Event(enable_timing=True)
+    e.record()  # creates the handle so that the library can re-record it
+    return e
+
+
+def time_calls(fn, iters, warmup=2):
+    """Median / mean wall time of fn() in ms, measured with events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    pairs = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in pairs]
+    return float(np.median(ms)), float(np.mean(ms))
+
+
+def cpu_baseline(cfg, layer, dY, X, state, W, seconds):
+    """The fp64 oracle, untuned, on this machine's host cores: compressed gradient on a bounded
+    sample of the selected rows (scaled to all r rows) plus Adam and scatter at full size."""
+    from oracle import ref  # test infrastructure; used here only for the reported baseline
+
+    def host(t):
+        t = t.cpu()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    dYh, Xh = host(dY), host(X)
+    idx, rho = state.idx.cpu().numpy(), state.rho.cpu().numpy()
+    r = len(idx)
+    rows = min(r, cores)
+    t0 = time.perf_counter()
+    ref.compressed_grad(dYh, Xh, idx[:rows], rho[:rows])
+    t_probe = time.perf_counter() - t0
+    # grow the sample towards the time budget, in multiples of the core count
+    want = int(seconds / max(t_probe, 1e-3)) * rows
+    want = max(rows, min(r, want // cores * cores))
+    if want > rows:
+        rows = want
+        t0 = time.perf_counter()
+        ref.compressed_grad(dYh, Xh, idx[:rows], rho[:rows])
+        t_probe = time.perf_counter() - t0
+    t_cgrad_full = t_probe * r / rows
+    GC = state.GC.cpu().numpy().astype(np.float64)
+    M = np.zeros_like(GC)
+    V = np.zeros_like(GC)
+    Wd = W.cpu().to(torch.float64).numpy()
+    a = state.adam
+    t0 = time.perf_counter()
+    U = ref.adam_rows(GC, M, V, a.lr, a.beta1, a.beta2, a.eps, 1)
+    ref.scatter_update(Wd, idx, rho, state.alpha, U)
+    t_tail = time.perf_counter() - t0
+    step_s = t_cgrad_full + t_tail
+    return {"value": 1.0 / step_s, "unit": "layer-steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"regular step: compressed_grad timed on {rows} of {r} selected rows "
+                      f"(all n, all T; {t_probe:.1f} s) and scaled by {r / rows:.0f}, plus "
+                      f"adam_rows + scatter_update at full size ({t_tail:.2f} s)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures the per-layer GRASS step on ONE GPU; "
+                 "--gpus N with N > 1 is not supported (no sharding or collectives are built).")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    grass.lib()
+    cfg = workloads.CONFIGS[args.config]
+    L = cfg.layers[args.layer]
+    T = args.tokens or cfg.T
+    m, n, r = L.m, L.n, cfg.r
+    dev = "cuda"
+
+    dY = workloads.make_dY(cfg, args.layer, 0, dev, T=T)
+    X = workloads.make_X(cfg, args.layer, 0, dev, T=T)
+    W = workloads.make_W(cfg, args.layer, dev)
+    adam = AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps)
+    st = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
+                    seed=workloads.BASE_SEED)
+
+    def run(steps, gemm_events=None):
+        for t in range(steps):
+            if t % REFRESH_EVERY == 0:
+                st.refresh(dY, X, reset_state=True)
+            st.step(dY, X, W, gemm_events[t] if gemm_events else None)
+
+    st.full_gradient(dY, X)  # set-up: allocates the refresh-step buffers outside the timed region
+    run(args.warmup)
+    torch.cuda.synchronize()
+    gemm_events = [(ev(), ev()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start, t_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    t_start.record()
+    run(args.steps, gemm_events)
+    t_stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    total_ms = t_start.elapsed_time(t_stop)
+    ms_per_step = total_ms / args.steps
+    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
+    if grass.select_status(st.ws_sel) != grass.OK:
+        sys.exit("selection reported non-finite row statistics")
+
+    flops = 2.0 * r * T * n
+    gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
+    out = {
+        "metric": "GRASS layer steps/s (refresh every 200 steps included)",
+        "value": args.steps / (total_ms * 1e-3),
+        "unit": "layer-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.cid} ({cfg.name}) layer {L.name}: W {m}x{n}, "
+                               f"T={T} tokens, r={r}, {cfg.method}"
+                               f"{'' if cfg.replacement else '-NR'} selection, fp32 Adam state, "
+                               f"refresh every {REFRESH_EVERY} steps",
+                   "m": m, "n": n, "T": T, "r": r},
+        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_kernel (compressed gradient)",
+                     "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                     "flops_per_launch": flops, "avg_launch_ms": gemm_ms},
+        "host_wall_s": wall,
+    }
+
+    if not args.no_extras:
+        detail = {}
+        it = 20
+        med, _ = time_calls(lambda: st.compressed_grad(dY, X), it)
+        detail["compressed_grad_call_ms"] = med  # pack + GEMM + split-K reduce
+        detail["compressed_grad_call_tflops"] = flops / (med * 1e-3) / 1e12
+        st.adam_t = 0
+        med, _ = time_calls(lambda: st.adam_scatter(W), it)
+        esz = 2 if cfg.dtype == torch.bfloat16 else 4
+        ab = r * n * (4 + 16 + 2 * esz)
+        detail["adam_scatter_ms"] = med
+        detail["adam_scatter_GBs"] = ab / (med * 1e-3) / 1e9
+        detail["adam_scatter_frac_hbm"] = detail["adam_scatter_GBs"] / PEAK_HBM_GBS
+        st.full_gradient(dY, X)
+        med, _ = time_calls(lambda: grass.row_stats(st.G, st.sumsq), it)
+        gb = m * n * st.G.element_size() + 4 * m
+        detail["row_stats_ms"] = med
+        detail["row_stats_GBs"] = gb / (med * 1e-3) / 1e9
+        detail["row_stats_frac_hbm"] = detail["row_stats_GBs"] / PEAK_HBM_GBS
+        med, _ = time_calls(lambda: grass.select_rows(st.sumsq, r, st.method, st.replacement,
+                                                      st.scale, st.seed, 0, st.idx, st.rho,
+                                                      st.ws_sel), it)
+        detail["select_rows_ms"] = med
+        med_dense, _ = time_calls(lambda: st.full_gradient(dY, X), 5, warmup=1)
+        tmp = torch.empty((r, n), dtype=torch.float32, device=dev)
+        med_g, _ = time_calls(lambda: grass.gather_rows(st.G, st.idx, st.rho, tmp), it)
+        detail["naive_full_grad_ms"] = med_dense
+        detail["naive_full_grad_tflops"] = 2.0 * m * T * n / (med_dense * 1e-3) / 1e12
+        detail["naive_gather_ms"] = med_g
+        detail["speedup_vs_naive_full_G_then_gather"] = (med_dense + med_g) / detail[
+            "compressed_grad_call_ms"]
+        detail["regular_step_ms"] = detail["compressed_grad_call_ms"] + detail["adam_scatter_ms"]
+        detail["paper_context"] = ("paper: 13B LLaMA half-precision pretraining on one 40 GB "
+                                   "A100; no per-layer timing is published")
+        out["detail"] = detail
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, L, dY, X, st, W, args.cpu_seconds)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

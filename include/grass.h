@@ -136,6 +136,17 @@ grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64
                                    const float* rho, float* GC, int64_t ldgc, void* ws,
                                    size_t ws_bytes, void* stream);
 
+/* grass_compressed_grad with a timing hook: the two hipEvent_t handles (passed as
+ * void*, either may be NULL) are recorded on `stream` immediately before and after
+ * the matrix-multiply kernel, so that a caller can time that kernel apart from the
+ * gather and reduction passes around it.  Everything else is identical. */
+grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                         const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                         int64_t m, int64_t n, int64_t r, const int32_t* idx,
+                                         const float* rho, float* GC, int64_t ldgc, void* ws,
+                                         size_t ws_bytes, void* stream, void* ev_gemm_start,
+                                         void* ev_gemm_stop);
+
 /* ---------------------------------------------------------------------------
  * opt.update = Adam on the r x n compressed gradient (Appendix A, adam.update):
  *   M <- b1*M + (1-b1)*g        V <- b2*V + (1-b2)*g^2

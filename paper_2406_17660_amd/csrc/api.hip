@@ -105,6 +105,16 @@ grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64
                                    int64_t m, int64_t n, int64_t r, const int32_t* idx,
                                    const float* rho, float* GC, int64_t ldgc, void* ws,
                                    size_t ws_bytes, void* stream) {
+    return grass_compressed_grad_timed(dY, layout, ldy, X, ldx, dt, T, m, n, r, idx, rho, GC, ldgc,
+                                       ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                         const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                         int64_t m, int64_t n, int64_t r, const int32_t* idx,
+                                         const float* rho, float* GC, int64_t ldgc, void* ws,
+                                         size_t ws_bytes, void* stream, void* ev_gemm_start,
+                                         void* ev_gemm_stop) {
     const grass_status st = check_products(dY, layout, ldy, X, ldx, dt, T, m, n);
     if (st != GRASS_OK) return st;
     if (r < 0 || r > kMaxGridRows || ldgc < n || (r > 0 && m == 0)) return GRASS_ERR_SHAPE;
@@ -112,7 +122,8 @@ grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64
     const size_t need = gemm_workspace_bytes(T, r, n, dt, layout, true);
     if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
     return launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, r, n, idx, rho, GC, GRASS_F32, ldgc, ws,
-                          as_stream(stream));
+                          as_stream(stream), static_cast<hipEvent_t>(ev_gemm_start),
+                          static_cast<hipEvent_t>(ev_gemm_stop));
 }
 
 grass_status grass_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,

@@ -375,11 +375,13 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
                             const int32_t* idx, const float* rho, void* C, grass_dtype odt,
-                            int64_t ldc, void* ws, hipStream_t s) {
+                            int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start,
+                            hipEvent_t ev_stop) {
     if (mrows == 0 || n == 0) return GRASS_OK;
-    if (mrows > 65535 * 64) return GRASS_ERR_SHAPE;
+    if (mrows > 65535) return GRASS_ERR_SHAPE;
     if (dt == GRASS_F32) {
         const dim3 grid(static_cast<unsigned>((n + 63) / 64), static_cast<unsigned>((mrows + 63) / 64));
+        if (ev_start) (void)hipEventRecord(ev_start, s);
         if (odt == GRASS_F32)
             tn_gemm_f32_kernel<float><<<grid, 256, 0, s>>>(
                 static_cast<const float*>(dY), layout, ldy, static_cast<const float*>(X), ldx, T,
@@ -388,6 +390,7 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
             tn_gemm_f32_kernel<uint16_t><<<grid, 256, 0, s>>>(
                 static_cast<const float*>(dY), layout, ldy, static_cast<const float*>(X), ldx, T,
                 mrows, n, idx, rho, static_cast<uint16_t*>(C), ldc);
+        if (ev_stop) (void)hipEventRecord(ev_stop, s);
         return launch_status();
     }
 
@@ -440,11 +443,12 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
     const int64_t items = static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.splits;
     const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
     if (chunk * kNumXcd > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
+    if (ev_start) (void)hipEventRecord(ev_start, s);
     tn_gemm_bf16_kernel<Cfg><<<static_cast<unsigned>(chunk * kNumXcd), Cfg::kThreads,
                                Cfg::kLdsBytes, s>>>(g);
+    if (ev_stop) (void)hipEventRecord(ev_stop, s);
 
     const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(mrows));
-    if (mrows > 65535) return GRASS_ERR_SHAPE;
     if (odt == GRASS_F32)
         splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(partial, p.splits, p.Mp, p.Np, mrows, n,
                                                           rho, static_cast<float*>(C), ldc);

@@ -22,7 +22,8 @@ DY_TxM, DY_MxT = 0, 1
 
 EXPORTS = [
     "grass_status_string", "grass_row_stats", "grass_select_workspace", "grass_select_rows",
-    "grass_cgrad_workspace", "grass_compressed_grad", "grass_adam_rows", "grass_scatter_update",
+    "grass_cgrad_workspace", "grass_compressed_grad", "grass_compressed_grad_timed",
+    "grass_adam_rows", "grass_scatter_update",
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
 ]
 
@@ -56,6 +57,7 @@ def lib():
     L.grass_cgrad_workspace.restype = sz
     L.grass_compressed_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, i64, vp, vp,
                                         vp, i64, vp, sz, vp]
+    L.grass_compressed_grad_timed.argtypes = L.grass_compressed_grad.argtypes + [vp, vp]
     L.grass_adam_rows.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, vp]
     L.grass_scatter_update.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, i64, vp]
     L.grass_adam_scatter.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, i32,
@@ -150,7 +152,9 @@ def cgrad_workspace(T, m, n, r, dtype, layout=DY_TxM) -> int:
     return int(lib().grass_cgrad_workspace(T, m, n, r, dtype, layout))
 
 
-def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM):
+def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM, gemm_events=None):
+    """gemm_events: optional (start, stop) torch.cuda.Event pair, already recorded once so
+    that their handles exist; the library re-records them around the GEMM kernel."""
     pY, ry, cy, ldy = _mat(dY)
     pX, T, n, ldx = _mat(X)
     m = cy if layout == DY_TxM else ry
@@ -159,9 +163,13 @@ def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM):
     pG, gr, gc, ldgc = _mat(GC)
     assert (gr, gc) == (r, n) and GC.dtype == torch.float32
     wp, wb = _ws(ws)
-    _check(lib().grass_compressed_grad(pY, layout, ldy, pX, ldx, _dtype(X), T, m, n, r,
-                                       _vec(idx, torch.int32), _vec(rho, torch.float32), pG, ldgc,
-                                       wp, wb, _stream()), "grass_compressed_grad")
+    args = (pY, layout, ldy, pX, ldx, _dtype(X), T, m, n, r, _vec(idx, torch.int32),
+            _vec(rho, torch.float32), pG, ldgc, wp, wb, _stream())
+    if gemm_events is None:
+        _check(lib().grass_compressed_grad(*args), "grass_compressed_grad")
+    else:
+        e0, e1 = (C.c_void_p(e.cuda_event) for e in gemm_events)
+        _check(lib().grass_compressed_grad_timed(*args, e0, e1), "grass_compressed_grad_timed")
     return GC
 
 

@@ -1,0 +1,87 @@
+"""Per-layer driver of Algorithm 1 (memory-efficient subspace optimisation) on top of the C ABI.
+
+Owns the buffers one linear layer needs (idx, rho, Adam moments, compressed gradient,
+workspaces) and issues the library calls in the order of Algorithm 1.  No arithmetic of the
+method happens here: every step is a HIP kernel behind `grass.*`.
+"""
+from dataclasses import dataclass
+
+import torch
+
+from . import grass
+
+METHODS = {"topr": grass.SEL_TOPR, "uniform": grass.SEL_UNIFORM,
+           "multi_norm": grass.SEL_MULTI_NORM, "multi_norm2": grass.SEL_MULTI_NORM2}
+
+
+@dataclass
+class AdamHyper:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+
+
+class GrassLayer:
+    """State of one m x n linear layer trained with GRASS at rank r.
+
+    refresh() is `compute_P` + `update_state` of Algorithm 1 (lines under "if t = 0 mod K");
+    step() is the regular part (G_C, opt.update, W += alpha P Delta).
+    """
+
+    def __init__(self, m, n, r, T, dtype, method="topr", replacement=False,
+                 scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, g_dtype=None,
+                 layout=grass.DY_TxM, device="cuda"):
+        self.m, self.n, self.r, self.T = m, n, r, T
+        self.dtype = dtype
+        self.dt = grass.F32 if dtype == torch.float32 else grass.BF16
+        self.method, self.replacement, self.scale = METHODS[method], replacement, scale
+        self.alpha, self.adam, self.seed, self.layout = alpha, adam or AdamHyper(), seed, layout
+        self.g_dtype = g_dtype or dtype
+        dev = device
+        self.idx = torch.zeros(r, dtype=torch.int32, device=dev)
+        self.rho = torch.ones(r, dtype=torch.float32, device=dev)
+        self.M = torch.zeros((r, n), dtype=torch.float32, device=dev)
+        self.V = torch.zeros((r, n), dtype=torch.float32, device=dev)
+        self.GC = torch.empty((r, n), dtype=torch.float32, device=dev)
+        self.sumsq = torch.empty(m, dtype=torch.float32, device=dev)
+        self.ws_sel = grass.workspace(grass.select_workspace(m, r, self.method, replacement), dev)
+        self.ws_gemm = grass.workspace(grass.cgrad_workspace(T, m, n, r, self.dt, layout), dev)
+        self.ws_dense = None  # allocated on first refresh: only refresh steps need it
+        self.G = None
+        self.adam_t = 0
+        self.refresh_id = 0
+
+    # -- refresh step -----------------------------------------------------------------
+    def full_gradient(self, dY, X):
+        if self.G is None:
+            self.G = torch.empty((self.m, self.n), dtype=self.g_dtype, device=X.device)
+            self.ws_dense = grass.workspace(
+                grass.dense_workspace(self.T, self.m, self.n, self.dt, self.layout), X.device)
+        return grass.dense_grad(dY, X, self.G, self.ws_dense, self.layout)
+
+    def refresh(self, dY, X, reset_state=True):
+        self.full_gradient(dY, X)
+        grass.row_stats(self.G, self.sumsq)
+        grass.select_rows(self.sumsq, self.r, self.method, self.replacement, self.scale, self.seed,
+                          self.refresh_id, self.idx, self.rho, self.ws_sel)
+        self.refresh_id += 1
+        if reset_state:  # update_state: moments back to zero, Adam's t restarts
+            self.M.zero_()
+            self.V.zero_()
+            self.adam_t = 0
+
+    # -- regular step -----------------------------------------------------------------
+    def compressed_grad(self, dY, X, gemm_events=None):
+        return grass.compressed_grad(dY, X, self.idx, self.rho, self.GC, self.ws_gemm, self.layout,
+                                     gemm_events)
+
+    def adam_scatter(self, W):
+        self.adam_t += 1
+        a = self.adam
+        return grass.adam_scatter(self.GC, self.M, self.V, a.lr, a.beta1, a.beta2, a.eps,
+                                  self.adam_t, W, self.idx, self.rho, self.alpha)
+
+    def step(self, dY, X, W, gemm_events=None):
+        self.compressed_grad(dY, X, gemm_events)
+        self.adam_scatter(W)
