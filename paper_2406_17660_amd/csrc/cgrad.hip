@@ -114,6 +114,8 @@ struct TileCfg {
     static constexpr int A_CHUNKS = BK * BM / 8 / kThreads;  // 16-byte chunks per thread
     static constexpr int B_CHUNKS = BK * BN / 8 / kThreads;
     static constexpr size_t kLdsBytes = static_cast<size_t>(BK) * (LDA + LDB) * 2;
+    static constexpr int kWgPerCu = 2;
+    static constexpr bool kWholeKTilesOnly = false;
     static_assert(BK % 16 == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
     static_assert((BK * BM / 8) % kThreads == 0 && (BK * BN / 8) % kThreads == 0, "chunking");
 };
@@ -144,7 +146,9 @@ struct GemmArgs {
     int a_fast, b_fast;
 };
 
-template <typename Cfg>
+// kDense only tags the instantiation (dense full gradient vs compressed gradient) so that a
+// profiler lists the two uses separately; the code is identical.
+template <typename Cfg, bool kDense>
 __global__ __launch_bounds__(Cfg::kThreads) void tn_gemm_bf16_kernel(GemmArgs g) {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     uint16_t* As = lds;
@@ -256,6 +260,224 @@ __global__ __launch_bounds__(Cfg::kThreads) void tn_gemm_bf16_kernel(GemmArgs g)
             }
 }
 
+// ------------------------------------------------------------------------------ bf16 MFMA GEMM, large tiles
+// 256 x 256 output tile, four wavefronts in a 2 x 2 arrangement, each owning a 128 x 128
+// block (16 accumulator fragments = 256 registers per lane, one wavefront per SIMD).
+//
+// Global -> LDS copies use the gfx950 16-byte load-to-LDS instruction, which needs no
+// staging registers: a wavefront load writes 1 KiB of consecutive LDS (two 512-byte tile
+// rows), each lane choosing its own global address.  K advances in tiles of 32 rows held
+// in a ring of four LDS stages (4 x 32 KiB): while tile kt is multiplied the loads of tiles
+// kt+1 .. kt+3 are in flight, which covers the L2/HBM latency with a single wavefront per
+// SIMD.  One barrier per K tile; the wait before it is s_waitcnt vmcnt(N) with N = the
+// loads issued for the younger tiles (the counter retires in order).
+//
+// LDS rows are not padded (the load-to-LDS destination is contiguous); instead the
+// 16-byte slots of row k are permuted by XOR with 4*(k mod 4).  The lane that fills
+// physical slot p of row k therefore fetches logical slot p ^ 4*(k%4) from global memory,
+// and the transposing LDS reads apply the same XOR.  One ds_read_b64_tr_b16 of a
+// wavefront touches 8 rows x 64 B; with the permutation every half-wavefront covers all 64
+// banks exactly once.
+//
+// Edges.  Columns past the matrix edge are redirected to column 0 of the same row: they
+// only feed output rows / columns that are never read back.  Only whole K tiles are
+// processed (g.K is a multiple of kFastBK here; the launcher hands a ragged tail of T to
+// the small-tile kernel as one more split-K slice).
+// Requirements (checked by the launcher): bases 16-byte aligned, leading dimensions and
+// column counts multiples of 8.
+constexpr int kFastBM = 256, kFastBN = 256, kFastBK = 32, kFastStages = 4;
+constexpr int kFastOperandElems = kFastBK * 256;          // one operand of one stage
+constexpr int kFastStageElems = 2 * kFastOperandElems;    // A then B
+constexpr int kFastLoadsPerTile = 2 * (kFastBK / 8);      // load-to-LDS instructions per wavefront
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wavefront writes
+// LDS bytes [lds_base + 16*i, +16).  Written as inline assembly so that the compiler's
+// automatic wait-count insertion does not see the transfer: it cannot tell the ring stages
+// apart and would wait for ALL outstanding loads before the first LDS read of every
+// stage, which serialises the pipeline.  The waits are placed by hand (wait_vmcnt below).
+__device__ __forceinline__ void load16_to_lds(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ bf16x8 read_frag_swz(const uint16_t* p) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 256));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits
+// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <bool kDense>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void tn_gemm_bf16_direct_kernel(GemmArgs g) {
+    __shared__ __attribute__((aligned(1024))) uint16_t ring[kFastStages * kFastStageElems];
+
+    const int64_t items = static_cast<int64_t>(g.tiles_m) * g.tiles_n * g.splits;
+    const int64_t chunk_items = (items + kNumXcd - 1) / kNumXcd;
+    const int64_t item =
+        static_cast<int64_t>(blockIdx.x % kNumXcd) * chunk_items + blockIdx.x / kNumXcd;
+    if (item >= items) return;
+    const int tiles = g.tiles_m * g.tiles_n;
+    const int split = static_cast<int>(item / tiles);
+    const int tile = static_cast<int>(item % tiles);
+    const int tm = tile % g.tiles_m, tn = tile / g.tiles_m;
+    const int64_t m0 = static_cast<int64_t>(tm) * kFastBM, n0 = static_cast<int64_t>(tn) * kFastBN;
+    const int64_t kt_begin = static_cast<int64_t>(split) * g.ktiles_per_split;
+    const int64_t ktiles_all = g.K / kFastBK;
+    int64_t kt_end = kt_begin + g.ktiles_per_split;
+    if (kt_end > ktiles_all) kt_end = ktiles_all;
+    const int ntiles = kt_end > kt_begin ? static_cast<int>(kt_end - kt_begin) : 0;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave & 1, wc = wave >> 1;
+
+    // ---- global -> LDS addressing: this lane fills physical slot `slot` of row lrow (+8 per pass)
+    const int lrow = wave * 2 + (lane >> 5);
+    const int slot = lane & 31;
+    const int lchunk_g = slot ^ (4 * (lrow & 3));
+    int64_t colA = m0 + lchunk_g * 8, colB = n0 + lchunk_g * 8;
+    if (colA >= g.Mcols) colA = 0;
+    if (colB >= g.Ncols) colB = 0;
+    const uint16_t* gA = g.A + (kt_begin * kFastBK + lrow) * g.lda + colA;
+    const uint16_t* gB = g.B + (kt_begin * kFastBK + lrow) * g.ldb + colB;
+    const int64_t passA = 8 * g.lda, passB = 8 * g.ldb;
+    const int64_t tileA = kFastBK * g.lda, tileB = kFastBK * g.ldb;
+    const int ldsrow = wave * 2;  // first LDS row this wavefront writes in a pass
+
+    // loads of K tile number `i` (counted from this workgroup's first tile) into its ring stage
+    const uint32_t ring_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)ring));
+    auto issue = [&](int i) {
+        const uint32_t dA = ring_base + ((i % kFastStages) * kFastStageElems + ldsrow * 256) * 2;
+        const uint32_t dB = dA + kFastOperandElems * 2;
+#pragma unroll
+        for (int p = 0; p < kFastBK / 8; ++p) {
+            load16_to_lds(gA + p * passA, dA + p * 8 * 256 * 2);
+            load16_to_lds(gB + p * passB, dB + p * 8 * 256 * 2);
+        }
+        gA += tileA;
+        gB += tileB;
+    };
+
+    // ---- LDS -> MFMA operand addressing (element offsets inside an operand block)
+    const int L = lane & 15, g2 = (lane >> 4) & 1, h = lane >> 5;
+    const int rrow = 8 * h + (L >> 2);
+    const int swz = 4 * (L >> 2);
+    const int lchunk = 2 * g2 + ((L & 3) >> 1);
+    const int half = (L & 1) * 4;
+    int offA[4], offB[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        offA[i] = rrow * 256 + ((((wr * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
+        offB[i] = kFastOperandElems + rrow * 256 +
+                  ((((wc * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
+    }
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // Operand fragments of one k16 slice of a tile: A rows 4 x 32, B columns 4 x 32.
+    struct Frags { bf16x8 a[4], b[4]; };
+    // read order = the order in which the MFMAs below consume them
+    auto read_frags = [&](Frags& f, int i, int k16) {
+        const uint16_t* st = ring + (i % kFastStages) * kFastStageElems + k16 * 256;
+        f.a[0] = read_frag_swz(st + offA[0]);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) f.b[b] = read_frag_swz(st + offB[b]);
+#pragma unroll
+        for (int a = 1; a < 4; ++a) f.a[a] = read_frag_swz(st + offA[a]);
+    };
+    auto mfma16 = [&](const Frags& f) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
+    };
+    // Ask the scheduler for "one MFMA, one LDS read" sixteen times: the 16 transposing reads
+    // of the next slice issue in the shadow of the 16 MFMAs of the current one.
+    auto interleave_hint = [&]() {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        }
+    };
+
+    // Software pipeline.  Each K tile has two k16 slices.  While the MFMAs of one slice run,
+    // the fragments of the next slice are read from LDS into the other fragment set, so the
+    // matrix pipe only idles at the barrier.  Loads run kAhead tiles ahead of the MFMAs.
+    //
+    //   iteration i:  wait(tile i landed) ; barrier
+    //                 F <- slice (i,0)   ||  MFMA on G = slice (i-1,1)
+    //                 issue loads of tile i+kAhead (overwrites the stage of tile i-1,
+    //                 whose last reads were issued before the barrier)
+    //                 G <- slice (i,1)   ||  MFMA on F
+    constexpr int kAhead = kFastStages - 1;
+    static_assert(kFastBK == 32, "two k16 slices per tile");
+    Frags F, G;
+    if (ntiles > 0) {
+        const int pre = ntiles < kAhead ? ntiles : kAhead;
+        for (int i = 0; i < pre; ++i) issue(i);
+        // tile 0: nothing to overlap with yet
+        if (ntiles > kAhead - 1) wait_vmcnt<(kAhead - 1) * kFastLoadsPerTile>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(F, 0, 0);
+        if (kAhead < ntiles) issue(kAhead);
+        read_frags(G, 0, 16);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma16(F);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 1; i < ntiles; ++i) {
+            // tiles i+1 .. i+kAhead-1 were issued after tile i (fewer near the end: wait for all)
+            if (i + kAhead - 1 < ntiles) wait_vmcnt<(kAhead - 1) * kFastLoadsPerTile>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): own LDS reads of tile i-1 done
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(F, i, 0);
+            mfma16(G);
+            interleave_hint();
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + kAhead < ntiles) issue(i + kAhead);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(G, i, 16);
+            mfma16(F);
+            interleave_hint();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mfma16(G);
+    }
+
+    float* P = g.P + (static_cast<int64_t>(split) * g.Mp + m0 + wr * 128) * g.Np + n0 + wc * 128;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                P[static_cast<int64_t>(row) * g.Np + b * 32 + (lane & 31)] = acc[a][b][v];
+            }
+}
+
 // out[j, i] = scale_j * sum_s P[s][j][i]   (fixed summation order: deterministic)
 template <typename OT>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, int splits,
@@ -326,6 +548,11 @@ __global__ __launch_bounds__(256) void tn_gemm_f32_kernel(
 
 // ------------------------------------------------------------------------------ host side
 using Cfg128 = TileCfg<128, 128, 64, 2, 2>;
+enum TileId { kTile128 = 0, kTile256 = 1 };
+struct Shape256 {
+    static constexpr int BM = kFastBM, BN = kFastBN, BK = kFastBK, kWgPerCu = 1;
+    static constexpr bool kWholeKTilesOnly = true;  // a ragged tail of T is a separate slice
+};
 
 struct Plan {
     int64_t Mp, Np, rp;  // padded rows / cols of the partial buffer; packed panel width
@@ -343,10 +570,11 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     p.Mp = static_cast<int64_t>(p.tiles_m) * Cfg::BM;
     p.Np = static_cast<int64_t>(p.tiles_n) * Cfg::BN;
     p.rp = p.Mp;
-    const int64_t ktiles = (T + Cfg::BK - 1) / Cfg::BK;
+    const int64_t ktiles = Cfg::kWholeKTilesOnly ? T / Cfg::BK : (T + Cfg::BK - 1) / Cfg::BK;
     const int64_t tiles = static_cast<int64_t>(p.tiles_m) * p.tiles_n;
-    // enough workgroups for two per CU, but keep at least 8 K tiles per split
-    int64_t s = tiles > 0 ? (2 * 256 + tiles - 1) / tiles : 1;
+    // split K until every CU has its share of workgroups, but keep >= 8 K tiles per split
+    const int64_t slots = 256 * Cfg::kWgPerCu;
+    int64_t s = tiles > 0 ? (slots + tiles / 2) / tiles : 1;
     const int64_t smax = ktiles / 8 > 0 ? ktiles / 8 : 1;
     if (s > smax) s = smax;
     if (s < 1) s = 1;
@@ -355,7 +583,8 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     p.splits = static_cast<int>((ktiles + p.ktiles_per_split - 1) / p.ktiles_per_split);
     if (p.splits < 1) p.splits = 1;
     p.pack_bytes = needs_pack ? round_up(static_cast<size_t>(T) * p.rp * 2, 256) : 0;
-    p.partial_bytes = static_cast<size_t>(p.splits) * p.Mp * p.Np * 4;
+    // one spare slice: the large-tile path gives the ragged tail of T to the small-tile kernel
+    p.partial_bytes = static_cast<size_t>(p.splits + 1) * p.Mp * p.Np * 4;
     return p;
 }
 
@@ -363,13 +592,46 @@ bool needs_pack(grass_dy_layout layout, bool gathered) {
     return gathered || layout == GRASS_DY_MxT;
 }
 
+// Large problems take the 256 x 256 tile (half the LDS traffic per flop); small ones keep
+// 128 x 128 so that there are enough tiles to spread over the CUs.
+TileId choose_tile(int64_t T, int64_t rows, int64_t n) {
+    if (const char* e = getenv("GRASS_GEMM_TILE")) return atoi(e) == 256 ? kTile256 : kTile128;
+    (void)T;
+    const int64_t tiles256 = ((rows + 255) / 256) * ((n + 255) / 256);
+    return (rows >= 512 && n >= 512 && tiles256 >= 32) ? kTile256 : kTile128;
+}
+
+Plan plan_for(TileId id, int64_t T, int64_t rows, int64_t n, bool pack) {
+    return id == kTile256 ? make_plan<Shape256>(T, rows, n, pack) : make_plan<Cfg128>(T, rows, n, pack);
+}
+
+template <typename Cfg, bool kDense>
+hipError_t launch_gemm_kernel(const GemmArgs& g, unsigned grid, hipStream_t s) {
+    auto kernel = tn_gemm_bf16_kernel<Cfg, kDense>;
+    if (Cfg::kLdsBytes > 64 * 1024) {
+        static bool raised = false;  // per instantiation; the attribute is sticky per process
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     static_cast<int>(Cfg::kLdsBytes));
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    kernel<<<grid, Cfg::kThreads, Cfg::kLdsBytes, s>>>(g);
+    return hipSuccess;
+}
+
 }  // namespace
 
 size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
                             grass_dy_layout layout, bool gathered) {
     if (dt == GRASS_F32) return 0;
-    const Plan p = make_plan<Cfg128>(T, mrows, n, needs_pack(layout, gathered));
-    return p.pack_bytes + p.partial_bytes + 256;
+    // the launcher may fall back to the small tile when alignment rules out the large one
+    const bool pack = needs_pack(layout, gathered);
+    const Plan a = plan_for(kTile128, T, mrows, n, pack), b = plan_for(kTile256, T, mrows, n, pack);
+    const size_t wa = a.pack_bytes + a.partial_bytes, wb = b.pack_bytes + b.partial_bytes;
+    return (wa > wb ? wa : wb) + 256;
 }
 
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
@@ -394,10 +656,17 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
         return launch_status();
     }
 
-    using Cfg = Cfg128;
     const bool gathered = idx != nullptr;
     const bool pack = needs_pack(layout, gathered);
-    const Plan p = make_plan<Cfg>(T, mrows, n, pack);
+    TileId tile = choose_tile(T, mrows, n);
+    {   // the large-tile kernel moves whole aligned 16-byte chunks only
+        const bool a_ok = pack || (aligned_to(dY, 16) && ldy % 8 == 0 && mrows % 8 == 0);
+        const bool b_ok = aligned_to(X, 16) && ldx % 8 == 0 && n % 8 == 0;
+        if (!(a_ok && b_ok && T >= kFastBK && mrows >= 8 && n >= 8)) tile = kTile128;
+    }
+    // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
+    const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
+    const Plan p = plan_for(tile, T, mrows, n, pack);  // sized for all T rows; K tiling per tile kind
     char* base = static_cast<char*>(ws);
     base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
     uint16_t* panel = reinterpret_cast<uint16_t*>(base);
@@ -432,7 +701,7 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
     g.Ncols = n;
     g.b_fast = aligned_to(X, 16) && ldx % 8 == 0;
     g.P = partial;
-    g.K = T;
+    g.K = T_main;
     g.Mp = p.Mp;
     g.Np = p.Np;
     g.tiles_m = p.tiles_m;
@@ -444,16 +713,45 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
     const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
     if (chunk * kNumXcd > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
     if (ev_start) (void)hipEventRecord(ev_start, s);
-    tn_gemm_bf16_kernel<Cfg><<<static_cast<unsigned>(chunk * kNumXcd), Cfg::kThreads,
-                               Cfg::kLdsBytes, s>>>(g);
+    const unsigned grid = static_cast<unsigned>(chunk * kNumXcd);
+    hipError_t le;
+    if (tile == kTile256) {
+        if (gathered)
+            tn_gemm_bf16_direct_kernel<false><<<grid, 256, 0, s>>>(g);
+        else
+            tn_gemm_bf16_direct_kernel<true><<<grid, 256, 0, s>>>(g);
+        le = hipSuccess;
+    } else
+        le = gathered ? launch_gemm_kernel<Cfg128, false>(g, grid, s)
+                      : launch_gemm_kernel<Cfg128, true>(g, grid, s);
+    if (le != hipSuccess) return GRASS_ERR_DEVICE;
     if (ev_stop) (void)hipEventRecord(ev_stop, s);
+    int slices = p.splits;
+    if (T_main < T) {  // rows [T_main, T) as one more slice, computed with 128 x 128 tiles
+        GemmArgs t = g;
+        t.A = g.A + T_main * g.lda;
+        t.B = g.B + T_main * g.ldb;
+        t.K = T - T_main;
+        t.P = partial + static_cast<int64_t>(p.splits) * p.Mp * p.Np;
+        t.tiles_m = static_cast<int>(p.Mp / Cfg128::BM);
+        t.tiles_n = static_cast<int>(p.Np / Cfg128::BN);
+        t.splits = 1;
+        t.ktiles_per_split = 1;
+        t.a_fast = t.b_fast = 1;
+        const int64_t titems = static_cast<int64_t>(t.tiles_m) * t.tiles_n;
+        const unsigned tgrid = static_cast<unsigned>((titems + kNumXcd - 1) / kNumXcd * kNumXcd);
+        le = gathered ? launch_gemm_kernel<Cfg128, false>(t, tgrid, s)
+                      : launch_gemm_kernel<Cfg128, true>(t, tgrid, s);
+        if (le != hipSuccess) return GRASS_ERR_DEVICE;
+        ++slices;
+    }
 
     const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(mrows));
     if (odt == GRASS_F32)
-        splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(partial, p.splits, p.Mp, p.Np, mrows, n,
+        splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(partial, slices, p.Mp, p.Np, mrows, n,
                                                           rho, static_cast<float*>(C), ldc);
     else
-        splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(partial, p.splits, p.Mp, p.Np, mrows,
+        splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(partial, slices, p.Mp, p.Np, mrows,
                                                              n, rho, static_cast<uint16_t*>(C), ldc);
     return launch_status();
 }

@@ -287,3 +287,51 @@ def test_adam_scatter_empty():
     i = torch.zeros((0,), dtype=torch.int32, device=DEV)
     grass.adam_scatter(e, e.clone(), e.clone(), LR, B1, B2, EPS, 1, W, i, torch.zeros(0, device=DEV), 1.0)
     assert (W == 0).all()
+
+
+# ------------------------------------------------------------------------------ large-tile GEMM path
+@pytest.mark.parametrize("layout", [grass.DY_TxM, grass.DY_MxT])
+@pytest.mark.parametrize("T,m,n,r,dup", [
+    (1000, 700, 1376, 300, True),    # ragged T (tail slice), n = 5*256 + 96, panel padded 300 -> 512
+    (2048, 512, 512, 512, False),    # exact tiles, r = m
+    (4100, 600, 264, 257, False),    # one row past a tile boundary, narrow n, T tail of 4 rows
+    (96, 300, 512, 256, False),      # fewer K tiles than ring stages
+])
+def test_compressed_grad_large_tile_kernel(monkeypatch, layout, T, m, n, r, dup):
+    """The 256 x 256 load-to-LDS kernel, forced for shapes small enough for a full oracle."""
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    dY = randn((T, m), torch.bfloat16, 11, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 12)
+    idx, rho = make_idx(m, r, 13, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    got = to_f64(gpu_cgrad(dY_dev, X, d_idx, d_rho, layout))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= 2e-5
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("T,m,n", [(1000, 520, 264), (2048, 512, 768)])
+def test_dense_grad_large_tile_kernel(monkeypatch, T, m, n):
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    dY = randn((T, m), torch.bfloat16, 15, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 16)
+    G = gpu_dense(dY, X, torch.float32)
+    assert rel_fro(to_f64(G), ref.full_grad(to_np(dY), to_np(X))) <= 2e-5
+
+
+def test_compressed_grad_large_tile_chosen_by_shape():
+    """A shape for which the launcher picks the large tile by itself; the oracle is evaluated
+    on a lattice of rows and columns that touches every 256 x 256 tile and every wavefront."""
+    T, m, n, r = 8192 + 37, 2048, 2048, 1024
+    dY = randn((T, m), torch.bfloat16, 21, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 22)
+    idx, rho = make_idx(m, r, 23, False)
+    got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
+    rows = np.arange(5, r, 37)
+    cols = np.arange(3, n, 29)
+    want = ref.compressed_grad(to_np(dY), np.ascontiguousarray(to_np(X)[:, cols]), idx[rows], rho[rows])
+    sub = got[np.ix_(rows, cols)]
+    assert rel_fro(sub, want) <= 2e-5
+    assert np.abs(sub - want).max() <= 1e-4 * np.abs(want).max()
