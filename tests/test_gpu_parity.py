@@ -275,7 +275,8 @@ def test_scatter_update_and_fused_adam_scatter(wdtype, m, n, r, dup, ldw):
         if delta_tol:
             assert rel_fro(got[sel] - W0[sel], Wo[sel] - W0[sel]) <= 1e-4  # fp32 cancellation
         else:
-            assert (np.abs(got[sel] - Wo[sel]) <= 1.01 * bf16_ulp(Wo[sel])).all()
+            slack = 4 * 2.0 ** -24 * (np.abs(W0[sel]) + np.abs(Wo[sel] - W0[sel]))  # fp32 sum
+            assert (np.abs(got[sel] - Wo[sel]) <= 1.01 * bf16_ulp(Wo[sel]) + slack).all()
         assert np.array_equal(to_np(Wg)[rest], W0_bits[rest])  # other rows untouched, bit for bit
         assert rel_fro(to_f64(Mg), Mo) <= TOL_F32 and rel_fro(to_f64(Vg), Vo) <= TOL_F32
     assert torch.equal(W1, W2) and torch.equal(M1, M2) and torch.equal(V1, V2)
