@@ -108,6 +108,17 @@ def cpu_baseline(cfg, layer, dY, X, state, W, seconds):
                       f"adam_rows + scatter_update at full size ({t_tail:.2f} s)"}
 
 
+def measured_traffic(layer_name, T):
+    """HBM bytes per launch of the GEMM kernel as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (profiles/gemm_traffic.json, written from those runs); None if not recorded
+    for this workload."""
+    path = os.path.join(ROOT, "profiles", "gemm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path)).get(f"{layer_name}:T={T}")
+    return rec["bytes_per_launch"] if rec else None
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -137,6 +148,11 @@ def main():
             st.step(dY, X, W, gemm_events[t] if gemm_events else None)
 
     st.full_gradient(dY, X)  # set-up: allocates the refresh-step buffers outside the timed region
+    # One plain device-to-device copy of X (T*n*2 bytes read, as many written): the known-size
+    # transfer against which the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated.
+    calib = torch.empty_like(X)
+    calib.copy_(X)
+    del calib
     run(args.warmup)
     torch.cuda.synchronize()
     gemm_events = [(ev(), ev()) for _ in range(args.steps)]
@@ -170,9 +186,10 @@ def main():
                                f"{'' if cfg.replacement else '-NR'} selection, fp32 Adam state, "
                                f"refresh every {REFRESH_EVERY} steps",
                    "m": m, "n": n, "T": T, "r": r},
-        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_kernel (compressed gradient)",
+        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_direct_kernel<false> (compressed-gradient GEMM)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS,
+                     "traffic": measured_traffic(L.name, T),
                      "flops_per_launch": flops, "avg_launch_ms": gemm_ms},
         "host_wall_s": wall,
     }
