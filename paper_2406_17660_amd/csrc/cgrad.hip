@@ -297,10 +297,14 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // automatic wait-count insertion does not see the transfer: it cannot tell the ring stages
 // apart and would wait for ALL outstanding loads before the first LDS read of every
 // stage, which serialises the pipeline.  The waits are placed by hand (wait_vmcnt below).
-__device__ __forceinline__ void load16_to_lds(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+// The global address is a wavefront-uniform 64-bit base (scalar registers) plus a 32-bit
+// per-lane byte offset, so advancing to the next K tile costs two scalar adds and no
+// vector arithmetic.
+__device__ __forceinline__ void load16_to_lds(const void* base, uint32_t lane_offset,
+                                              uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(gptr), "s"(lds_base)
+                 : "v"(lane_offset), "s"(base), "s"(lds_base)
                  : "memory", "m0");
 }
 
@@ -351,24 +355,37 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     int64_t colA = m0 + lchunk_g * 8, colB = n0 + lchunk_g * 8;
     if (colA >= g.Mcols) colA = 0;
     if (colB >= g.Ncols) colB = 0;
-    const uint16_t* gA = g.A + (kt_begin * kFastBK + lrow) * g.lda + colA;
-    const uint16_t* gB = g.B + (kt_begin * kFastBK + lrow) * g.ldb + colB;
-    const int64_t passA = 8 * g.lda, passB = 8 * g.ldb;
+    // uniform tile base (advances by one K tile per issue) + constant per-lane byte offsets
+    const uint16_t* gA = g.A + kt_begin * kFastBK * g.lda;
+    const uint16_t* gB = g.B + kt_begin * kFastBK * g.ldb;
+    uint32_t laneA[kFastBK / 8], laneB[kFastBK / 8];
+#pragma unroll
+    for (int p = 0; p < kFastBK / 8; ++p) {
+        laneA[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.lda + colA) * 2);
+        laneB[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.ldb + colB) * 2);
+    }
     const int64_t tileA = kFastBK * g.lda, tileB = kFastBK * g.ldb;
     const int ldsrow = wave * 2;  // first LDS row this wavefront writes in a pass
 
-    // loads of K tile number `i` (counted from this workgroup's first tile) into its ring stage
+    // Loads of K tile number `i` (counted from this workgroup's first tile) into its ring
+    // stage, split into kFastLoadsPerTile single instructions (part = 0..7: A rows 8p.., then
+    // B rows) so that the main loop can space them out between MFMA groups: the four
+    // wavefronts of a workgroup share one address unit, and eight back-to-back 1 KiB loads
+    // from each of them right after a barrier stall the last wavefront's MFMAs.
     const uint32_t ring_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)ring));
+    auto issue_part = [&](int i, int part) {
+        const uint32_t d = ring_base + ((i % kFastStages) * kFastStageElems + ldsrow * 256) * 2;
+        if (part < kFastBK / 8)
+            load16_to_lds(gA, laneA[part], d + part * 8 * 256 * 2);
+        else
+            load16_to_lds(gB, laneB[part - kFastBK / 8],
+                          d + kFastOperandElems * 2 + (part - kFastBK / 8) * 8 * 256 * 2);
+    };
+    auto advance_tile = [&]() { gA += tileA; gB += tileB; };
     auto issue = [&](int i) {
-        const uint32_t dA = ring_base + ((i % kFastStages) * kFastStageElems + ldsrow * 256) * 2;
-        const uint32_t dB = dA + kFastOperandElems * 2;
 #pragma unroll
-        for (int p = 0; p < kFastBK / 8; ++p) {
-            load16_to_lds(gA + p * passA, dA + p * 8 * 256 * 2);
-            load16_to_lds(gB + p * passB, dB + p * 8 * 256 * 2);
-        }
-        gA += tileA;
-        gB += tileB;
+        for (int part = 0; part < kFastLoadsPerTile; ++part) issue_part(i, part);
+        advance_tile();
     };
 
     // ---- LDS -> MFMA operand addressing (element offsets inside an operand block)
@@ -395,29 +412,50 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
 
     // Operand fragments of one k16 slice of a tile: A rows 4 x 32, B columns 4 x 32.
     struct Frags { bf16x8 a[4], b[4]; };
-    // read order = the order in which the MFMAs below consume them
-    auto read_frags = [&](Frags& f, int i, int k16) {
+    // Quarter `part` of the fragment reads of a slice, in the order the MFMAs consume them
+    // (a0 b0 | b1 b2 | b3 a1 | a2 a3): two fragments = four transposing LDS reads.
+    auto read_quarter = [&](Frags& f, int i, int k16, int part) {
         const uint16_t* st = ring + (i % kFastStages) * kFastStageElems + k16 * 256;
-        f.a[0] = read_frag_swz(st + offA[0]);
+        if (part == 0) { f.a[0] = read_frag_swz(st + offA[0]); f.b[0] = read_frag_swz(st + offB[0]); }
+        else if (part == 1) { f.b[1] = read_frag_swz(st + offB[1]); f.b[2] = read_frag_swz(st + offB[2]); }
+        else if (part == 2) { f.b[3] = read_frag_swz(st + offB[3]); f.a[1] = read_frag_swz(st + offA[1]); }
+        else { f.a[2] = read_frag_swz(st + offA[2]); f.a[3] = read_frag_swz(st + offA[3]); }
+    };
+    auto read_frags = [&](Frags& f, int i, int k16) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) f.b[b] = read_frag_swz(st + offB[b]);
+        for (int part = 0; part < 4; ++part) read_quarter(f, i, k16, part);
+    };
+    // Row `a` of the 4 x 4 fragment products of a slice.
+    auto mfma_row = [&](const Frags& f, int a) {
 #pragma unroll
-        for (int a = 1; a < 4; ++a) f.a[a] = read_frag_swz(st + offA[a]);
+        for (int b = 0; b < 4; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
     };
     auto mfma16 = [&](const Frags& f) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
+        for (int a = 0; a < 4; ++a) mfma_row(f, a);
     };
-    // Ask the scheduler for "one MFMA, one LDS read" sixteen times: the 16 transposing reads
-    // of the next slice issue in the shadow of the 16 MFMAs of the current one.
-    auto interleave_hint = [&]() {
+    // "one MFMA, one LDS read" four times: the reads issue in the shadow of the MFMAs
+    auto interleave_hint4 = [&]() {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < 4; ++k) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        }
+    };
+    // One slice of work: the 16 MFMAs of `cur` in four groups of four, each group overlapped
+    // with a quarter of the LDS reads of the following slice (`next`) and followed by one
+    // global->LDS load of tile `load_tile` (if any).
+    auto slice = [&](const Frags& cur, Frags& next, int next_tile, int next_k16, int load_tile,
+                     int load_part0, bool do_load) {
+#pragma unroll
+        for (int part = 0; part < 4; ++part) {
+            read_quarter(next, next_tile, next_k16, part);
+            mfma_row(cur, part);
+            interleave_hint4();
+            __builtin_amdgcn_sched_barrier(0);
+            if (do_load) issue_part(load_tile, load_part0 + part);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -426,12 +464,12 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     // matrix pipe only idles at the barrier.  Loads run kAhead tiles ahead of the MFMAs.
     //
     //   iteration i:  wait(tile i landed) ; barrier
-    //                 F <- slice (i,0)   ||  MFMA on G = slice (i-1,1)
-    //                 issue loads of tile i+kAhead (overwrites the stage of tile i-1,
-    //                 whose last reads were issued before the barrier)
-    //                 G <- slice (i,1)   ||  MFMA on F
+    //                 MFMA on G = slice (i-1,1)  ||  F <- slice (i,0)  ||  A loads of tile i+kAhead
+    //                 MFMA on F                  ||  G <- slice (i,1)  ||  B loads of tile i+kAhead
+    //   The loads overwrite the stage of tile i-1, whose last LDS reads were issued (and
+    //   waited for) before the barrier.
     constexpr int kAhead = kFastStages - 1;
-    static_assert(kFastBK == 32, "two k16 slices per tile");
+    static_assert(kFastBK == 32 && kFastLoadsPerTile == 8, "two k16 slices, eight loads per tile");
     Frags F, G;
     if (ntiles > 0) {
         const int pre = ntiles < kAhead ? ntiles : kAhead;
@@ -445,23 +483,25 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_barrier(0);
         mfma16(F);
         __builtin_amdgcn_sched_barrier(0);
-        for (int i = 1; i < ntiles; ++i) {
-            // tiles i+1 .. i+kAhead-1 were issued after tile i (fewer near the end: wait for all)
-            if (i + kAhead - 1 < ntiles) wait_vmcnt<(kAhead - 1) * kFastLoadsPerTile>();
-            else wait_vmcnt<0>();
+        // steady state: tiles i+1, i+2 are in flight behind tile i; tile i+kAhead is issued here
+        int i = 1;
+        for (; i + kAhead < ntiles; ++i) {
+            wait_vmcnt<(kAhead - 1) * kFastLoadsPerTile>();
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): own LDS reads of tile i-1 done
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            read_frags(F, i, 0);
-            mfma16(G);
-            interleave_hint();
+            slice(G, F, i, 0, i + kAhead, 0, true);
+            slice(F, G, i, 16, i + kAhead, 4, true);
+            advance_tile();
+        }
+        // drain: nothing left to issue; wait for everything that is still in flight
+        for (; i < ntiles; ++i) {
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (i + kAhead < ntiles) issue(i + kAhead);
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(G, i, 16);
-            mfma16(F);
-            interleave_hint();
-            __builtin_amdgcn_sched_barrier(0);
+            slice(G, F, i, 0, 0, 0, false);
+            slice(F, G, i, 16, 0, 0, false);
         }
         mfma16(G);
     }
@@ -662,7 +702,11 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
     {   // the large-tile kernel moves whole aligned 16-byte chunks only
         const bool a_ok = pack || (aligned_to(dY, 16) && ldy % 8 == 0 && mrows % 8 == 0);
         const bool b_ok = aligned_to(X, 16) && ldx % 8 == 0 && n % 8 == 0;
-        if (!(a_ok && b_ok && T >= kFastBK && mrows >= 8 && n >= 8)) tile = kTile128;
+        // per-lane byte offsets inside one K tile are kept in 32 bits
+        const int64_t lda_eff = pack ? (mrows + kFastBM - 1) / kFastBM * kFastBM : ldy;
+        const bool off_ok = (kFastBK + 1) * lda_eff * 2 < (int64_t{1} << 32) &&
+                            (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
+        if (!(a_ok && b_ok && off_ok && T >= kFastBK && mrows >= 8 && n >= 8)) tile = kTile128;
     }
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
     const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
