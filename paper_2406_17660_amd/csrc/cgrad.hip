@@ -31,6 +31,19 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kNumXcd = 8;
 
+// Tile numbering inside one K slice: panels of four tile rows, column-major inside a panel,
+// so that a run of consecutive tile numbers (what one XCD receives) forms a compact block
+// and re-reads as little of A and B as possible through that XCD's L2.
+__device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int& tm, int& tn) {
+    constexpr int kPanel = 4;
+    const int per_panel = kPanel * tiles_n;
+    const int panel = tile / per_panel;
+    const int rows_here = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;
+    const int in_panel = tile - panel * per_panel;
+    tm = panel * kPanel + in_panel % rows_here;
+    tn = in_panel / rows_here;
+}
+
 // ------------------------------------------------------------------------------ pack
 // out[t, j] = dY[t, idx[j]] (j < r), 0 for r <= j < rp.  Thread = 4 adjacent j, loops over
 // kPackRows values of t; wave stores are contiguous 512 B.
@@ -163,7 +176,8 @@ __global__ __launch_bounds__(Cfg::kThreads) void tn_gemm_bf16_kernel(GemmArgs g)
     const int tiles = g.tiles_m * g.tiles_n;
     const int split = static_cast<int>(item / tiles);
     const int tile = static_cast<int>(item % tiles);
-    const int tm = tile % g.tiles_m, tn = tile / g.tiles_m;
+    int tm, tn;
+    tile_coords(tile, g.tiles_m, g.tiles_n, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * Cfg::BM, n0 = static_cast<int64_t>(tn) * Cfg::BN;
     const int64_t kt_begin = static_cast<int64_t>(split) * g.ktiles_per_split;
     const int64_t ktiles_all = (g.K + Cfg::BK - 1) / Cfg::BK;
@@ -336,7 +350,8 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     const int tiles = g.tiles_m * g.tiles_n;
     const int split = static_cast<int>(item / tiles);
     const int tile = static_cast<int>(item % tiles);
-    const int tm = tile % g.tiles_m, tn = tile / g.tiles_m;
+    int tm, tn;
+    tile_coords(tile, g.tiles_m, g.tiles_n, tm, tn);
     const int64_t m0 = static_cast<int64_t>(tm) * kFastBM, n0 = static_cast<int64_t>(tn) * kFastBN;
     const int64_t kt_begin = static_cast<int64_t>(split) * g.ktiles_per_split;
     const int64_t ktiles_all = g.K / kFastBK;
@@ -632,13 +647,14 @@ bool needs_pack(grass_dy_layout layout, bool gathered) {
     return gathered || layout == GRASS_DY_MxT;
 }
 
-// Large problems take the 256 x 256 tile (half the LDS traffic per flop); small ones keep
-// 128 x 128 so that there are enough tiles to spread over the CUs.
+// The 256 x 256 tile halves the LDS traffic per flop and is the faster kernel whenever it
+// does not waste much of itself on padding; narrow problems (r = 128, say) keep 128 x 128.
 TileId choose_tile(int64_t T, int64_t rows, int64_t n) {
     if (const char* e = getenv("GRASS_GEMM_TILE")) return atoi(e) == 256 ? kTile256 : kTile128;
     (void)T;
-    const int64_t tiles256 = ((rows + 255) / 256) * ((n + 255) / 256);
-    return (rows >= 512 && n >= 512 && tiles256 >= 32) ? kTile256 : kTile128;
+    if (rows < 1 || n < 1) return kTile128;
+    const double padded = static_cast<double>((rows + 255) / 256 * 256) * ((n + 255) / 256 * 256);
+    return padded <= 1.35 * static_cast<double>(rows) * static_cast<double>(n) ? kTile256 : kTile128;
 }
 
 Plan plan_for(TileId id, int64_t T, int64_t rows, int64_t n, bool pack) {
