@@ -197,6 +197,22 @@ grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ld
                               void* G, grass_dtype gdt, int64_t ldg, void* ws, size_t ws_bytes,
                               void* stream);
 
+/* Refresh-step statistic in one pass (Section 3.2 needs only the row norms of G, and the
+ * paper's memory table counts the full gradient as an intermittent cost of the projection
+ * update): sumsq[k] = sum_i (sum_t dY[t,k] X[t,i])^2 without writing G to memory.  For
+ * bf16 inputs in T x m layout with T a multiple of 32, m, n, ldy, ldx multiples of 8 and
+ * 16-byte aligned bases, the squares are taken from the fp32 accumulators in the GEMM
+ * epilogue and the workspace is a few hundred KB; other inputs form G in fp32 inside the
+ * (then m*n*4 bytes larger) workspace and reduce it from there.  The query assumes aligned
+ * bases; a call with misaligned bases and only the small workspace returns
+ * GRASS_ERR_WORKSPACE.  Errors: NULL, SHAPE, DTYPE, WORKSPACE. */
+size_t grass_grad_row_stats_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                                      grass_dy_layout layout, int64_t ldy, int64_t ldx);
+grass_status grass_grad_row_stats(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                  const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t m,
+                                  int64_t n, float* sumsq, void* ws, size_t ws_bytes,
+                                  void* stream);
+
 /* Row gather used by the naive comparator: out[j, :] = rho[j] * G[idx[j], :]
  * (fp32 out, r x n, leading dimension ldo).  Errors: NULL, SHAPE, DTYPE. */
 grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,

@@ -177,6 +177,26 @@ grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ld
                           as_stream(stream));
 }
 
+size_t grass_grad_row_stats_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                                      grass_dy_layout layout, int64_t ldy, int64_t ldx) {
+    if (T < 0 || m < 0 || n < 0) return 0;
+    return grad_row_stats_workspace_bytes(T, m, n, dt, layout, ldy, ldx);
+}
+
+grass_status grass_grad_row_stats(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                  const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t m,
+                                  int64_t n, float* sumsq, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    const grass_status st = check_products(dY, layout, ldy, X, ldx, dt, T, m, n);
+    if (st != GRASS_OK) return st;
+    if (!present(sumsq, m)) return GRASS_ERR_NULL;
+    if (m > kMaxGridRows) return GRASS_ERR_SHAPE;
+    if (!ws || ws_bytes < grad_row_stats_workspace_bytes(T, m, n, dt, layout, ldy, ldx))
+        return GRASS_ERR_WORKSPACE;
+    return launch_grad_row_stats(dY, layout, ldy, X, ldx, dt, T, m, n, sumsq, ws, ws_bytes,
+                                 as_stream(stream));
+}
+
 grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,
                                const int32_t* idx, const float* rho, int64_t r, float* out,
                                int64_t ldo, void* stream) {

@@ -337,7 +337,11 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <bool kDense>
+// kRowStats: instead of storing its output tile, the workgroup squares it and sums it along
+// each row (columns past the matrix edge excluded) and stores 256 partial row sums per
+// half-tile of columns: the row statistic of G without G ever being written.  Only valid
+// with a single K slice.
+template <bool kDense, bool kRowStats = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     __shared__ __attribute__((aligned(1024))) uint16_t ring[kFastStages * kFastStageElems];
@@ -521,6 +525,27 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
         mfma16(G);
     }
 
+    if (kRowStats) {
+        // P is used as float rowpart[2 * tiles_n][Mp]: slot 2*tn + wc holds, for every row of
+        // this tile row-block, the sum of squares over this wavefront's 128 columns.
+        float* part = g.P + static_cast<int64_t>(2 * tn + wc) * g.Mp + m0 + wr * 128;
+        const int64_t col0 = n0 + wc * 128 + (lane & 31);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float sq = 0.f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float x = col0 + b * 32 < g.Ncols ? acc[a][b][v] : 0.f;
+                    sq += x * x;
+                }
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, kWave);  // 32 lanes = 32 columns
+                if ((lane & 31) == 0) part[a * 32 + 8 * (v / 4) + 4 * h + (v % 4)] = sq;
+            }
+        return;
+    }
     float* P = g.P + (static_cast<int64_t>(split) * g.Mp + m0 + wr * 128) * g.Np + n0 + wc * 128;
 #pragma unroll
     for (int a = 0; a < 4; ++a)
@@ -531,6 +556,17 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
                 const int row = a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                 P[static_cast<int64_t>(row) * g.Np + b * 32 + (lane & 31)] = acc[a][b][v];
             }
+}
+
+// sumsq[k] = sum over the column slots of rowpart[slot][k], in slot order (deterministic)
+__global__ __launch_bounds__(256) void rowpart_reduce_kernel(const float* __restrict__ part, int slots,
+                                                             int64_t Mp, int64_t m,
+                                                             float* __restrict__ sumsq) {
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (k >= m) return;
+    float s = 0.f;
+    for (int i = 0; i < slots; ++i) s += part[static_cast<int64_t>(i) * Mp + k];
+    sumsq[k] = s;
 }
 
 // out[j, i] = scale_j * sum_s P[s][j][i]   (fixed summation order: deterministic)
@@ -678,7 +714,68 @@ hipError_t launch_gemm_kernel(const GemmArgs& g, unsigned grid, hipStream_t s) {
     return hipSuccess;
 }
 
+bool fused_stats_shape_ok(int64_t T, int64_t m, int64_t n, grass_dtype dt, grass_dy_layout layout,
+                          int64_t ldy, int64_t ldx) {
+    return dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kFastBK && T % kFastBK == 0 &&
+           m >= 8 && n >= 8 && m % 8 == 0 && n % 8 == 0 && ldy % 8 == 0 && ldx % 8 == 0 &&
+           (kFastBK + 1) * ldy * 2 < (int64_t{1} << 32) && (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
+}
+
+size_t fused_stats_bytes(int64_t m, int64_t n) {
+    const int64_t tiles_m = (m + kFastBM - 1) / kFastBM, tiles_n = (n + kFastBN - 1) / kFastBN;
+    return static_cast<size_t>(2 * tiles_n) * tiles_m * kFastBM * 4 + 256;
+}
+
 }  // namespace
+
+size_t grad_row_stats_workspace_bytes(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                                      grass_dy_layout layout, int64_t ldy, int64_t ldx) {
+    if (fused_stats_shape_ok(T, m, n, dt, layout, ldy, ldx)) return fused_stats_bytes(m, n);
+    // otherwise G is formed in fp32 inside the workspace and reduced from there
+    return static_cast<size_t>(m) * n * 4 + 256 + gemm_workspace_bytes(T, m, n, dt, layout, false);
+}
+
+grass_status launch_grad_row_stats(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                   const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t m,
+                                   int64_t n, float* sumsq, void* ws, size_t ws_bytes,
+                                   hipStream_t s) {
+    if (m == 0) return GRASS_OK;
+    char* base = static_cast<char*>(ws);
+    base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
+    const bool fused = fused_stats_shape_ok(T, m, n, dt, layout, ldy, ldx) && aligned_to(dY, 16) &&
+                       aligned_to(X, 16);
+    if (fused) {
+        if (ws_bytes < fused_stats_bytes(m, n)) return GRASS_ERR_WORKSPACE;
+        GemmArgs g;
+        g.A = static_cast<const uint16_t*>(dY);
+        g.B = static_cast<const uint16_t*>(X);
+        g.P = reinterpret_cast<float*>(base);
+        g.lda = ldy; g.ldb = ldx; g.K = T; g.Mcols = m; g.Ncols = n;
+        g.tiles_m = static_cast<int>((m + kFastBM - 1) / kFastBM);
+        g.tiles_n = static_cast<int>((n + kFastBN - 1) / kFastBN);
+        g.Mp = static_cast<int64_t>(g.tiles_m) * kFastBM;
+        g.Np = static_cast<int64_t>(g.tiles_n) * kFastBN;
+        g.splits = 1;
+        g.ktiles_per_split = static_cast<int>(T / kFastBK);
+        g.a_fast = g.b_fast = 1;
+        const int64_t items = static_cast<int64_t>(g.tiles_m) * g.tiles_n;
+        const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
+        if (chunk * kNumXcd > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
+        tn_gemm_bf16_direct_kernel<true, true><<<static_cast<unsigned>(chunk * kNumXcd), 256, 0, s>>>(g);
+        rowpart_reduce_kernel<<<static_cast<unsigned>((m + 255) / 256), 256, 0, s>>>(
+            g.P, 2 * g.tiles_n, g.Mp, m, sumsq);
+        return launch_status();
+    }
+    const size_t g_bytes = static_cast<size_t>(m) * n * 4 + 256;
+    const size_t need = g_bytes + gemm_workspace_bytes(T, m, n, dt, layout, false);
+    if (ws_bytes < need) return GRASS_ERR_WORKSPACE;
+    if (m > 65535) return GRASS_ERR_SHAPE;
+    float* G = reinterpret_cast<float*>(base);
+    const grass_status st = launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, m, n, nullptr, nullptr, G,
+                                           GRASS_F32, n, base + g_bytes, s);
+    if (st != GRASS_OK) return st;
+    return launch_row_stats(G, GRASS_F32, m, n, n, sumsq, s);
+}
 
 size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
                             grass_dy_layout layout, bool gathered) {

@@ -100,4 +100,12 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
                             int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start = nullptr,
                             hipEvent_t ev_stop = nullptr);
 
+// Row statistic of G = dY^T X without storing G (fused into the GEMM when the shape allows).
+size_t grad_row_stats_workspace_bytes(int64_t T, int64_t m, int64_t n, grass_dtype dt,
+                                      grass_dy_layout layout, int64_t ldy, int64_t ldx);
+grass_status launch_grad_row_stats(const void* dY, grass_dy_layout layout, int64_t ldy,
+                                   const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t m,
+                                   int64_t n, float* sumsq, void* ws, size_t ws_bytes,
+                                   hipStream_t s);
+
 }  // namespace grass

@@ -25,6 +25,7 @@ EXPORTS = [
     "grass_cgrad_workspace", "grass_compressed_grad", "grass_compressed_grad_timed",
     "grass_adam_rows", "grass_scatter_update",
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
+    "grass_grad_row_stats_workspace", "grass_grad_row_stats",
 ]
 
 _lib = None
@@ -67,9 +68,12 @@ def lib():
     L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
                                    sz, vp]
     L.grass_gather_rows.argtypes = [vp, i32, i64, i64, i64, vp, vp, i64, vp, i64, vp]
+    L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
+    L.grass_grad_row_stats_workspace.restype = sz
+    L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
     for name in EXPORTS:
         if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
-                        "grass_dense_workspace"):
+                        "grass_dense_workspace", "grass_grad_row_stats_workspace"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -220,6 +224,24 @@ def dense_grad(dY, X, G, ws, layout=DY_TxM):
     _check(lib().grass_dense_grad(pY, layout, ldy, pX, ldx, _dtype(X), T, m, n, pG, _dtype(G),
                                   ldg, wp, wb, _stream()), "grass_dense_grad")
     return G
+
+
+def grad_row_stats_workspace(T, m, n, dtype, layout=DY_TxM, ldy=None, ldx=None) -> int:
+    ldy = (m if layout == DY_TxM else T) if ldy is None else ldy
+    ldx = n if ldx is None else ldx
+    return int(lib().grass_grad_row_stats_workspace(T, m, n, dtype, layout, ldy, ldx))
+
+
+def grad_row_stats(dY, X, sumsq, ws, layout=DY_TxM):
+    pY, ry, cy, ldy = _mat(dY)
+    pX, T, n, ldx = _mat(X)
+    m = cy if layout == DY_TxM else ry
+    assert sumsq.shape == (m,) and dY.dtype == X.dtype
+    wp, wb = _ws(ws)
+    _check(lib().grass_grad_row_stats(pY, layout, ldy, pX, ldx, _dtype(X), T, m, n,
+                                      _vec(sumsq, torch.float32), wp, wb, _stream()),
+           "grass_grad_row_stats")
+    return sumsq
 
 
 def gather_rows(G, idx, rho, out):

@@ -31,7 +31,7 @@ class GrassLayer:
 
     def __init__(self, m, n, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, g_dtype=None,
-                 layout=grass.DY_TxM, device="cuda"):
+                 layout=grass.DY_TxM, device="cuda", materialise_G=False):
         self.m, self.n, self.r, self.T = m, n, r, T
         self.dtype = dtype
         self.dt = grass.F32 if dtype == torch.float32 else grass.BF16
@@ -49,6 +49,8 @@ class GrassLayer:
         self.ws_gemm = grass.workspace(grass.cgrad_workspace(T, m, n, r, self.dt, layout), dev)
         self.ws_dense = None  # allocated on first refresh: only refresh steps need it
         self.G = None
+        self.ws_stats = None
+        self.materialise_G = materialise_G
         self.adam_t = 0
         self.refresh_id = 0
 
@@ -60,9 +62,21 @@ class GrassLayer:
                 grass.dense_workspace(self.T, self.m, self.n, self.dt, self.layout), X.device)
         return grass.dense_grad(dY, X, self.G, self.ws_dense, self.layout)
 
+    def row_statistic(self, dY, X):
+        """Squared row norms of G for compute_P.  By default G is not stored: the squares are
+        taken in the GEMM epilogue; with materialise_G the two-call form (full gradient, then
+        grass_row_stats) is used instead."""
+        if self.materialise_G:
+            self.full_gradient(dY, X)
+            return grass.row_stats(self.G, self.sumsq)
+        if self.ws_stats is None:
+            ldy, ldx = dY.stride(0), X.stride(0)
+            self.ws_stats = grass.workspace(grass.grad_row_stats_workspace(
+                self.T, self.m, self.n, self.dt, self.layout, ldy, ldx), X.device)
+        return grass.grad_row_stats(dY, X, self.sumsq, self.ws_stats, self.layout)
+
     def refresh(self, dY, X, reset_state=True):
-        self.full_gradient(dY, X)
-        grass.row_stats(self.G, self.sumsq)
+        self.row_statistic(dY, X)
         grass.select_rows(self.sumsq, self.r, self.method, self.replacement, self.scale, self.seed,
                           self.refresh_id, self.idx, self.rho, self.ws_sel)
         self.refresh_id += 1

@@ -126,6 +126,17 @@ def test_adam_and_scatter_validation():
     assert g(FAKE, 0, 4, 8, 8, FAKE, FAKE, 2, FAKE, 7, None) == grass.ERR_SHAPE
 
 
+def test_grad_row_stats_validation():
+    L = grass.lib()
+    f = L.grass_grad_row_stats
+    assert f(None, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, FAKE, 1 << 30, None) == grass.ERR_NULL
+    assert f(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, None, FAKE, 1 << 30, None) == grass.ERR_NULL
+    assert f(FAKE, 0, 63, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, FAKE, 1 << 30, None) == grass.ERR_SHAPE
+    assert f(FAKE, 0, 64, FAKE, 32, 9, 128, 64, 32, FAKE, FAKE, 1 << 30, None) == grass.ERR_DTYPE
+    assert f(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, None, 1 << 30, None) == grass.ERR_WORKSPACE
+    assert f(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, FAKE, 64, None) == grass.ERR_WORKSPACE
+
+
 def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(grass, "_lib", None)
     monkeypatch.setattr(grass, "LIB_PATH", "/nonexistent/libgrass.so")

@@ -336,3 +336,34 @@ def test_compressed_grad_large_tile_chosen_by_shape():
     sub = got[np.ix_(rows, cols)]
     assert rel_fro(sub, want) <= 2e-5
     assert np.abs(sub - want).max() <= 1e-4 * np.abs(want).max()
+
+
+# ------------------------------------------------------------------------------ fused refresh statistic
+@pytest.mark.parametrize("dtype,layout,T,m,n,pad", [
+    (torch.bfloat16, grass.DY_TxM, 1024, 512, 512, 0),     # fused: exact tiles
+    (torch.bfloat16, grass.DY_TxM, 2048, 1032, 1376, 0),   # fused: ragged tiles in both dimensions
+    (torch.bfloat16, grass.DY_TxM, 96, 264, 24, 8),        # fused: tiny n, padded leading dimensions
+    (torch.bfloat16, grass.DY_TxM, 1000, 512, 512, 0),     # T not a multiple of 32: via fp32 G
+    (torch.bfloat16, grass.DY_TxM, 512, 130, 333, 0),      # odd n: via fp32 G
+    (torch.bfloat16, grass.DY_MxT, 512, 256, 256, 0),      # transposed storage: via fp32 G
+    (torch.float32, grass.DY_TxM, 512, 256, 256, 0),       # fp32 inputs: via fp32 G
+])
+def test_grad_row_stats_without_storing_G(dtype, layout, T, m, n, pad):
+    dY = randn((T, m), dtype, 31, scale=0.1, ld=m + pad)
+    X = randn((T, n), dtype, 32, ld=n + pad)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    out = torch.full((m,), float("nan"), device=DEV)
+    dt = grass.F32 if dtype == torch.float32 else grass.BF16
+    ldy = dY_dev.stride(0)
+    ws = grass.workspace(grass.grad_row_stats_workspace(T, m, n, dt, layout, ldy, X.stride(0)))
+    grass.grad_row_stats(dY_dev, X, out, ws, layout)
+    want = ref.row_stats(ref.full_grad(to_np(dY), to_np(X)))
+    got = to_f64(out)
+    assert rel_fro(got, want) <= TOL_F32
+    np.testing.assert_allclose(got, want, rtol=1e-5)
+
+
+def test_grad_row_stats_small_workspace_is_enough_when_fused():
+    """The point of the fused form: no m x n buffer.  4096 x 4096 needs well under 1 MB."""
+    assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.BF16) < 1 << 20
+    assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.F32) > 4096 * 4096 * 4
