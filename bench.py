@@ -38,6 +38,8 @@ def parse():
     p.add_argument("--config", type=int, default=5)
     p.add_argument("--layer", type=int, default=0, help="index into the config's layer list")
     p.add_argument("--tokens", type=int, default=None, help="override T (debug)")
+    p.add_argument("--side", choices=["rows", "cols"], default="rows",
+                   help="rows: select r rows of W (default); cols: right-hand projection, r columns")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
     p.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -140,7 +142,7 @@ def main():
     W = workloads.make_W(cfg, args.layer, dev)
     adam = AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps)
     st = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
-                    seed=workloads.BASE_SEED)
+                    seed=workloads.BASE_SEED, side=args.side)
 
     def run(steps, gemm_events=None):
         for t in range(steps):
@@ -171,7 +173,7 @@ def main():
     if grass.select_status(st.ws_sel) != grass.OK:
         sys.exit("selection reported non-finite row statistics")
 
-    flops = 2.0 * r * T * n
+    flops = 2.0 * r * T * st.n  # st.n = width of the compressed gradient (n, or m for side=cols)
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
         "metric": "GRASS layer steps/s (refresh every 200 steps included)",
@@ -184,7 +186,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cid} ({cfg.name}) layer {L.name}: W {m}x{n}, "
                                f"T={T} tokens, r={r}, {cfg.method}"
-                               f"{'' if cfg.replacement else '-NR'} selection, fp32 Adam state, "
+                               f"{'' if cfg.replacement else '-NR'} selection of {args.side}, fp32 Adam state, "
                                f"refresh every {REFRESH_EVERY} steps",
                    "m": m, "n": n, "T": T, "r": r},
         "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_direct_kernel<false> (compressed-gradient GEMM)",
@@ -195,7 +197,7 @@ def main():
         "host_wall_s": wall,
     }
 
-    if not args.no_extras:
+    if not args.no_extras and args.side == "rows":
         detail = {}
         it = 20
         med, _ = time_calls(lambda: st.compressed_grad(dY, X), it)
@@ -233,7 +235,7 @@ def main():
                                    "A100; no per-layer timing is published")
         out["detail"] = detail
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.side == "rows":
         out["cpu_baseline"] = cpu_baseline(cfg, L, dY, X, st, W, args.cpu_seconds)
 
     print(json.dumps(out))

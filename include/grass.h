@@ -174,6 +174,20 @@ grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n
                                   const int32_t* idx, const float* rho, float alpha,
                                   const float* U, int64_t r, void* stream);
 
+/* Column form of the sparse weight update, for layers whose input dimension n is the
+ * smaller one (Section 4.1 projects the smaller dimension of G).  With an n x r projection
+ * the compressed gradient is G P = (rho (B X^T) dY)^T, i.e. grass_compressed_grad called
+ * with X in the place of dY and dY in the place of X (result r x m), the statistic is the
+ * row statistic of G^T (grass_grad_row_stats / grass_dense_grad with the same exchange),
+ * Adam runs on r x m state, and the update goes to r COLUMNS of W:
+ *   W[:, idx[j]] += alpha * rho[j] * U[j, :]^T      for j < r,   U dense r x m fp32.
+ * idx sorted ascending, values in [0, n); duplicates are summed in fp32 in j order and
+ * rounded once.  Columns not in idx are not touched.
+ * Errors: NULL, SHAPE, DTYPE. */
+grass_status grass_scatter_update_cols(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
+                                       const int32_t* idx, const float* rho, float alpha,
+                                       const float* U, int64_t r, void* stream);
+
 /* Fused form of grass_adam_rows followed by grass_scatter_update: same
  * arithmetic, but U is never written to memory.  This is the call the regular
  * step uses. */

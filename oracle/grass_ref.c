@@ -142,6 +142,22 @@ int grass_ref_scatter_update(double* W, int64_t m, int64_t n, int64_t ldw, const
     return REF_OK;
 }
 
+/* Right-hand (column) projection, used when the input dimension is the smaller one
+ * (Section 4.1 projects whichever dimension of G is smaller): the r selected columns of
+ * W receive the update, W[:, sigma_j] += alpha * rho_j * U[j, :]^T with U of shape r x m.
+ * This is W + alpha * (P U)^T for the n x r projection P = (rho B)^T. */
+int grass_ref_scatter_update_cols(double* W, int64_t m, int64_t n, int64_t ldw, const int32_t* idx,
+                                  const float* rho, double alpha, const double* U, int64_t r) {
+    if (!W || !idx || !rho || !U) return REF_ERR_NULL;
+    if (m < 0 || n < 0 || r < 0 || ldw < n) return REF_ERR_SHAPE;
+    for (int64_t j = 0; j < r; ++j)
+        if (idx[j] < 0 || idx[j] >= n) return REF_ERR_SHAPE;
+    for (int64_t j = 0; j < r; ++j)
+        for (int64_t i = 0; i < m; ++i)
+            W[i * ldw + idx[j]] += alpha * (double)rho[j] * U[j * m + i];
+    return REF_OK;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as
  * 1, 2, 3", SC'11): ten rounds of two 32x32->64 multiplications, a word

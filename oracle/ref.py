@@ -38,6 +38,7 @@ def lib():
         L.grass_ref_adam_rows.argtypes = [vp, i64, vp, vp, i64, i64, C.c_double, C.c_double,
                                           C.c_double, C.c_double, i64, vp]
         L.grass_ref_scatter_update.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64]
+        L.grass_ref_scatter_update_cols.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64]
         L.grass_ref_philox4x32_10.argtypes = [vp, vp, vp]
         L.grass_ref_philox4x32_10.restype = None
         L.grass_ref_draw_word.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
@@ -138,6 +139,21 @@ def scatter_update(W, idx, rho, alpha, U):
     assert U.shape == (r, n)
     _chk(lib().grass_ref_scatter_update(_p(W), m, n, ldw, _p(idx), _p(rho), float(alpha), _p(U),
                                         r))
+    return W
+
+
+def scatter_update_cols(W, idx, rho, alpha, U):
+    """Updates W (float64, m x n) in place: W[:, idx[j]] += alpha * rho[j] * U[j, :] (U is r x m)."""
+    assert W.dtype == np.float64
+    W, ldw = _mat(W)
+    m, n = W.shape
+    idx = np.ascontiguousarray(idx, np.int32)
+    rho = np.ascontiguousarray(rho, np.float32)
+    U = np.ascontiguousarray(U, np.float64)
+    r = idx.shape[0]
+    assert U.shape == (r, m)
+    _chk(lib().grass_ref_scatter_update_cols(_p(W), m, n, ldw, _p(idx), _p(rho), float(alpha),
+                                             _p(U), r))
     return W
 
 

@@ -224,6 +224,43 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     }
 }
 
+// Column form of the update (right-hand projection): W[i, idx[j]] += alpha * sum over the
+// run of equal idx of rho * U[., i], with U stored r x mrows (row j contiguous along i).
+// A workgroup owns a 64 (j) x 64 (i) tile: U is read with lanes along i (coalesced), turned
+// through LDS, and W is touched with lanes along j, so that a wavefront's 64 two- or
+// four-byte read-modify-writes fall into the few cache lines that hold 64 consecutive
+// selected columns of one row of W.  The first member of a run of equal idx sums the run
+// (members beyond this tile are read from global memory), so each W element is written by
+// one thread only.
+template <typename WT>
+__global__ __launch_bounds__(256) void scatter_cols_kernel(
+    WT* __restrict__ W, int64_t ldw, int64_t mrows, const int32_t* __restrict__ idx,
+    const float* __restrict__ rho, float alpha, const float* __restrict__ U, int64_t r) {
+    __shared__ float tile[64][65];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t i0 = static_cast<int64_t>(blockIdx.x) * 64, j0 = static_cast<int64_t>(blockIdx.y) * 64;
+    for (int jj = w; jj < 64; jj += 4) {
+        const int64_t j = j0 + jj, i = i0 + lane;
+        tile[jj][lane] = (j < r && i < mrows) ? rho[j] * U[j * mrows + i] : 0.f;
+    }
+    __syncthreads();
+    const int64_t j = j0 + lane;
+    if (j >= r) return;
+    const int32_t col = idx[j];
+    if (j > 0 && idx[j - 1] == col) return;  // a later member of a run
+    int64_t run_end = j + 1;
+    while (run_end < r && idx[run_end] == col) ++run_end;
+    for (int ii = w; ii < 64; ii += 4) {
+        const int64_t i = i0 + ii;
+        if (i >= mrows) break;
+        float acc = 0.f;
+        for (int64_t jn = j; jn < run_end; ++jn)
+            acc += jn < j0 + 64 ? tile[jn - j0][ii] : rho[jn] * U[jn * mrows + i];
+        WT* wp = W + i * ldw + col;
+        store_from_f32(wp, load_as_f32(wp) + alpha * acc);
+    }
+}
+
 AdamParams make_params(float lr, float b1, float b2, float eps, int64_t t) {
     AdamParams p;
     p.b1 = b1;
@@ -325,6 +362,20 @@ grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float*
                ? adam_scatter_typed<float>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
                : adam_scatter_typed<uint16_t>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho,
                                               alpha, s);
+}
+
+grass_status launch_scatter_cols(void* W, grass_dtype wdt, int64_t mrows, int64_t ldw,
+                                 const int32_t* idx, const float* rho, float alpha, const float* U,
+                                 int64_t r, hipStream_t s) {
+    if (r == 0 || mrows == 0) return GRASS_OK;
+    const dim3 grid(static_cast<unsigned>((mrows + 63) / 64), static_cast<unsigned>((r + 63) / 64));
+    if (wdt == GRASS_F32)
+        scatter_cols_kernel<float><<<grid, 256, 0, s>>>(static_cast<float*>(W), ldw, mrows, idx, rho,
+                                                        alpha, U, r);
+    else
+        scatter_cols_kernel<uint16_t><<<grid, 256, 0, s>>>(static_cast<uint16_t*>(W), ldw, mrows,
+                                                           idx, rho, alpha, U, r);
+    return launch_status();
 }
 
 template <typename GT>

@@ -144,6 +144,17 @@ grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n
     return launch_scatter(W, wdt, n, ldw, idx, rho, alpha, U, r, as_stream(stream));
 }
 
+grass_status grass_scatter_update_cols(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
+                                       const int32_t* idx, const float* rho, float alpha,
+                                       const float* U, int64_t r, void* stream) {
+    if (m < 0 || n < 0 || r < 0 || ldw < n || (r + 63) / 64 > kMaxGridRows || (r > 0 && n == 0))
+        return GRASS_ERR_SHAPE;
+    if (!present(W, m * n) || !present(idx, r) || !present(rho, r) || !present(U, r * m))
+        return GRASS_ERR_NULL;
+    if (!dtype_ok(wdt)) return GRASS_ERR_DTYPE;
+    return launch_scatter_cols(W, wdt, m, ldw, idx, rho, alpha, U, r, as_stream(stream));
+}
+
 grass_status grass_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
                                 int64_t n, float lr, float beta1, float beta2, float eps,
                                 int64_t t, void* W, grass_dtype wdt, int64_t m, int64_t ldw,

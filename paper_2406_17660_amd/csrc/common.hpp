@@ -83,6 +83,9 @@ grass_status launch_adam_rows(const float* GC, int64_t ldgc, float* M, float* V,
 grass_status launch_scatter(void* W, grass_dtype wdt, int64_t n, int64_t ldw, const int32_t* idx,
                             const float* rho, float alpha, const float* U, int64_t r,
                             hipStream_t s);
+grass_status launch_scatter_cols(void* W, grass_dtype wdt, int64_t mrows, int64_t ldw,
+                                 const int32_t* idx, const float* rho, float alpha, const float* U,
+                                 int64_t r, hipStream_t s);
 grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
                                  int64_t n, float lr, float b1, float b2, float eps, int64_t t,
                                  void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,

@@ -25,7 +25,7 @@ EXPORTS = [
     "grass_cgrad_workspace", "grass_compressed_grad", "grass_compressed_grad_timed",
     "grass_adam_rows", "grass_scatter_update",
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
-    "grass_grad_row_stats_workspace", "grass_grad_row_stats",
+    "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
 ]
 
 _lib = None
@@ -61,6 +61,7 @@ def lib():
     L.grass_compressed_grad_timed.argtypes = L.grass_compressed_grad.argtypes + [vp, vp]
     L.grass_adam_rows.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, vp]
     L.grass_scatter_update.argtypes = [vp, i32, i64, i64, i64, vp, vp, f32, vp, i64, vp]
+    L.grass_scatter_update_cols.argtypes = L.grass_scatter_update.argtypes
     L.grass_adam_scatter.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, i32,
                                      i64, i64, vp, vp, f32, vp]
     L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
@@ -194,6 +195,17 @@ def scatter_update(W, idx, rho, alpha, U):
     _check(lib().grass_scatter_update(pW, _dtype(W), m, n, ldw, _vec(idx, torch.int32),
                                       _vec(rho, torch.float32), alpha, C.c_void_p(U.data_ptr()), r,
                                       _stream()), "grass_scatter_update")
+    return W
+
+
+def scatter_update_cols(W, idx, rho, alpha, U):
+    pW, m, n, ldw = _mat(W)
+    r = idx.shape[0]
+    assert U.shape == (r, m) and U.is_contiguous() and U.dtype == torch.float32
+    _check(lib().grass_scatter_update_cols(pW, _dtype(W), m, n, ldw, _vec(idx, torch.int32),
+                                           _vec(rho, torch.float32), alpha,
+                                           C.c_void_p(U.data_ptr()), r, _stream()),
+           "grass_scatter_update_cols")
     return W
 
 

@@ -27,11 +27,22 @@ class GrassLayer:
 
     refresh() is `compute_P` + `update_state` of Algorithm 1 (lines under "if t = 0 mod K");
     step() is the regular part (G_C, opt.update, W += alpha P Delta).
+
+    side="rows" selects r of the m rows of W (output features).  side="cols" is the right-hand
+    form for layers whose input dimension is the smaller one: r of the n columns are selected.
+    It is the row form of the transposed layer (G^T = X^T dY), so the same library calls are
+    used with dY and X exchanged; only the final update differs (columns of W).
     """
 
     def __init__(self, m, n, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, g_dtype=None,
-                 layout=grass.DY_TxM, device="cuda", materialise_G=False):
+                 layout=grass.DY_TxM, device="cuda", materialise_G=False, side="rows"):
+        assert side in ("rows", "cols")
+        self.side = side
+        self.w_shape = (m, n)
+        if side == "cols":  # work on the transposed problem: "rows" of G^T, state r x m
+            assert layout == grass.DY_TxM
+            m, n = n, m
         self.m, self.n, self.r, self.T = m, n, r, T
         self.dtype = dtype
         self.dt = grass.F32 if dtype == torch.float32 else grass.BF16
@@ -55,7 +66,11 @@ class GrassLayer:
         self.refresh_id = 0
 
     # -- refresh step -----------------------------------------------------------------
+    def _operands(self, dY, X):
+        return (X, dY) if self.side == "cols" else (dY, X)
+
     def full_gradient(self, dY, X):
+        dY, X = self._operands(dY, X)
         if self.G is None:
             self.G = torch.empty((self.m, self.n), dtype=self.g_dtype, device=X.device)
             self.ws_dense = grass.workspace(
@@ -69,6 +84,7 @@ class GrassLayer:
         if self.materialise_G:
             self.full_gradient(dY, X)
             return grass.row_stats(self.G, self.sumsq)
+        dY, X = self._operands(dY, X)
         if self.ws_stats is None:
             ldy, ldx = dY.stride(0), X.stride(0)
             self.ws_stats = grass.workspace(grass.grad_row_stats_workspace(
@@ -87,12 +103,20 @@ class GrassLayer:
 
     # -- regular step -----------------------------------------------------------------
     def compressed_grad(self, dY, X, gemm_events=None):
+        dY, X = self._operands(dY, X)
         return grass.compressed_grad(dY, X, self.idx, self.rho, self.GC, self.ws_gemm, self.layout,
                                      gemm_events)
 
     def adam_scatter(self, W):
         self.adam_t += 1
         a = self.adam
+        assert tuple(W.shape) == self.w_shape
+        if self.side == "cols":  # Adam on r x m, then the update of r columns of W
+            if not hasattr(self, "U"):
+                self.U = torch.empty_like(self.GC)
+            grass.adam_rows(self.GC, self.M, self.V, a.lr, a.beta1, a.beta2, a.eps, self.adam_t,
+                            self.U)
+            return grass.scatter_update_cols(W, self.idx, self.rho, self.alpha, self.U)
         return grass.adam_scatter(self.GC, self.M, self.V, a.lr, a.beta1, a.beta2, a.eps,
                                   self.adam_t, W, self.idx, self.rho, self.alpha)
 

@@ -112,6 +112,11 @@ def test_adam_and_scatter_validation():
     assert s(FAKE, 3, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_DTYPE
     assert s(FAKE, 0, 4, 8, 7, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_SHAPE
     assert s(FAKE, 0, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 70000, None) == grass.ERR_SHAPE
+    sc = L.grass_scatter_update_cols
+    assert sc(None, 0, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_NULL
+    assert sc(FAKE, 0, 4, 8, 8, FAKE, FAKE, 1.0, None, 2, None) == grass.ERR_NULL
+    assert sc(FAKE, 5, 4, 8, 8, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_DTYPE
+    assert sc(FAKE, 0, 4, 8, 7, FAKE, FAKE, 1.0, FAKE, 2, None) == grass.ERR_SHAPE
     f = L.grass_adam_scatter
     assert f(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None, 0, 4, 8, FAKE, FAKE, 1.0,
              None) == grass.ERR_NULL

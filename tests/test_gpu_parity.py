@@ -367,3 +367,30 @@ def test_grad_row_stats_small_workspace_is_enough_when_fused():
     """The point of the fused form: no m x n buffer.  4096 x 4096 needs well under 1 MB."""
     assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.BF16) < 1 << 20
     assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.F32) > 4096 * 4096 * 4
+
+
+# ------------------------------------------------------------------------------ column projection
+@pytest.mark.parametrize("wdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("m,n,r,dup,ldw", [(64, 64, 8, False, 64), (200, 96, 40, True, 96),
+                                           (333, 130, 130, True, 136), (1030, 512, 100, True, 512),
+                                           (70, 5461, 300, True, 5461), (5, 9, 3, False, 9)])
+def test_scatter_update_cols(wdtype, m, n, r, dup, ldw):
+    idx, rho = make_idx(n, r, 61, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    W = randn((m, n), wdtype, 62, scale=0.02, ld=ldw)
+    W0 = to_f64(W).copy()
+    W0_bits = to_np(W).copy()
+    U = randn((r, m), torch.float32, 63, scale=1e-3).contiguous()
+    grass.scatter_update_cols(W, d_idx, d_rho, 0.25, U)
+    Wo = W0.copy()
+    ref.scatter_update_cols(Wo, idx, rho, float(np.float32(0.25)), to_f64(U))
+    got = to_f64(W)
+    sel = np.unique(idx)
+    assert rel_fro(got[:, sel], Wo[:, sel]) <= tol_for(wdtype)
+    slack = 4 * 2.0 ** -24 * (np.abs(W0[:, sel]) + np.abs(Wo[:, sel] - W0[:, sel]))
+    if wdtype == torch.bfloat16:
+        assert (np.abs(got[:, sel] - Wo[:, sel]) <= 1.01 * bf16_ulp(Wo[:, sel]) + slack).all()
+    else:
+        assert (np.abs(got[:, sel] - Wo[:, sel]) <= 2.0 ** -23 * np.abs(Wo[:, sel]) + slack).all()
+    rest = np.setdiff1d(np.arange(n), sel)
+    assert np.array_equal(to_np(W)[:, rest], W0_bits[:, rest])  # other columns untouched

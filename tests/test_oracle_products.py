@@ -166,3 +166,33 @@ def test_reconstruction_identity_for_unit_scale():
         err = ((recon - G) ** 2).sum()
         rest = sorted(set(range(m)) - set(sel))
         np.testing.assert_allclose(err, ss[rest].sum(), rtol=1e-12)
+
+
+def test_column_projection_is_the_transposed_problem():
+    """Projecting the columns of G (Section 4.1 projects the smaller dimension) with an n x r matrix P:
+    G P = (P^T G^T)^T, and G^T = X^T dY is the gradient of the transposed layer, so the
+    compressed gradient is the row form with dY and X exchanged; the update is W + alpha (P U)^T."""
+    rng = np.random.default_rng(41)
+    T, m, n, r = 25, 9, 6, 4
+    dY = rng.standard_normal((T, m))
+    X = rng.standard_normal((T, n))
+    W0 = rng.standard_normal((m, n))
+    idx = np.array([0, 2, 2, 5], np.int32)  # columns of W, one duplicate
+    rho = rng.uniform(0.5, 2.0, r).astype(np.float32)
+    P = np.zeros((n, r))
+    P[idx, np.arange(r)] = rho
+    G = dY.T @ X
+    GC = ref.compressed_grad(X, dY, idx, rho)  # r x m
+    np.testing.assert_allclose(GC, (G @ P).T, rtol=1e-12, atol=1e-13)
+    U = rng.standard_normal((r, m))
+    W = W0.copy()
+    ref.scatter_update_cols(W, idx, rho, 0.25, U)
+    np.testing.assert_allclose(W, W0 + 0.25 * (P @ U).T, rtol=1e-14, atol=1e-15)
+    untouched = sorted(set(range(n)) - set(idx.tolist()))
+    assert (W[:, untouched] == W0[:, untouched]).all()
+    # hand-checkable: one column, two rows
+    W = np.zeros((2, 3))
+    ref.scatter_update_cols(W, [2], [2.0], 0.5, np.array([[1.0, -3.0]]))
+    assert W.tolist() == [[0.0, 0.0, 1.0], [0.0, 0.0, -3.0]]
+    with pytest.raises(ref.OracleError):
+        ref.scatter_update_cols(np.zeros((2, 3)), [3], [1.0], 1.0, np.zeros((1, 2)))
