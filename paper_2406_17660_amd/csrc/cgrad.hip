@@ -663,12 +663,23 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     p.rp = p.Mp;
     const int64_t ktiles = Cfg::kWholeKTilesOnly ? T / Cfg::BK : (T + Cfg::BK - 1) / Cfg::BK;
     const int64_t tiles = static_cast<int64_t>(p.tiles_m) * p.tiles_n;
-    // split K until every CU has its share of workgroups, but keep >= 8 K tiles per split
+    // Split K so that the workgroups fill whole rounds of the machine (256 CUs x workgroups
+    // per CU) without paying too much for the partial tiles every slice adds.  In units of
+    // the GEMM's time at full occupancy, c slices cost about 1 / fill(c) + c * 1400 / T: a
+    // slice writes and re-reads 8 bytes per output element at ~4 TB/s while the GEMM spends
+    // 2 T flops per output element at ~1.4 PFLOP/s (a slice of at most 16 MB stays in the
+    // caches and costs about a third of that).  Each slice keeps at least 8 K tiles.
     const int64_t slots = 256 * Cfg::kWgPerCu;
-    int64_t s = tiles > 0 ? (slots + tiles / 2) / tiles : 1;
-    const int64_t smax = ktiles / 8 > 0 ? ktiles / 8 : 1;
-    if (s > smax) s = smax;
-    if (s < 1) s = 1;
+    const int64_t smax = ktiles / 8 > 0 ? (ktiles / 8 < 128 ? ktiles / 8 : 128) : 1;
+    const bool cached = p.Mp * p.Np * 4 <= (int64_t{16} << 20);
+    const double per_slice = (cached ? 400.0 : 1400.0) / static_cast<double>(T > 0 ? T : 1);
+    int64_t s = 1;
+    double best = 1e300;
+    for (int64_t c = 1; c <= smax && tiles > 0; ++c) {
+        const int64_t wgs = tiles * c, rounds = (wgs + slots - 1) / slots;
+        const double cost = static_cast<double>(rounds * slots) / static_cast<double>(wgs) + per_slice * c;
+        if (cost < best - 1e-12) { best = cost; s = c; }
+    }
     p.ktiles_per_split = static_cast<int>((ktiles + s - 1) / s);
     if (p.ktiles_per_split < 1) p.ktiles_per_split = 1;
     p.splits = static_cast<int>((ktiles + p.ktiles_per_split - 1) / p.ktiles_per_split);

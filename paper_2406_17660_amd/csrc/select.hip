@@ -132,6 +132,7 @@ __global__ __launch_bounds__(kThreads) void select_topr_kernel(
     float* __restrict__ rho, int32_t* __restrict__ status) {
     __shared__ Shared sh;
     if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    if (r == 0) return;  // nothing to select: only the status word is written
     const int tid = threadIdx.x;
 
     // Radix select: after the four passes `prefix` is the r-th largest key and `need`
@@ -205,6 +206,7 @@ __global__ __launch_bounds__(kThreads) void select_repl_kernel(
     uint32_t* __restrict__ hits) {
     __shared__ Shared sh;
     if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    if (r == 0) return;  // nothing to select: only the status word is written
     const int tid = threadIdx.x;
 
     double wmax = 0.0;
@@ -282,6 +284,7 @@ __global__ __launch_bounds__(kThreads) void select_norepl_kernel(
     __shared__ Shared sh;
     extern __shared__ unsigned long long lds_tree[];
     if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
+    if (r == 0) return;  // nothing to select: only the status word is written
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     unsigned long long* tree = tree_in_lds ? lds_tree : ws_tree;
     if (tid < kMaxLevels) {
