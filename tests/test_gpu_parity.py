@@ -394,3 +394,17 @@ def test_scatter_update_cols(wdtype, m, n, r, dup, ldw):
         assert (np.abs(got[:, sel] - Wo[:, sel]) <= 2.0 ** -23 * np.abs(Wo[:, sel]) + slack).all()
     rest = np.setdiff1d(np.arange(n), sel)
     assert np.array_equal(to_np(W)[:, rest], W0_bits[:, rest])  # other columns untouched
+
+
+@pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 192, 224, 256, 288, 1056])
+def test_large_tile_kernel_every_pipeline_length(monkeypatch, T):
+    """1 to 9 and 33 K tiles per workgroup: prologue, steady state and drain of the LDS ring."""
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    m, n, r = 300, 264, 260
+    dY = randn((T, m), torch.bfloat16, 71, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 72)
+    idx, rho = make_idx(m, r, 73, False)
+    got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert rel_fro(got, want) <= 2e-5
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
