@@ -37,8 +37,6 @@ struct Shared {
     uint32_t prefix;
     uint32_t need;
     int bad;
-    long long level_offset[kMaxLevels];  // sum-tree geometry (sampling without replacement)
-    long long level_count[kMaxLevels];
 };
 
 __device__ __forceinline__ uint32_t key_of(float s) { return s == 0.0f ? 0u : __float_as_uint(s); }
@@ -270,27 +268,93 @@ __global__ __launch_bounds__(kThreads) void select_repl_kernel(
 }
 
 // ------------------------------------------------------------------------------ without replacement
+// Sampling without replacement is r sequential draws from the weights that are left (the
+// weight of a drawn row is taken out before the next draw).  The weights sit in a radix-64
+// tree whose nodes store, instead of their own sum, the INCLUSIVE PREFIX of the sums inside
+// their group of 64 siblings.  One wavefront then walks a draw down the tree with one load,
+// one compare and one ballot per level (the first lane whose prefix exceeds the target is
+// the child to enter; the prefix of the lane before it is what the target loses), and takes
+// the drawn weight w out by subtracting w from the prefixes at and after the path's lane in
+// each of the path's groups.  Every value is an exact integer, so the draws are those of the
+// sequential definition.  Every level is padded to whole groups; padding carries weight 0.
 struct TreeShape {
-    int levels;                 // level 0 = leaves
-    int64_t count[kMaxLevels];  // nodes per level
-    int64_t offset[kMaxLevels]; // start of the level inside the node array
+    int levels;                  // level 0 = leaves
+    int64_t groups[kMaxLevels];  // groups of 64 entries per level (the top level has one)
+    int64_t offset[kMaxLevels];  // first entry of the level inside the node array
 };
 
+__device__ __forceinline__ unsigned long long read_lane64(unsigned long long v, int l) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(v), l);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(v >> 32), l);
+    return (static_cast<unsigned long long>(hi) << 32) | lo;
+}
+
+// The r draws, by one wavefront.  TreePtr is an LDS or a global pointer; kFence orders the
+// updates of a global tree before the next draw's loads.
+template <int LEVELS, bool kFence, typename TreePtr>
+__device__ __forceinline__ void draw_without_replacement(TreePtr tree, const TreeShape& shape,
+                                                         int64_t r, unsigned long long seed,
+                                                         unsigned long long refresh,
+                                                         unsigned long long total_w, int lane) {
+    unsigned long long remaining = total_w;
+    for (int64_t j0 = 0; j0 < r; j0 += kWave) {
+        // the Philox words of the next 64 draws, one per lane
+        const unsigned long long words = draw_word(seed, refresh, static_cast<unsigned long long>(j0 + lane));
+        const int in_block = r - j0 < kWave ? static_cast<int>(r - j0) : kWave;
+        for (int jj = 0; jj < in_block; ++jj) {
+            unsigned long long target = __umul64hi(read_lane64(words, jj), remaining);
+            unsigned long long prefix[LEVELS];
+            int64_t entry[LEVELS];
+            int first[LEVELS];
+            unsigned long long w = 0;
+            int64_t node = 0;
+#pragma unroll
+            for (int L = LEVELS - 1; L >= 0; --L) {
+                entry[L] = shape.offset[L] + node * kWave + lane;
+                prefix[L] = tree[entry[L]];
+                const unsigned long long hit = __ballot(prefix[L] > target);
+                const int f = __ffsll(static_cast<long long>(hit)) - 1;  // hit != 0: target < total
+                const unsigned long long before = f > 0 ? read_lane64(prefix[L], f - 1) : 0ull;
+                if (L == 0) w = read_lane64(prefix[0], f) - before;  // the leaf drawn
+                target -= before;
+                first[L] = f;
+                node = node * kWave + f;
+            }
+#pragma unroll
+            for (int L = 0; L < LEVELS; ++L)
+                if (lane >= first[L]) tree[entry[L]] = prefix[L] - w;
+            remaining -= w;
+            if (kFence) __threadfence_block();
+        }
+    }
+}
+
+template <bool kFence, typename TreePtr>
+__device__ __forceinline__ void draw_dispatch(TreePtr tree, const TreeShape& shape, int64_t r,
+                                              unsigned long long seed, unsigned long long refresh,
+                                              unsigned long long total_w, int lane) {
+    switch (shape.levels) {
+        case 1: draw_without_replacement<1, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+        case 2: draw_without_replacement<2, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+        case 3: draw_without_replacement<3, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+        case 4: draw_without_replacement<4, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+        case 5: draw_without_replacement<5, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+        default: draw_without_replacement<6, kFence>(tree, shape, r, seed, refresh, total_w, lane); break;
+    }
+}
+
+template <bool kTreeInLds>
 __global__ __launch_bounds__(kThreads) void select_norepl_kernel(
     const float* __restrict__ sumsq, int64_t m, int64_t r, int method, int rescale,
     unsigned long long seed, unsigned long long refresh, int32_t* __restrict__ idx,
     float* __restrict__ rho, int32_t* __restrict__ status, unsigned long long* ws_tree,
-    TreeShape shape, int tree_in_lds) {
+    TreeShape shape) {
     __shared__ Shared sh;
     extern __shared__ unsigned long long lds_tree[];
     if (reject_nonfinite(sumsq, m, r, idx, rho, status, &sh)) return;
     if (r == 0) return;  // nothing to select: only the status word is written
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    unsigned long long* tree = tree_in_lds ? lds_tree : ws_tree;
-    if (tid < kMaxLevels) {
-        sh.level_offset[tid] = tid < shape.levels ? shape.offset[tid] : 0;
-        sh.level_count[tid] = tid < shape.levels ? shape.count[tid] : 0;
-    }
+    unsigned long long* tree = kTreeInLds ? lds_tree : ws_tree;
 
     double wmax = 0.0;
     for (int64_t k = tid; k < m; k += kThreads) {
@@ -299,47 +363,29 @@ __global__ __launch_bounds__(kThreads) void select_norepl_kernel(
     }
     wmax = block_max(wmax, &sh);
 
-    for (int64_t k = tid; k < m; k += kThreads) tree[k] = quantise(weight_of(sumsq[k], method), wmax);
+    // padding entries of the inner levels (children that do not exist) weigh 0
+    for (int L = 1; L < shape.levels; ++L)
+        for (int64_t e = shape.groups[L - 1] + tid; e < shape.groups[L] * kWave; e += kThreads)
+            tree[shape.offset[L] + e] = 0ull;
     __threadfence_block();
     __syncthreads();
-    // inner levels: one wavefront sums the 64 children of a node
-    for (int L = 1; L < shape.levels; ++L) {
-        const unsigned long long* child = tree + shape.offset[L - 1];
-        for (int64_t node = wave; node < shape.count[L]; node += kWaves) {
-            const int64_t c = node * kWave + lane;
-            unsigned long long v = c < shape.count[L - 1] ? child[c] : 0ull;
-#pragma unroll
-            for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-            if (lane == 0) tree[shape.offset[L] + node] = v;
+    // level by level: prefix sums inside each group; the group's sum goes up one level
+    for (int L = 0; L < shape.levels; ++L) {
+        for (int64_t g = wave; g < shape.groups[L]; g += kWaves) {
+            const int64_t e = g * kWave + lane;
+            unsigned long long v;
+            if (L == 0) v = e < m ? quantise(weight_of(sumsq[e], method), wmax) : 0ull;
+            else v = tree[shape.offset[L] + e];
+            v = wave_inclusive_scan(v);
+            tree[shape.offset[L] + e] = v;
+            if (lane == kWave - 1 && L + 1 < shape.levels) tree[shape.offset[L + 1] + g] = v;
         }
         __threadfence_block();
         __syncthreads();
     }
-    // total weight = sum of the (at most 64) top-level nodes
-    const int top = shape.levels - 1;
-    unsigned long long total_w = 0;
-    for (int64_t i = 0; i < shape.count[top]; ++i) total_w += tree[shape.offset[top] + i];
+    const unsigned long long total_w = tree[shape.offset[shape.levels - 1] + kWave - 1];
 
-    if (wave == 0) {
-        unsigned long long remaining = total_w;
-        for (int64_t j = 0; j < r; ++j) {
-            unsigned long long target = __umul64hi(draw_word(seed, refresh, j), remaining);
-            int64_t node = 0;
-            for (int L = top; L >= 0; --L) {
-                const int64_t c = node * kWave + lane;  // node = 0 at the top level
-                const unsigned long long v = c < shape.count[L] ? tree[shape.offset[L] + c] : 0ull;
-                const unsigned long long incl = wave_inclusive_scan(v);
-                const unsigned long long hit = __ballot(incl > target);
-                const int f = __ffsll(static_cast<long long>(hit)) - 1;  // hit != 0: target < sum
-                target -= __shfl(incl - v, f, kWave);
-                node = node * kWave + f;
-            }
-            const unsigned long long w = tree[node];  // the leaf drawn
-            if (lane <= top) tree[sh.level_offset[lane] + (node >> (6 * lane))] -= w;
-            remaining -= w;
-            __threadfence_block();
-        }
-    }
+    if (wave == 0) draw_dispatch<!kTreeInLds>(tree, shape, r, seed, refresh, total_w, lane);
     __threadfence_block();
     __syncthreads();
 
@@ -347,7 +393,12 @@ __global__ __launch_bounds__(kThreads) void select_norepl_kernel(
     uint32_t carry = 0;
     for (int64_t base = 0; base < m; base += kThreads) {
         const int64_t k = base + tid;
-        const uint32_t chosen = (k < m && tree[k] == 0ull) ? 1u : 0u;
+        uint32_t chosen = 0;
+        if (k < m) {
+            const unsigned long long here = tree[k];  // level 0 starts at offset 0
+            const unsigned long long before = (k & (kWave - 1)) ? tree[k - 1] : 0ull;
+            chosen = here == before ? 1u : 0u;
+        }
         uint32_t total;
         const uint32_t pos = carry + block_exclusive_scan(chosen, &sh, total);
         if (chosen) {
@@ -367,20 +418,21 @@ __global__ __launch_bounds__(kThreads) void select_norepl_kernel(
 TreeShape tree_shape(int64_t m) {
     TreeShape s;
     s.levels = 0;
-    int64_t cnt = m > 0 ? m : 1, off = 0;
+    int64_t groups = m > 0 ? (m + kWave - 1) / kWave : 1, off = 0;
     while (true) {
-        s.count[s.levels] = cnt;
+        s.groups[s.levels] = groups;
         s.offset[s.levels] = off;
         ++s.levels;
-        if (cnt <= kWave || s.levels == kMaxLevels) break;
-        off += cnt;
-        cnt = (cnt + kWave - 1) / kWave;
+        if (groups == 1 || s.levels == kMaxLevels) break;
+        off += groups * kWave;
+        groups = (groups + kWave - 1) / kWave;
     }
     return s;
 }
 
 size_t tree_bytes(const TreeShape& s) {
-    return static_cast<size_t>(s.offset[s.levels - 1] + s.count[s.levels - 1]) * sizeof(unsigned long long);
+    return static_cast<size_t>(s.offset[s.levels - 1] + s.groups[s.levels - 1] * kWave) *
+           sizeof(unsigned long long);
 }
 
 }  // namespace
@@ -413,18 +465,19 @@ grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_metho
     }
     const TreeShape shape = tree_shape(m);
     const size_t bytes = tree_bytes(shape);
-    const int in_lds = bytes <= kLdsTreeBytes;
-    const size_t dyn = in_lds ? bytes : 0;
-    if (dyn > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(select_norepl_kernel),
+    unsigned long long* ws_tree = reinterpret_cast<unsigned long long*>(body);
+    if (bytes <= kLdsTreeBytes) {
+        if (bytes > 48 * 1024 &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(select_norepl_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(dyn)) != hipSuccess)
+                                static_cast<int>(bytes)) != hipSuccess)
             return GRASS_ERR_DEVICE;
+        select_norepl_kernel<true><<<1, kThreads, bytes, s>>>(
+            sumsq, m, r, method, rescale, seed, refresh_id, idx, rho, status, ws_tree, shape);
+    } else {
+        select_norepl_kernel<false><<<1, kThreads, 0, s>>>(
+            sumsq, m, r, method, rescale, seed, refresh_id, idx, rho, status, ws_tree, shape);
     }
-    select_norepl_kernel<<<1, kThreads, dyn, s>>>(sumsq, m, r, method, rescale, seed, refresh_id,
-                                                  idx, rho, status,
-                                                  reinterpret_cast<unsigned long long*>(body),
-                                                  shape, in_lds);
     return launch_status();
 }
 
