@@ -40,6 +40,9 @@ def parse():
     p.add_argument("--tokens", type=int, default=None, help="override T (debug)")
     p.add_argument("--side", choices=["rows", "cols"], default="rows",
                    help="rows: select r rows of W (default); cols: right-hand projection, r columns")
+    p.add_argument("--block", choices=sorted(workloads.BLOCKS), default=None,
+                   help="time Algorithm 1 over all seven linear layers of one LLaMA block "
+                        "(grouped q/k/v and gate/up calls) instead of the single layer")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
     p.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -122,6 +125,45 @@ def measured_traffic(layer_name, T):
     return rec["bytes_per_launch"] if rec else None
 
 
+def bench_block(args, cfg):
+    """Amortised block steps/s: every layer of one block, refresh every 200 steps, the
+    re-warm-up schedule supplying the learning rate.  A secondary measurement: the headline
+    metric stays the single layer step."""
+    from paper_2406_17660_amd.block import GrassBlock, RewarmSchedule
+    hidden, inter = workloads.BLOCKS[args.block]
+    T = args.tokens or cfg.T
+    shapes, groups = workloads.llama_block(hidden, inter)
+    dY, X, W = workloads.make_block_inputs(cfg, shapes, groups, "cuda", T=T)
+    blk = GrassBlock(shapes, groups, cfg.r, T, cfg.dtype, cfg.method, cfg.replacement,
+                     alpha=cfg.alpha, adam=AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps),
+                     seed=workloads.BASE_SEED)
+    sched = RewarmSchedule(base_lr=cfg.lr, K=REFRESH_EVERY, rewarm=REFRESH_EVERY)
+    blk.refresh(dY, X)  # set-up: refresh-step workspaces are allocated outside the timed region
+    for _ in range(args.warmup):
+        blk.step(dY, X, W)
+    torch.cuda.synchronize()
+    blk.t = 0
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(args.steps):
+        blk.train_step(dY, X, W, sched)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b)
+    flops = sum(2.0 * l.r * T * l.n for l in blk.layers.values())
+    print(json.dumps({
+        "metric": "GRASS block steps/s (7 linear layers, refresh every 200 steps included)",
+        "value": args.steps / (ms * 1e-3), "unit": "block-steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": f"LLaMA-{args.block} block: q,k,v,o {hidden}x{hidden}, gate,up "
+                               f"{inter}x{hidden}, down {hidden}x{inter}; T={T}, r={cfg.r}, "
+                               f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection"},
+        "compressed_grad_tflops_incl_gather_and_reduce_and_adam": flops * args.steps / (ms * 1e-3) / 1e12,
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -132,6 +174,8 @@ def main():
     torch.cuda.set_device(0)
     grass.lib()
     cfg = workloads.CONFIGS[args.config]
+    if args.block:
+        return bench_block(args, cfg)
     L = cfg.layers[args.layer]
     T = args.tokens or cfg.T
     m, n, r = L.m, L.n, cfg.r

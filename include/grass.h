@@ -148,6 +148,32 @@ grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout,
                                          void* ev_gemm_stop);
 
 /* ---------------------------------------------------------------------------
+ * Compressed gradients of several weight matrices that read the same activations
+ * (the query, key and value projections of an attention block, or the gate and up
+ * projections of an MLP: Section 4 trains all linear layers of a block).  For set
+ * i < count:
+ *   GC[i][j, c] = rho[i][j] * sum_t dY[i][t, idx[i][j]] * X[t, c],  j < r[i], c < n,
+ * exactly what grass_compressed_grad returns for (dY[i], idx[i], rho[i]) alone; the
+ * selected rows of all sets are gathered into one panel and multiplied with X in a
+ * single pass over X.
+ * dY, ldy, m, r, idx, rho, GC, ldgc are HOST arrays of `count` entries (1 <= count
+ * <= GRASS_MAX_GROUP); the entries of dY, idx, rho and GC are device pointers.  All
+ * sets share T, n, dt, layout, X and the stream.  Each GC[i] is fp32, r[i] x n,
+ * leading dimension ldgc[i]; the outputs must not overlap.  `ws` must hold
+ * grass_cgrad_group_workspace(...) bytes.
+ * Errors: NULL, SHAPE (also count out of range), DTYPE, WORKSPACE. */
+#define GRASS_MAX_GROUP 8
+size_t grass_cgrad_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
+                                   grass_dtype dt, grass_dy_layout layout);
+grass_status grass_compressed_grad_group(int count, const void* const* dY, grass_dy_layout layout,
+                                         const int64_t* ldy, const void* X, int64_t ldx,
+                                         grass_dtype dt, int64_t T, const int64_t* m, int64_t n,
+                                         const int64_t* r, const int32_t* const* idx,
+                                         const float* const* rho, float* const* GC,
+                                         const int64_t* ldgc, void* ws, size_t ws_bytes,
+                                         void* stream);
+
+/* ---------------------------------------------------------------------------
  * opt.update = Adam on the r x n compressed gradient (Appendix A, adam.update):
  *   M <- b1*M + (1-b1)*g        V <- b2*V + (1-b2)*g^2
  *   U  = -lr * (M/(1-b1^t)) / (sqrt(V/(1-b2^t)) + eps)

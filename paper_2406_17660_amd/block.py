@@ -1,0 +1,107 @@
+"""Algorithm 1 over the linear layers of one transformer block, and the step schedule around it.
+
+Layers that read the same activations (query/key/value; gate/up) form a group whose compressed
+gradients come from one library call, `grass_compressed_grad_group`.  The schedule is the host
+side of Section 3.3 ("Updating the Optimizer State") and Appendix "Pretraining" details: the
+projection is recomputed every K steps, the Adam moments may be zeroed at that point, and the
+learning rate is warmed up again after every recomputation.  Only call order and scalar
+bookkeeping live here; all array arithmetic is in the HIP library.
+"""
+import math
+from dataclasses import dataclass
+
+import torch
+
+from . import grass
+from .layer import AdamHyper, GrassLayer
+
+
+@dataclass
+class RewarmSchedule:
+    """Learning rate at optimiser step t (0-based).
+
+    global part: linear warm-up over `warmup` steps to `base_lr`, then cosine decay to
+    `min_ratio * base_lr` at `total` steps (the pretraining recipe of the paper's appendix:
+    1000 warm-up steps, decay to 10 %).
+    local part: after every projection update (steps t = 0, K, 2K, ...) the rate is ramped
+    again over `rewarm` steps.  The paper gives the length of that ramp (200 steps) but not
+    its shape; a linear ramp (s + 1) / rewarm, s = steps since the update, is used here.
+    """
+    base_lr: float = 1e-3
+    warmup: int = 1000
+    total: int = 10000
+    min_ratio: float = 0.1
+    K: int = 200
+    rewarm: int = 200
+
+    def global_factor(self, t: int) -> float:
+        if self.warmup > 0 and t < self.warmup:
+            return (t + 1) / self.warmup
+        span = max(self.total - self.warmup, 1)
+        x = min(max(t - self.warmup, 0), span) / span
+        return self.min_ratio + (1.0 - self.min_ratio) * 0.5 * (1.0 + math.cos(math.pi * x))
+
+    def local_factor(self, t: int) -> float:
+        if self.rewarm <= 0 or self.K <= 0:
+            return 1.0
+        return min(1.0, (t % self.K + 1) / self.rewarm)
+
+    def lr(self, t: int) -> float:
+        return self.base_lr * self.global_factor(t) * self.local_factor(t)
+
+    def is_refresh(self, t: int) -> bool:
+        return self.K > 0 and t % self.K == 0
+
+
+class GrassBlock:
+    """The GRASS-trained linear layers of one block.
+
+    shapes: {name: (m, n)}; groups: list of tuples of names, each tuple sharing one X (and so
+    one n).  A layer outside every tuple is a group of its own.  All layers select rows.
+    """
+
+    def __init__(self, shapes, groups, r, T, dtype, method="topr", replacement=False,
+                 scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, device="cuda",
+                 reset_state=True):
+        self.adam = adam or AdamHyper()
+        self.reset_state = reset_state
+        named = [n for g in groups for n in g]
+        assert len(set(named)) == len(named) and set(named) <= set(shapes)
+        self.groups = [tuple(g) for g in groups] + [(n,) for n in shapes if n not in named]
+        self.layers = {}
+        for k, (name, (m, n)) in enumerate(shapes.items()):
+            self.layers[name] = GrassLayer(m, n, min(r, m), T, dtype, method, replacement, scale,
+                                           alpha, self.adam, seed + k, device=device)
+        self.ws = {}
+        dt = grass.F32 if dtype == torch.float32 else grass.BF16
+        for g in self.groups:
+            ns = {self.layers[name].n for name in g}
+            assert len(ns) == 1, "layers of a group read the same activations"
+            rs = [self.layers[name].r for name in g]
+            self.ws[g] = grass.workspace(grass.cgrad_group_workspace(T, ns.pop(), rs, dt), device)
+        self.t = 0
+
+    def refresh(self, dY, X):
+        """compute_P (+ update_state) for every layer.  dY: {name: tensor}, X: {group: tensor}."""
+        for g in self.groups:
+            for name in g:
+                self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state)
+
+    def step(self, dY, X, W, lr=None):
+        """One regular step of every layer: grouped G_C, then Adam and the row update."""
+        for g in self.groups:
+            members = [self.layers[name] for name in g]
+            grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
+                                        [l.rho for l in members], [l.GC for l in members],
+                                        self.ws[g])
+            for name, l in zip(g, members):
+                if lr is not None:
+                    l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
+                l.adam_scatter(W[name])
+
+    def train_step(self, dY, X, W, schedule: RewarmSchedule):
+        """Step t of Algorithm 1 under `schedule`: refresh when t = 0 mod K, then update."""
+        if schedule.is_refresh(self.t):
+            self.refresh(dY, X)
+        self.step(dY, X, W, schedule.lr(self.t))
+        self.t += 1

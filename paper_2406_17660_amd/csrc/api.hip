@@ -126,6 +126,39 @@ grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout,
                           static_cast<hipEvent_t>(ev_gemm_stop));
 }
 
+size_t grass_cgrad_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
+                                   grass_dtype dt, grass_dy_layout layout) {
+    if (T < 0 || n < 0 || count < 1 || count > GRASS_MAX_GROUP || !r) return 0;
+    for (int i = 0; i < count; ++i)
+        if (r[i] < 0 || r[i] > kMaxGridRows) return 0;
+    return gemm_group_workspace_bytes(T, r, count, n, dt, layout);
+}
+
+grass_status grass_compressed_grad_group(int count, const void* const* dY, grass_dy_layout layout,
+                                         const int64_t* ldy, const void* X, int64_t ldx,
+                                         grass_dtype dt, int64_t T, const int64_t* m, int64_t n,
+                                         const int64_t* r, const int32_t* const* idx,
+                                         const float* const* rho, float* const* GC,
+                                         const int64_t* ldgc, void* ws, size_t ws_bytes,
+                                         void* stream) {
+    if (count < 1 || count > GRASS_MAX_GROUP) return GRASS_ERR_SHAPE;
+    if (!dY || !ldy || !m || !r || !idx || !rho || !GC || !ldgc) return GRASS_ERR_NULL;
+    GemmSegment seg[GRASS_MAX_GROUP];
+    for (int i = 0; i < count; ++i) {
+        const grass_status st = check_products(dY[i], layout, ldy[i], X, ldx, dt, T, m[i], n);
+        if (st != GRASS_OK) return st;
+        if (r[i] < 0 || r[i] > kMaxGridRows || ldgc[i] < n || (r[i] > 0 && m[i] == 0))
+            return GRASS_ERR_SHAPE;
+        if (!present(idx[i], r[i]) || !present(rho[i], r[i]) || !present(GC[i], r[i] * n))
+            return GRASS_ERR_NULL;
+        seg[i] = GemmSegment{dY[i], ldy[i], idx[i], rho[i], GC[i], ldgc[i], r[i]};
+    }
+    const size_t need = gemm_group_workspace_bytes(T, r, count, n, dt, layout);
+    if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
+    return launch_tn_gemm_segments(seg, count, layout, X, ldx, dt, T, n, GRASS_F32, ws,
+                                   as_stream(stream));
+}
+
 grass_status grass_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
                              int64_t n, float lr, float beta1, float beta2, float eps, int64_t t,
                              float* U, void* stream) {

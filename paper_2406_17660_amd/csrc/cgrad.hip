@@ -45,12 +45,13 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
 }
 
 // ------------------------------------------------------------------------------ pack
-// out[t, j] = dY[t, idx[j]] (j < r), 0 for r <= j < rp.  Thread = 4 adjacent j, loops over
+// out[t, j] = dY[t, idx[j]] (j < r), 0 for r <= j < rp; rows of `out` are ldo apart (several
+// matrices may fill adjacent column ranges of one panel).  Thread = 4 adjacent j, loops over
 // kPackRows values of t; wave stores are contiguous 512 B.
 constexpr int kPackRows = 16;
 __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restrict__ dY, int64_t ldy,
                                                        int64_t T, const int32_t* __restrict__ idx,
-                                                       int64_t r, int64_t rp,
+                                                       int64_t r, int64_t rp, int64_t ldo,
                                                        uint16_t* __restrict__ out) {
     const int64_t j0 = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
     if (j0 >= rp) return;
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restric
         uint2 w;
         w.x = v[0] | (static_cast<uint32_t>(v[1]) << 16);
         w.y = v[2] | (static_cast<uint32_t>(v[3]) << 16);
-        *reinterpret_cast<uint2*>(out + t * rp + j0) = w;
+        *reinterpret_cast<uint2*>(out + t * ldo + j0) = w;
     }
 }
 
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restric
 // a 64 x 64 LDS tile so that both the reads (along t) and the writes (along j) coalesce.
 __global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restrict__ dYt, int64_t ldy,
                                                        int64_t T, const int32_t* __restrict__ idx,
-                                                       int64_t r, int64_t rp,
+                                                       int64_t r, int64_t rp, int64_t ldo,
                                                        uint16_t* __restrict__ out) {
     __shared__ uint16_t tile[64][66];
     const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restric
     __syncthreads();
     for (int tt = w; tt < 64; tt += 4) {
         const int64_t t = t0 + tt, j = j0 + lane;
-        if (t < T && j < rp) out[t * rp + j] = tile[lane][tt];
+        if (t < T && j < rp) out[t * ldo + j] = tile[lane][tt];
     }
 }
 
@@ -653,6 +654,9 @@ struct Plan {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// A slice of partial tiles up to this size is re-read from the caches by the reduction.
+constexpr int64_t kCachedSliceBytes = int64_t{16} << 20;
+
 template <typename Cfg>
 Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     Plan p;
@@ -671,7 +675,7 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     // caches and costs about a third of that).  Each slice keeps at least 8 K tiles.
     const int64_t slots = 256 * Cfg::kWgPerCu;
     const int64_t smax = ktiles / 8 > 0 ? (ktiles / 8 < 128 ? ktiles / 8 : 128) : 1;
-    const bool cached = p.Mp * p.Np * 4 <= (int64_t{16} << 20);
+    const bool cached = p.Mp * p.Np * 4 <= kCachedSliceBytes;
     const double per_slice = (cached ? 400.0 : 1400.0) / static_cast<double>(T > 0 ? T : 1);
     int64_t s = 1;
     double best = 1e300;
@@ -798,43 +802,83 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
     return (wa > wb ? wa : wb) + 256;
 }
 
-grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
-                            int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
-                            const int32_t* idx, const float* rho, void* C, grass_dtype odt,
-                            int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start,
-                            hipEvent_t ev_stop) {
-    if (mrows == 0 || n == 0) return GRASS_OK;
-    if (mrows > 65535) return GRASS_ERR_SHAPE;
+size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
+                                  grass_dtype dt, grass_dy_layout layout) {
+    int64_t total = 0;
+    size_t need = 0;  // the sets may also be run one at a time
+    for (int i = 0; i < count; ++i) {
+        total += (rows[i] + 7) / 8 * 8;
+        const size_t one = gemm_workspace_bytes(T, rows[i], n, dt, layout, true);
+        need = one > need ? one : need;
+    }
+    const size_t joint = gemm_workspace_bytes(T, total, n, dt, layout, true);
+    return joint > need ? joint : need;
+}
+
+// C_i = scale_i * (A_i^T X) for `count` row sets that share X.  The sets are packed side by
+// side into one panel (each starts at a multiple of 8 columns), one GEMM covers the panel,
+// and the partial tiles are reduced into each set's own output.
+grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy_layout layout,
+                                     const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                     int64_t n, grass_dtype odt, void* ws, hipStream_t s,
+                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
+    int64_t total = 0;  // panel columns in use
+    for (int i = 0; i < count; ++i) {
+        if (seg[i].rows > 65535) return GRASS_ERR_SHAPE;
+        total += count > 1 ? (seg[i].rows + 7) / 8 * 8 : seg[i].rows;
+    }
+    if (total == 0 || n == 0) return GRASS_OK;
     if (dt == GRASS_F32) {
-        const dim3 grid(static_cast<unsigned>((n + 63) / 64), static_cast<unsigned>((mrows + 63) / 64));
         if (ev_start) (void)hipEventRecord(ev_start, s);
-        if (odt == GRASS_F32)
-            tn_gemm_f32_kernel<float><<<grid, 256, 0, s>>>(
-                static_cast<const float*>(dY), layout, ldy, static_cast<const float*>(X), ldx, T,
-                mrows, n, idx, rho, static_cast<float*>(C), ldc);
-        else
-            tn_gemm_f32_kernel<uint16_t><<<grid, 256, 0, s>>>(
-                static_cast<const float*>(dY), layout, ldy, static_cast<const float*>(X), ldx, T,
-                mrows, n, idx, rho, static_cast<uint16_t*>(C), ldc);
+        for (int i = 0; i < count; ++i) {
+            const GemmSegment& g = seg[i];
+            if (g.rows == 0) continue;
+            const dim3 grid(static_cast<unsigned>((n + 63) / 64), static_cast<unsigned>((g.rows + 63) / 64));
+            if (odt == GRASS_F32)
+                tn_gemm_f32_kernel<float><<<grid, 256, 0, s>>>(
+                    static_cast<const float*>(g.dY), layout, g.ldy, static_cast<const float*>(X),
+                    ldx, T, g.rows, n, g.idx, g.rho, static_cast<float*>(g.C), g.ldc);
+            else
+                tn_gemm_f32_kernel<uint16_t><<<grid, 256, 0, s>>>(
+                    static_cast<const float*>(g.dY), layout, g.ldy, static_cast<const float*>(X),
+                    ldx, T, g.rows, n, g.idx, g.rho, static_cast<uint16_t*>(g.C), g.ldc);
+        }
         if (ev_stop) (void)hipEventRecord(ev_stop, s);
         return launch_status();
     }
 
-    const bool gathered = idx != nullptr;
+    const bool gathered = count > 1 || seg[0].idx != nullptr;
     const bool pack = needs_pack(layout, gathered);
-    TileId tile = choose_tile(T, mrows, n);
+    if (count > 1) {
+        // One panel pays off while a slice of partial tiles of the joint problem still fits
+        // the caches (fewer, fuller launches).  Beyond that every set fills the machine on its
+        // own and the joint partial tiles would only spill to HBM: run the sets one by one.
+        const Plan joint = plan_for(choose_tile(T, total, n), T, total, n, pack);
+        if (joint.Mp * joint.Np * 4 > kCachedSliceBytes) {
+            for (int i = 0; i < count; ++i) {
+                const grass_status st = launch_tn_gemm_segments(
+                    seg + i, 1, layout, X, ldx, dt, T, n, odt, ws, s, i == 0 ? ev_start : nullptr,
+                    i + 1 == count ? ev_stop : nullptr);
+                if (st != GRASS_OK) return st;
+            }
+            return GRASS_OK;
+        }
+    }
+    const void* dY0 = seg[0].dY;  // read directly by the GEMM only when nothing is packed
+    const int64_t ldy0 = seg[0].ldy;
+    TileId tile = choose_tile(T, total, n);
     {   // the large-tile kernel moves whole aligned 16-byte chunks only
-        const bool a_ok = pack || (aligned_to(dY, 16) && ldy % 8 == 0 && mrows % 8 == 0);
+        const bool a_ok = pack || (aligned_to(dY0, 16) && ldy0 % 8 == 0 && total % 8 == 0);
         const bool b_ok = aligned_to(X, 16) && ldx % 8 == 0 && n % 8 == 0;
         // per-lane byte offsets inside one K tile are kept in 32 bits
-        const int64_t lda_eff = pack ? (mrows + kFastBM - 1) / kFastBM * kFastBM : ldy;
+        const int64_t lda_eff = pack ? (total + kFastBM - 1) / kFastBM * kFastBM : ldy0;
         const bool off_ok = (kFastBK + 1) * lda_eff * 2 < (int64_t{1} << 32) &&
                             (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
-        if (!(a_ok && b_ok && off_ok && T >= kFastBK && mrows >= 8 && n >= 8)) tile = kTile128;
+        if (!(a_ok && b_ok && off_ok && T >= kFastBK && total >= 8 && n >= 8)) tile = kTile128;
     }
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
     const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
-    const Plan p = plan_for(tile, T, mrows, n, pack);  // sized for all T rows; K tiling per tile kind
+    const Plan p = plan_for(tile, T, total, n, pack);  // sized for all T rows; K tiling per tile kind
     char* base = static_cast<char*>(ws);
     base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
     uint16_t* panel = reinterpret_cast<uint16_t*>(base);
@@ -842,27 +886,36 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
 
     GemmArgs g;
     if (pack) {
-        if (T > 0) {
-            if (layout == GRASS_DY_TxM) {
-                const dim3 grid(static_cast<unsigned>((p.rp + 1023) / 1024),
-                                static_cast<unsigned>((T + kPackRows - 1) / kPackRows));
-                pack_txm_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(dY), ldy, T, idx,
-                                                     mrows, p.rp, panel);
-            } else {
-                const dim3 grid(static_cast<unsigned>(p.rp / 64), static_cast<unsigned>((T + 63) / 64));
-                pack_mxt_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(dY), ldy, T, idx,
-                                                     mrows, p.rp, panel);
+        int64_t off = 0;
+        for (int i = 0; i < count && T > 0; ++i) {
+            // the last set also zero-fills the panel's padding columns
+            const int64_t width = i + 1 == count ? p.rp - off : (seg[i].rows + 7) / 8 * 8;
+            if (width > 0) {
+                if (layout == GRASS_DY_TxM) {
+                    const dim3 grid(static_cast<unsigned>((width + 1023) / 1024),
+                                    static_cast<unsigned>((T + kPackRows - 1) / kPackRows));
+                    pack_txm_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(seg[i].dY),
+                                                         seg[i].ldy, T, seg[i].idx, seg[i].rows,
+                                                         width, p.rp, panel + off);
+                } else {
+                    const dim3 grid(static_cast<unsigned>((width + 63) / 64),
+                                    static_cast<unsigned>((T + 63) / 64));
+                    pack_mxt_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(seg[i].dY),
+                                                         seg[i].ldy, T, seg[i].idx, seg[i].rows,
+                                                         width, p.rp, panel + off);
+                }
             }
+            off += width;
         }
         g.A = panel;
         g.lda = p.rp;
         g.Mcols = p.rp;
         g.a_fast = 1;
     } else {
-        g.A = static_cast<const uint16_t*>(dY);
-        g.lda = ldy;
-        g.Mcols = mrows;
-        g.a_fast = aligned_to(dY, 16) && ldy % 8 == 0;
+        g.A = static_cast<const uint16_t*>(dY0);
+        g.lda = ldy0;
+        g.Mcols = total;
+        g.a_fast = aligned_to(dY0, 16) && ldy0 % 8 == 0;
     }
     g.B = static_cast<const uint16_t*>(X);
     g.ldb = ldx;
@@ -914,14 +967,31 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
         ++slices;
     }
 
-    const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(mrows));
-    if (odt == GRASS_F32)
-        splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(partial, slices, p.Mp, p.Np, mrows, n,
-                                                          rho, static_cast<float*>(C), ldc);
-    else
-        splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(partial, slices, p.Mp, p.Np, mrows,
-                                                             n, rho, static_cast<uint16_t*>(C), ldc);
+    int64_t off = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmSegment& q = seg[i];
+        if (q.rows > 0) {
+            const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
+            const float* part = partial + off * p.Np;
+            if (odt == GRASS_F32)
+                splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(
+                    part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
+            else
+                splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
+                    part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+        }
+        off += (q.rows + 7) / 8 * 8;
+    }
     return launch_status();
+}
+
+grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
+                            int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
+                            const int32_t* idx, const float* rho, void* C, grass_dtype odt,
+                            int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start,
+                            hipEvent_t ev_stop) {
+    const GemmSegment one{dY, ldy, idx, rho, C, ldc, mrows};
+    return launch_tn_gemm_segments(&one, 1, layout, X, ldx, dt, T, n, odt, ws, s, ev_start, ev_stop);
 }
 
 }  // namespace grass

@@ -103,6 +103,23 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
                             int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start = nullptr,
                             hipEvent_t ev_stop = nullptr);
 
+// The same product for several row sets that share X (one packed panel, one GEMM).
+struct GemmSegment {
+    const void* dY;      // this set's left operand
+    int64_t ldy;
+    const int32_t* idx;  // its selected rows (device), and their scales
+    const float* rho;
+    void* C;             // its rows x n output
+    int64_t ldc;
+    int64_t rows;
+};
+size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
+                                  grass_dtype dt, grass_dy_layout layout);
+grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy_layout layout,
+                                     const void* X, int64_t ldx, grass_dtype dt, int64_t T,
+                                     int64_t n, grass_dtype odt, void* ws, hipStream_t s,
+                                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+
 // Row statistic of G = dY^T X without storing G (fused into the GEMM when the shape allows).
 size_t grad_row_stats_workspace_bytes(int64_t T, int64_t m, int64_t n, grass_dtype dt,
                                       grass_dy_layout layout, int64_t ldy, int64_t ldx);

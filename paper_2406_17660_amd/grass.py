@@ -26,6 +26,7 @@ EXPORTS = [
     "grass_adam_rows", "grass_scatter_update",
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
+    "grass_cgrad_group_workspace", "grass_compressed_grad_group",
 ]
 
 _lib = None
@@ -72,9 +73,14 @@ def lib():
     L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
     L.grass_grad_row_stats_workspace.restype = sz
     L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
+    L.grass_cgrad_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
+    L.grass_cgrad_group_workspace.restype = sz
+    L.grass_compressed_grad_group.argtypes = [i32, vp, i32, vp, vp, i64, i32, i64, vp, i64, vp,
+                                              vp, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS:
         if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
-                        "grass_dense_workspace", "grass_grad_row_stats_workspace"):
+                        "grass_dense_workspace", "grass_grad_row_stats_workspace",
+                        "grass_cgrad_group_workspace"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -176,6 +182,42 @@ def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM, gemm_events=None):
         e0, e1 = (C.c_void_p(e.cuda_event) for e in gemm_events)
         _check(lib().grass_compressed_grad_timed(*args, e0, e1), "grass_compressed_grad_timed")
     return GC
+
+
+def _i64_array(values):
+    return (C.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def _ptr_array(pointers):
+    return (C.c_void_p * len(pointers))(*[p.value if isinstance(p, C.c_void_p) else p
+                                          for p in pointers])
+
+
+def cgrad_group_workspace(T, n, rs, dtype, layout=DY_TxM) -> int:
+    return int(lib().grass_cgrad_group_workspace(T, n, len(rs), _i64_array(rs), dtype, layout))
+
+
+def compressed_grad_group(dYs, X, idxs, rhos, GCs, ws, layout=DY_TxM):
+    """Compressed gradients of several matrices that share the activations X, in one call."""
+    count = len(dYs)
+    assert count == len(idxs) == len(rhos) == len(GCs) and count >= 1
+    pX, T, n, ldx = _mat(X)
+    pYs, ldys, ms, rs, pIs, pRs, pGs, ldgcs = [], [], [], [], [], [], [], []
+    for dY, idx, rho, GC in zip(dYs, idxs, rhos, GCs):
+        pY, ry, cy, ldy = _mat(dY)
+        assert (ry if layout == DY_TxM else cy) == T and dY.dtype == X.dtype
+        r = idx.shape[0]
+        pG, gr, gc, ldgc = _mat(GC)
+        assert (gr, gc) == (r, n) and GC.dtype == torch.float32
+        pYs.append(pY); ldys.append(ldy); ms.append(cy if layout == DY_TxM else ry); rs.append(r)
+        pIs.append(_vec(idx, torch.int32)); pRs.append(_vec(rho, torch.float32))
+        pGs.append(pG); ldgcs.append(ldgc)
+    wp, wb = _ws(ws)
+    _check(lib().grass_compressed_grad_group(
+        count, _ptr_array(pYs), layout, _i64_array(ldys), pX, ldx, _dtype(X), T, _i64_array(ms), n,
+        _i64_array(rs), _ptr_array(pIs), _ptr_array(pRs), _ptr_array(pGs), _i64_array(ldgcs),
+        wp, wb, _stream()), "grass_compressed_grad_group")
+    return GCs
 
 
 def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, U):

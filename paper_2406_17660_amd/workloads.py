@@ -143,3 +143,33 @@ def make_W(cfg: Config, layer: int, device, m=None, n=None):
     m = cfg.layers[layer].m if m is None else m
     n = cfg.layers[layer].n if n is None else n
     return _randn((m, n), device, tensor_seed(cfg.cid, layer, 0, 2), dtype=cfg.dtype, scale=0.02)
+
+
+# ------------------------------------------------------------------------------ whole blocks
+# The seven linear layers of one LLaMA block (the paper trains all of them with GRASS), and
+# which of them read the same activations.  Tensors use layer codes 50 + position so that
+# they never collide with the per-layer configurations above.
+def llama_block(hidden: int, inter: int):
+    shapes = {"q": (hidden, hidden), "k": (hidden, hidden), "v": (hidden, hidden),
+              "o": (hidden, hidden), "gate": (inter, hidden), "up": (inter, hidden),
+              "down": (hidden, inter)}
+    groups = [("q", "k", "v"), ("o",), ("gate", "up"), ("down",)]
+    return shapes, groups
+
+
+BLOCKS = {"7b": (4096, 11008), "13b": (5120, 13824), "1b": (2048, 5461), "350m": (1024, 2736),
+          "60m": (512, 1376)}
+
+
+def make_block_inputs(cfg: Config, shapes, groups, device, T=None, step=0):
+    """dY per layer, X per group and W per layer for one block, drawn like cfg's layers
+    (dY ~ N(0, 0.1^2), X ~ N(0, 1), W ~ N(0, 0.02^2))."""
+    T = cfg.T if T is None else T
+    names = list(shapes)
+    dY = {name: _randn((T, shapes[name][0]), device, tensor_seed(cfg.cid, 50 + i, step, 0),
+                       dtype=cfg.dtype, scale=0.1) for i, name in enumerate(names)}
+    X = {tuple(g): _randn((T, shapes[g[0]][1]), device, tensor_seed(cfg.cid, 50 + i, step, 1),
+                          dtype=cfg.dtype) for i, g in enumerate(groups)}
+    W = {name: _randn(shapes[name], device, tensor_seed(cfg.cid, 50 + i, 0, 2), dtype=cfg.dtype,
+                      scale=0.02) for i, name in enumerate(names)}
+    return dY, X, W

@@ -98,6 +98,42 @@ def test_compressed_grad_validation():
     assert call(wsb=1024) == grass.ERR_WORKSPACE
 
 
+def test_compressed_grad_group_validation():
+    import ctypes as C
+    L = grass.lib()
+    f = L.grass_compressed_grad_group
+    big = 1 << 40
+
+    def i64(*v):
+        return (C.c_int64 * len(v))(*v)
+
+    def ptrs(*v):
+        return (C.c_void_p * len(v))(*v)
+
+    def call(count=2, dY=(FAKE, FAKE), ldy=(64, 48), ldx=32, dt=grass.BF16, T=128, m=(64, 48), n=32,
+             r=(8, 5), idx=(FAKE, FAKE), rho=(FAKE, FAKE), GC=(FAKE, FAKE), ldgc=(32, 40), ws=FAKE,
+             wsb=big):
+        return f(count, ptrs(*dY), 0, i64(*ldy), FAKE, ldx, dt, T, i64(*m), n, i64(*r), ptrs(*idx),
+                 ptrs(*rho), ptrs(*GC), i64(*ldgc), ws, wsb, None)
+
+    assert call(count=0) == grass.ERR_SHAPE
+    assert call(count=9) == grass.ERR_SHAPE
+    assert call(dY=(FAKE, None)) == grass.ERR_NULL
+    assert call(idx=(None, FAKE)) == grass.ERR_NULL
+    assert call(GC=(FAKE, None)) == grass.ERR_NULL
+    assert call(ldy=(64, 47)) == grass.ERR_SHAPE
+    assert call(ldgc=(32, 31)) == grass.ERR_SHAPE
+    assert call(r=(8, -1)) == grass.ERR_SHAPE
+    assert call(dt=7) == grass.ERR_DTYPE
+    assert call(ws=None) == grass.ERR_WORKSPACE
+    assert call(wsb=512) == grass.ERR_WORKSPACE
+    # the group's workspace covers the packed panel of all sets and is a pure host query
+    one = L.grass_cgrad_workspace(4096, 64, 512, 256, grass.BF16, 0)
+    two = L.grass_cgrad_group_workspace(4096, 512, 2, i64(256, 256), grass.BF16, 0)
+    assert two > one > 0
+    assert L.grass_cgrad_group_workspace(4096, 512, 0, i64(), grass.BF16, 0) == 0
+
+
 def test_adam_and_scatter_validation():
     L = grass.lib()
     a = L.grass_adam_rows

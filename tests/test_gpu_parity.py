@@ -408,3 +408,38 @@ def test_large_tile_kernel_every_pipeline_length(monkeypatch, T):
     want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
     assert rel_fro(got, want) <= 2e-5
     assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("layout", [grass.DY_TxM, grass.DY_MxT])
+@pytest.mark.parametrize("T,n,ms,rs,tile", [
+    (512, 256, (256, 256, 256), (16, 16, 16), None),    # q, k, v of the small configuration
+    (300, 150, (200, 90), (37, 13), None),              # nothing divides anything; r not a multiple of 8
+    (1056, 264, (300, 520, 64), (130, 129, 0), "256"),  # large tile, an empty set in last place
+    (777, 333, (130, 40, 50), (0, 40, 9), None),        # an empty set first, odd n
+    (2048, 512, (384,), (260,), "256"),                 # a group of one
+])
+def test_compressed_grad_group_matches_per_matrix_oracle(monkeypatch, dtype, layout, T, n, ms, rs, tile):
+    """Several matrices sharing X (q, k, v): every output equals the single-matrix definition."""
+    if tile:
+        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    X = randn((T, n), dtype, 20)
+    dYs, idxs, rhos, host = [], [], [], []
+    for i, (m, r) in enumerate(zip(ms, rs)):
+        dY = randn((T, m), dtype, 21 + i, scale=0.1)
+        idx, rho = make_idx(m, r, 30 + i, duplicates=(i == 1))
+        host.append((dY, idx, rho))
+        dYs.append(dY if layout == grass.DY_TxM else dY.t().contiguous())
+        idxs.append(torch.from_numpy(idx).to(DEV))
+        rhos.append(torch.from_numpy(rho).to(DEV))
+    GCs = [torch.full((r, n), float("nan"), dtype=torch.float32, device=DEV) for r in rs]
+    dt = grass.F32 if dtype == torch.float32 else grass.BF16
+    ws = grass.workspace(grass.cgrad_group_workspace(T, n, rs, dt, layout))
+    grass.compressed_grad_group(dYs, X, idxs, rhos, GCs, ws, layout)
+    for (dY, idx, rho), GC in zip(host, GCs):
+        want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+        got = to_f64(GC)
+        assert got.shape == want.shape and np.isfinite(got).all()
+        if want.size:
+            assert rel_fro(got, want) <= 2e-5
+            assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
