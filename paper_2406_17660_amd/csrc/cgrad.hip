@@ -45,7 +45,8 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
 }
 
 // ------------------------------------------------------------------------------ pack
-// out[t, j] = dY[t, idx[j]] (j < r), 0 for r <= j < rp; rows of `out` are ldo apart (several
+// out[t, j] = dY[t, idx[j]] (j < r; idx == nullptr: column j itself), 0 for r <= j < rp; rows
+// of `out` are ldo apart (several
 // matrices may fill adjacent column ranges of one panel).  Thread = 4 adjacent j, loops over
 // kPackRows values of t; wave stores are contiguous 512 B.
 constexpr int kPackRows = 16;
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restric
     if (j0 >= rp) return;
     int64_t col[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) col[e] = j0 + e < r ? idx[j0 + e] : -1;
+    for (int e = 0; e < 4; ++e) col[e] = j0 + e < r ? (idx ? idx[j0 + e] : j0 + e) : -1;
     const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kPackRows;
 #pragma unroll 4
     for (int tt = 0; tt < kPackRows; ++tt) {
@@ -94,6 +95,37 @@ __global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restric
     for (int tt = w; tt < 64; tt += 4) {
         const int64_t t = t0 + tt, j = j0 + lane;
         if (t < T && j < rp) out[t * ldo + j] = tile[lane][tt];
+    }
+}
+
+// out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np even, rows of `out` np apart): a copy
+// of a matrix whose rows start at odd element offsets (n not a multiple of 8, as in the
+// 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM can take.  `in` itself
+// is 4-byte aligned.  A thread moves one 32-bit pair at a time; a row that starts in the upper
+// half of an aligned word is read as two words and shifted.
+__global__ __launch_bounds__(256) void align_rows_kernel(const uint16_t* __restrict__ in, int64_t ld,
+                                                         int64_t n, int64_t np, int chunks,
+                                                         uint16_t* __restrict__ out) {
+    const int64_t t = blockIdx.x / chunks;
+    const int chunk = blockIdx.x % chunks;
+    const uint16_t* row = in + t * ld;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(row);
+    const bool upper = (a & 2) != 0;
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(a - (upper ? 2 : 0));
+    uint32_t* o = reinterpret_cast<uint32_t*>(out + t * np);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t d = static_cast<int64_t>(chunk) * 1024 + i * 256 + threadIdx.x;
+        const int64_t c = 2 * d;
+        if (c >= np) break;
+        uint32_t v;
+        if (upper ? c + 2 < n : c + 1 < n) {  // every word touched lies inside the row
+            v = upper ? (w[d] >> 16) | (w[d + 1] << 16) : w[d];
+        } else {
+            const uint32_t lo = c < n ? row[c] : 0u, hi = c + 1 < n ? row[c + 1] : 0u;
+            v = lo | (hi << 16);
+        }
+        o[d] = v;
     }
 }
 
@@ -586,6 +618,45 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     store_from_f32(out + j * ldo + i, s);
 }
 
+// The same sum for many slices (short, wide problems split K dozens of times): one workgroup
+// per output row and 256 columns; each of its four wavefronts adds a contiguous quarter of the
+// slices, four columns per lane, and the four partial sums are added in wavefront order.  The
+// order is fixed, so the result does not change from run to run.
+template <typename OT>
+__global__ __launch_bounds__(256) void splitk_reduce_many_kernel(
+    const float* __restrict__ P, int splits, int64_t Mp, int64_t Np, int64_t rows, int64_t cols,
+    const float* __restrict__ scale, OT* __restrict__ out, int64_t ldo) {
+    __shared__ float4 part[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t j = blockIdx.y;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + lane * 4;  // < Np: Np % 128 == 0
+    const int per = (splits + 3) / 4;
+    const int k0 = w * per, k1 = k0 + per < splits ? k0 + per : splits;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < Np) {
+        const float* p = P + (static_cast<int64_t>(k0) * Mp + j) * Np + i;
+        const int64_t step = Mp * Np;
+#pragma unroll 4
+        for (int k = k0; k < k1; ++k, p += step) {
+            const float4 v = *reinterpret_cast<const float4*>(p);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    }
+    part[w][lane] = s;
+    __syncthreads();
+    if (w != 0 || i >= cols) return;
+    float r[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float4 v = part[q][lane];
+        r[0] += v.x; r[1] += v.y; r[2] += v.z; r[3] += v.w;
+    }
+    const float sc = scale ? scale[j] : 1.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (i + e < cols) store_from_f32(out + j * ldo + i + e, r[e] * sc);
+}
+
 // ------------------------------------------------------------------------------ fp32 path
 // 64 x 64 output tile, 256 threads, each a 4 x 4 block; BK = 16.
 template <typename OT>
@@ -656,6 +727,7 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // A slice of partial tiles up to this size is re-read from the caches by the reduction.
 constexpr int64_t kCachedSliceBytes = int64_t{16} << 20;
+constexpr int kManySlices = 8;  // above this the reduction spreads the slices over wavefronts
 
 template <typename Cfg>
 Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
@@ -694,8 +766,15 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     return p;
 }
 
-bool needs_pack(grass_dy_layout layout, bool gathered) {
-    return gathered || layout == GRASS_DY_MxT;
+// The GEMM kernels read the left operand as T x rows with 16-byte chunks along the rows: a
+// gather, the m x T storage, or a row count that breaks the chunks needs the packing pass.
+bool needs_pack(grass_dy_layout layout, bool gathered, int64_t rows) {
+    return gathered || layout == GRASS_DY_MxT || rows % 8 != 0;
+}
+
+// X with n not a multiple of 8 is first copied to rows of round_up(n, 8) elements.
+size_t aligned_x_bytes(int64_t T, int64_t n) {
+    return n % 8 != 0 ? round_up(static_cast<size_t>(T) * ((n + 7) / 8 * 8) * 2, 256) : 0;
 }
 
 // The 256 x 256 tile halves the LDS traffic per flop and is the faster kernel whenever it
@@ -796,10 +875,10 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
                             grass_dy_layout layout, bool gathered) {
     if (dt == GRASS_F32) return 0;
     // the launcher may fall back to the small tile when alignment rules out the large one
-    const bool pack = needs_pack(layout, gathered);
+    const bool pack = needs_pack(layout, gathered, mrows);
     const Plan a = plan_for(kTile128, T, mrows, n, pack), b = plan_for(kTile256, T, mrows, n, pack);
     const size_t wa = a.pack_bytes + a.partial_bytes, wb = b.pack_bytes + b.partial_bytes;
-    return (wa > wb ? wa : wb) + 256;
+    return (wa > wb ? wa : wb) + aligned_x_bytes(T, n) + 256;
 }
 
 size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
@@ -848,7 +927,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     }
 
     const bool gathered = count > 1 || seg[0].idx != nullptr;
-    const bool pack = needs_pack(layout, gathered);
+    const bool pack = needs_pack(layout, gathered, total);
     if (count > 1) {
         // One panel pays off while a slice of partial tiles of the joint problem still fits
         // the caches (fewer, fuller launches).  Beyond that every set fills the machine on its
@@ -867,13 +946,17 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     const void* dY0 = seg[0].dY;  // read directly by the GEMM only when nothing is packed
     const int64_t ldy0 = seg[0].ldy;
     TileId tile = choose_tile(T, total, n);
+    // X whose width breaks the 16-byte chunks is copied to padded rows first (T > 0: nothing
+    // to copy otherwise); the GEMM then sees a matrix of round_up(n, 8) columns
+    const bool copy_x = n % 8 != 0 && aligned_to(X, 4) && T > 0;
+    const int64_t nb = copy_x ? (n + 7) / 8 * 8 : n;
     {   // the large-tile kernel moves whole aligned 16-byte chunks only
         const bool a_ok = pack || (aligned_to(dY0, 16) && ldy0 % 8 == 0 && total % 8 == 0);
-        const bool b_ok = aligned_to(X, 16) && ldx % 8 == 0 && n % 8 == 0;
+        const bool b_ok = copy_x || (aligned_to(X, 16) && ldx % 8 == 0 && n % 8 == 0);
         // per-lane byte offsets inside one K tile are kept in 32 bits
         const int64_t lda_eff = pack ? (total + kFastBM - 1) / kFastBM * kFastBM : ldy0;
         const bool off_ok = (kFastBK + 1) * lda_eff * 2 < (int64_t{1} << 32) &&
-                            (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
+                            (kFastBK + 1) * (copy_x ? nb : ldx) * 2 < (int64_t{1} << 32);
         if (!(a_ok && b_ok && off_ok && T >= kFastBK && total >= 8 && n >= 8)) tile = kTile128;
     }
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
@@ -917,10 +1000,22 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         g.Mcols = total;
         g.a_fast = aligned_to(dY0, 16) && ldy0 % 8 == 0;
     }
-    g.B = static_cast<const uint16_t*>(X);
-    g.ldb = ldx;
-    g.Ncols = n;
-    g.b_fast = aligned_to(X, 16) && ldx % 8 == 0;
+    if (copy_x) {
+        uint16_t* xa = reinterpret_cast<uint16_t*>(base + p.pack_bytes + round_up(p.partial_bytes, 256));
+        const int chunks = static_cast<int>((nb / 2 + 1023) / 1024);
+        if (T * chunks > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
+        align_rows_kernel<<<static_cast<unsigned>(T * chunks), 256, 0, s>>>(
+            static_cast<const uint16_t*>(X), ldx, n, nb, chunks, xa);
+        g.B = xa;
+        g.ldb = nb;
+        g.Ncols = nb;
+        g.b_fast = 1;
+    } else {
+        g.B = static_cast<const uint16_t*>(X);
+        g.ldb = ldx;
+        g.Ncols = n;
+        g.b_fast = aligned_to(X, 16) && ldx % 8 == 0;
+    }
     g.P = partial;
     g.K = T_main;
     g.Mp = p.Mp;
@@ -973,7 +1068,14 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         if (q.rows > 0) {
             const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
             const float* part = partial + off * p.Np;
-            if (odt == GRASS_F32)
+            if (slices > kManySlices && p.Np % 128 == 0) {
+                if (odt == GRASS_F32)
+                    splitk_reduce_many_kernel<float><<<rgrid, 256, 0, s>>>(
+                        part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
+                else
+                    splitk_reduce_many_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
+                        part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+            } else if (odt == GRASS_F32)
                 splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(
                     part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
             else

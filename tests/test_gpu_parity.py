@@ -443,3 +443,42 @@ def test_compressed_grad_group_matches_per_matrix_oracle(monkeypatch, dtype, lay
         if want.size:
             assert rel_fro(got, want) <= 2e-5
             assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("tile", ["256", "128"])
+@pytest.mark.parametrize("T,m,n,r,ldx,xoff", [
+    (1056, 300, 531, 260, 531, 0),    # odd n: every other row of X starts in the middle of a word
+    (1056, 300, 531, 260, 533, 2),    # odd leading dimension, X itself only 4-byte aligned
+    (520, 300, 1365, 257, 1365, 0),   # the 5461-wide MLP of the 1B model, quartered
+    (777, 130, 334, 129, 340, 0),     # even n that is not a multiple of 8
+    (64, 40, 9, 40, 9, 0),            # fewer columns than one 16-byte chunk and a half
+])
+def test_compressed_grad_with_activations_that_break_16_byte_rows(monkeypatch, tile, T, m, n, r, ldx, xoff):
+    """X whose rows cannot be read in aligned 16-byte chunks is first copied into padded rows."""
+    monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    dY = randn((T, m), torch.bfloat16, 51, scale=0.1)
+    flat = randn((1, T * ldx + xoff), torch.bfloat16, 52)[0]
+    X = flat[xoff:xoff + T * ldx].view(T, ldx)[:, :n]
+    assert X.data_ptr() % 4 == 0 and (xoff == 0 or X.data_ptr() % 16 != 0)
+    idx, rho = make_idx(m, r, 53, False)
+    got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= 2e-5
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("T,m,n", [(1056, 301, 531), (520, 1365, 264), (96, 13, 9)])
+def test_dense_grad_with_unaligned_widths_on_the_large_tile(monkeypatch, T, m, n):
+    """Full gradient when neither m nor n is a multiple of 8: dY goes through the packing
+    pass with the identity selection, X through the aligning copy."""
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    dY = randn((T, m), torch.bfloat16, 55, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 56)
+    G = gpu_dense(dY, X, torch.float32)
+    want = ref.full_grad(to_np(dY), to_np(X))
+    assert rel_fro(to_f64(G), want) <= 2e-5
+    ss = torch.empty(m, device=DEV)
+    ws = grass.workspace(grass.grad_row_stats_workspace(T, m, n, grass.BF16, grass.DY_TxM, m, n))
+    grass.grad_row_stats(dY, X, ss, ws)
+    assert rel_fro(ss.cpu().numpy(), ref.row_stats(want)) <= TOL_F32
