@@ -127,6 +127,44 @@ int grass_ref_adam_rows(const double* GC, int64_t ldgc, double* M, double* V, in
     return REF_OK;
 }
 
+/* Nearest bf16 value (8 significant bits, ties to even) of a double, as a double. */
+double grass_ref_round_bf16(double x) {
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);       /* |x| in [2^(e-1), 2^e) */
+    int q = e - 8;            /* spacing of bf16 values there is 2^q */
+    if (q < -133) q = -133;   /* subnormal range: fixed spacing 2^-133 */
+    const double y = ldexp(nearbyint(ldexp(x, -q)), q); /* default rounding mode: ties to even */
+    return fabs(y) >= ldexp(1.0, 128) ? copysign(INFINITY, x) : y;
+}
+
+/* adam.update of Appendix A with the moments KEPT IN bf16 (the pure-bf16 optimizer state of
+ * the paper's memory accounting, Appendix "Optimizer State Memory Calculation"): the new
+ * moments are rounded once to bf16, stored, and the update is computed from the stored
+ * values, so that U is a function of the state a checkpoint would hold.  M and V are
+ * double arrays whose values are bf16-representable on entry and on exit. */
+int grass_ref_adam_rows_bf16state(const double* GC, int64_t ldgc, double* M, double* V, int64_t r,
+                                  int64_t n, double lr, double beta1, double beta2, double eps,
+                                  int64_t t, double* U) {
+    if (!GC || !M || !V || !U) return REF_ERR_NULL;
+    if (r < 0 || n < 0 || ldgc < n || t < 1) return REF_ERR_SHAPE;
+    if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0)) return REF_ERR_SHAPE;
+    const double c1 = 1.0 - pow(beta1, (double)t);
+    const double c2 = 1.0 - pow(beta2, (double)t);
+    for (int64_t j = 0; j < r; ++j)
+        for (int64_t i = 0; i < n; ++i) {
+            const double g = GC[j * ldgc + i];
+            const double mn = grass_ref_round_bf16(beta1 * M[j * n + i] + (1.0 - beta1) * g);
+            const double vn = grass_ref_round_bf16(beta2 * V[j * n + i] + (1.0 - beta2) * g * g);
+            M[j * n + i] = mn;
+            V[j * n + i] = vn;
+            const double ms = mn / c1;
+            const double vs = vn / c2;
+            U[j * n + i] = -lr * ms / (sqrt(vs) + eps);
+        }
+    return REF_OK;
+}
+
 /* Weight update of Algorithm 1 with P = (rho B)^T:  W += alpha * P * U, i.e. row
  * sigma_j of W receives alpha * rho_j * U_j; a row selected several times receives
  * the sum (that is what the product P U does). */

@@ -37,6 +37,9 @@ def lib():
                                                 vp, vp, vp]
         L.grass_ref_adam_rows.argtypes = [vp, i64, vp, vp, i64, i64, C.c_double, C.c_double,
                                           C.c_double, C.c_double, i64, vp]
+        L.grass_ref_adam_rows_bf16state.argtypes = L.grass_ref_adam_rows.argtypes
+        L.grass_ref_round_bf16.argtypes = [C.c_double]
+        L.grass_ref_round_bf16.restype = C.c_double
         L.grass_ref_scatter_update.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64]
         L.grass_ref_scatter_update_cols.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64]
         L.grass_ref_philox4x32_10.argtypes = [vp, vp, vp]
@@ -114,16 +117,25 @@ def compressed_grad(dY, X, idx, rho, layout=DY_TxM):
     return GC
 
 
-def adam_rows(GC, M, V, lr, beta1, beta2, eps, t):
-    """Updates M and V (float64, C-contiguous) in place and returns U."""
+def round_bf16(x):
+    """Nearest bf16 value (ties to even) of every element, as float64."""
+    x = np.ascontiguousarray(x, np.float64)
+    f = lib().grass_ref_round_bf16
+    return np.array([f(float(v)) for v in x.ravel()], np.float64).reshape(x.shape)
+
+
+def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, state_bf16=False):
+    """Updates M and V (float64, C-contiguous) in place and returns U.  With state_bf16 the
+    moments are rounded to bf16 before they are stored and used."""
     GC, ldgc = _mat(np.asarray(GC, np.float64))
     r, n = GC.shape
     assert M.dtype == np.float64 and V.dtype == np.float64
     assert M.shape == (r, n) and V.shape == (r, n)
     assert M.flags.c_contiguous and V.flags.c_contiguous
     U = np.empty((r, n), np.float64)
-    _chk(lib().grass_ref_adam_rows(_p(GC), ldgc, _p(M), _p(V), r, n, float(lr), float(beta1),
-                                   float(beta2), float(eps), int(t), _p(U)))
+    fn = lib().grass_ref_adam_rows_bf16state if state_bf16 else lib().grass_ref_adam_rows
+    _chk(fn(_p(GC), ldgc, _p(M), _p(V), r, n, float(lr), float(beta1), float(beta2), float(eps),
+            int(t), _p(U)))
     return U
 
 

@@ -123,3 +123,82 @@ def test_sparse_step_equals_dense_formulation_with_explicit_P():
     ref.scatter_update(W, idx, rho, 0.25, U)
     np.testing.assert_allclose(GC, GC_dense, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(W, W_dense, rtol=1e-11, atol=1e-14)
+
+
+# ------------------------------------------------------------------------------ bf16 moments
+def exact_bf16(x):
+    """Round a float to 8 significant bits, ties to even, in exact rational arithmetic."""
+    from fractions import Fraction
+    if x == 0.0:
+        return 0.0
+    fx = Fraction(x)
+    e = 0
+    while abs(fx) >= Fraction(2) ** e:
+        e += 1
+    while abs(fx) < Fraction(2) ** (e - 1):
+        e -= 1
+    q = Fraction(2) ** max(e - 8, -133)
+    k = fx / q
+    lo = k.numerator // k.denominator  # floor
+    rem = k - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return float(lo * q)
+
+
+def test_round_bf16_against_exact_rational_rounding_and_bit_patterns():
+    rng = np.random.default_rng(31)
+    xs = np.concatenate([rng.standard_normal(200) * 10.0 ** rng.integers(-20, 20, 200),
+                         [1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -40,
+                          -(1.0 + 2.0 ** -8), 255.5, 256.5, 2.0 ** -126, 3 * 2.0 ** -134, 0.0]])
+    got = ref.round_bf16(xs)
+    assert got.tolist() == [exact_bf16(float(x)) for x in xs]
+    # ties go to the even neighbour: 1 + 2^-8 -> 1, 1 + 3*2^-8 -> 1 + 2^-6
+    assert got[201] == 1.0 and got[202] == 1.0 + 2.0 ** -6 and got[203] == 1.0 + 2.0 ** -7
+    # the results are bf16 values: fp32 bit patterns with 16 zero low bits
+    bits = got.astype(np.float32).view(np.uint32)
+    assert (got.astype(np.float32) == got).all() and ((bits & 0xFFFF) == 0).all()
+    # fp32 inputs: same as the integer rounding of the bit pattern
+    f = rng.standard_normal(500).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    want = (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16).astype(np.uint32).view(np.float32)
+    assert (ref.round_bf16(f) == want).all()
+
+
+def test_adam_bf16_state_python_loop_with_exact_rounding():
+    """Moments rounded once per step, the update computed from the rounded moments."""
+    rng = np.random.default_rng(32)
+    r, n = 3, 4
+    M = np.zeros((r, n))
+    V = np.zeros((r, n))
+    Mp = [[0.0] * n for _ in range(r)]
+    Vp = [[0.0] * n for _ in range(r)]
+    for t in range(1, 5):
+        g = rng.standard_normal((r, n)) * 0.3
+        U = ref.adam_rows(g, M, V, LR, B1, B2, EPS, t, state_bf16=True)
+        for j in range(r):
+            for i in range(n):
+                Mp[j][i] = exact_bf16(B1 * Mp[j][i] + (1 - B1) * g[j, i])
+                Vp[j][i] = exact_bf16(B2 * Vp[j][i] + (1 - B2) * g[j, i] * g[j, i])
+                u = -LR * (Mp[j][i] / (1 - B1 ** t)) / ((Vp[j][i] / (1 - B2 ** t)) ** 0.5 + EPS)
+                assert M[j, i] == Mp[j][i] and V[j, i] == Vp[j][i]
+                np.testing.assert_allclose(U[j, i], u, rtol=1e-13)
+    # the rounding is really there: the fp64 moments of the same sequence differ
+    M64 = np.zeros((r, n))
+    V64 = np.zeros((r, n))
+    rng = np.random.default_rng(32)
+    for t in range(1, 5):
+        ref.adam_rows(rng.standard_normal((r, n)) * 0.3, M64, V64, LR, B1, B2, EPS, t)
+    assert np.abs(M - M64).max() > 0 and np.abs(M - M64).max() <= 2.0 ** -7 * np.abs(M64).max()
+
+
+def test_adam_bf16_state_equals_fp64_adam_when_nothing_needs_rounding():
+    """b1 = b2 = 0.5 and power-of-two gradients keep every moment exactly representable."""
+    g1 = np.array([[2.0, -4.0, 0.5]])
+    g2 = np.array([[1.0, 8.0, -0.25]])
+    Ma, Va, Mb, Vb = (np.zeros((1, 3)) for _ in range(4))
+    for t, g in ((1, g1), (2, g2)):
+        Ua = ref.adam_rows(g, Ma, Va, 0.1, 0.5, 0.5, 0.0, t)
+        Ub = ref.adam_rows(g, Mb, Vb, 0.1, 0.5, 0.5, 0.0, t, state_bf16=True)
+        assert (Ua == Ub).all() and (Ma == Mb).all() and (Va == Vb).all()
+    assert Mb.tolist() == [[1.0, 3.0, 0.0]]  # 0.5*(0.5*g1) + 0.5*g2
