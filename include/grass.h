@@ -223,6 +223,22 @@ grass_status grass_adam_scatter(const float* GC, int64_t ldgc, float* M, float* 
                                 const int32_t* idx, const float* rho, float alpha,
                                 void* stream);
 
+/* grass_adam_rows and grass_adam_scatter with the moments M, V stored in dtype `sdt`
+ * (GRASS_F32: identical to the calls above; GRASS_BF16: the pure-bf16 optimizer state of
+ * the paper's memory accounting, Appendix "Optimizer State Memory Calculation", 2 bytes
+ * per moment).  With bf16 moments each new moment is computed in fp32 from the stored
+ * value, rounded once to bf16 (nearest even), stored, and the update U is computed from
+ * the rounded values, so U depends only on what a checkpoint of the state holds.
+ * Errors: as the fp32 calls, plus DTYPE for a bad `sdt`. */
+grass_status grass_adam_rows_state(const float* GC, int64_t ldgc, void* M, void* V,
+                                   grass_dtype sdt, int64_t r, int64_t n, float lr, float beta1,
+                                   float beta2, float eps, int64_t t, float* U, void* stream);
+grass_status grass_adam_scatter_state(const float* GC, int64_t ldgc, void* M, void* V,
+                                      grass_dtype sdt, int64_t r, int64_t n, float lr, float beta1,
+                                      float beta2, float eps, int64_t t, void* W, grass_dtype wdt,
+                                      int64_t m, int64_t ldw, const int32_t* idx, const float* rho,
+                                      float alpha, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Full gradient G = dY^T X (m x n), Section 3.1.  This is what dense-projection
  * methods compute every step ("mbn" FLOPs, Appendix F) and what GRASS needs on a

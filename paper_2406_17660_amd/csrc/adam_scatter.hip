@@ -23,10 +23,20 @@ struct AdamParams {
     float lr, eps;
 };
 
-// adam.update of Appendix A for one element; returns U.
+// What a moment becomes when it is stored: itself in fp32, the nearest bf16 value otherwise.
+template <typename ST>
+__device__ __forceinline__ float as_stored(float x);
+template <>
+__device__ __forceinline__ float as_stored<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ float as_stored<uint16_t>(float x) { return bf16_to_f32(f32_to_bf16(x)); }
+
+// adam.update of Appendix A for one element; returns U.  With bf16 moments the update is
+// computed from the values that are stored, so it is a function of the saved state.
+template <typename ST>
 __device__ __forceinline__ float adam_elem(float g, float& m, float& v, const AdamParams& p) {
-    m = p.b1 * m + p.one_minus_b1 * g;
-    v = p.b2 * v + p.one_minus_b2 * g * g;
+    m = as_stored<ST>(p.b1 * m + p.one_minus_b1 * g);
+    v = as_stored<ST>(p.b2 * v + p.one_minus_b2 * g * g);
     const float ms = m / p.c1;
     const float vs = v / p.c2;
     return -p.lr * ms / (sqrtf(vs) + p.eps);
@@ -90,29 +100,31 @@ __device__ __forceinline__ int64_t thread_col(int64_t n, int& cnt) {
     return c;
 }
 
-template <int VEC>
+template <typename ST, int VEC>
 __global__ __launch_bounds__(kThreads) void adam_rows_kernel(
-    const float* __restrict__ GC, int64_t ldgc, float* __restrict__ M, float* __restrict__ V,
+    const float* __restrict__ GC, int64_t ldgc, ST* __restrict__ M, ST* __restrict__ V,
     float* __restrict__ U, int64_t n, AdamParams p) {
     const int64_t j = blockIdx.y;
     int cnt;
     const int64_t c = thread_col<VEC>(n, cnt);
     if (cnt == 0) return;
     const float* g = GC + j * ldgc + c;
-    float* mp = M + j * n + c;
-    float* vp = V + j * n + c;
+    ST* mp = M + j * n + c;
+    ST* vp = V + j * n + c;
     float* up = U + j * n + c;
     if (cnt == VEC) {
-        F32Vec<VEC> gv, mv, vv, uv;
+        F32Vec<VEC> gv, uv;
+        WVec<ST, VEC> mv, vv;
         gv.load(g); mv.load(mp); vv.load(vp);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) uv.x[e] = adam_elem(gv.x[e], mv.x[e], vv.x[e], p);
+        for (int e = 0; e < VEC; ++e) uv.x[e] = adam_elem<ST>(gv.x[e], mv.x[e], vv.x[e], p);
         mv.store(mp); vv.store(vp); uv.store(up);
     } else {
         for (int e = 0; e < cnt; ++e) {
-            float mm = mp[e], vv = vp[e];
-            up[e] = adam_elem(g[e], mm, vv, p);
-            mp[e] = mm; vp[e] = vv;
+            float mm = load_as_f32(mp + e), vv = load_as_f32(vp + e);
+            up[e] = adam_elem<ST>(g[e], mm, vv, p);
+            store_from_f32(mp + e, mm);
+            store_from_f32(vp + e, vv);
         }
     }
 }
@@ -155,9 +167,9 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(
 }
 
 // Adam on every row of the run, then one write of W; U stays in registers.
-template <typename WT, int VEC>
+template <typename WT, typename ST, int VEC>
 __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
-    const float* __restrict__ GC, int64_t ldgc, float* __restrict__ M, float* __restrict__ V,
+    const float* __restrict__ GC, int64_t ldgc, ST* __restrict__ M, ST* __restrict__ V,
     int64_t n, int64_t r, AdamParams p, WT* __restrict__ W, int64_t ldw,
     const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha) {
     const int64_t j = blockIdx.y;
@@ -174,13 +186,14 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
-            F32Vec<VEC> gv, mv, vv;
+            F32Vec<VEC> gv;
+            WVec<ST, VEC> mv, vv;
             gv.load(GC + jj * ldgc + c);
             mv.load(M + jj * n + c);
             vv.load(V + jj * n + c);
             const float s = rho[jj];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += s * adam_elem(gv.x[e], mv.x[e], vv.x[e], p);
+            for (int e = 0; e < VEC; ++e) acc[e] += s * adam_elem<ST>(gv.x[e], mv.x[e], vv.x[e], p);
             mv.store(M + jj * n + c);
             vv.store(V + jj * n + c);
         }
@@ -191,10 +204,10 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
         for (int e = 0; e < cnt; ++e) {
             float acc = 0.f;
             for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
-                float mm = M[jj * n + c + e], vv = V[jj * n + c + e];
-                acc += rho[jj] * adam_elem(GC[jj * ldgc + c + e], mm, vv, p);
-                M[jj * n + c + e] = mm;
-                V[jj * n + c + e] = vv;
+                float mm = load_as_f32(M + jj * n + c + e), vv = load_as_f32(V + jj * n + c + e);
+                acc += rho[jj] * adam_elem<ST>(GC[jj * ldgc + c + e], mm, vv, p);
+                store_from_f32(M + jj * n + c + e, mm);
+                store_from_f32(V + jj * n + c + e, vv);
             }
             store_from_f32(wp + e, load_as_f32(wp + e) + alpha * acc);
         }
@@ -289,23 +302,33 @@ bool w_rows_vectorisable(const void* p, grass_dtype dt, int64_t ld) {
 // blockIdx.y carries the row: at most 65535 rows per launch, larger r goes in slices.
 constexpr int64_t kMaxGridY = 65535;
 
-grass_status launch_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
-                              int64_t n, float lr, float b1, float b2, float eps, int64_t t,
-                              float* U, hipStream_t s) {
-    if (r == 0 || n == 0) return GRASS_OK;
-    const AdamParams p = make_params(lr, b1, b2, eps, t);
-    const bool vec = f32_rows_vectorisable(GC, ldgc) && f32_rows_vectorisable(M, n) &&
-                     f32_rows_vectorisable(V, n) && f32_rows_vectorisable(U, n);
+template <typename ST>
+static grass_status adam_rows_typed(const float* GC, int64_t ldgc, void* Mv, void* Vv,
+                                    grass_dtype sdt, int64_t r, int64_t n, const AdamParams& p,
+                                    float* U, hipStream_t s) {
+    ST* M = static_cast<ST*>(Mv);
+    ST* V = static_cast<ST*>(Vv);
+    const bool vec = f32_rows_vectorisable(GC, ldgc) && w_rows_vectorisable(M, sdt, n) &&
+                     w_rows_vectorisable(V, sdt, n) && f32_rows_vectorisable(U, n);
     for (int64_t j0 = 0; j0 < r; j0 += kMaxGridY) {
         const int64_t rr = r - j0 < kMaxGridY ? r - j0 : kMaxGridY;
         if (vec)
-            adam_rows_kernel<4><<<grid_for(n, rr, 4), kThreads, 0, s>>>(
+            adam_rows_kernel<ST, 4><<<grid_for(n, rr, 4), kThreads, 0, s>>>(
                 GC + j0 * ldgc, ldgc, M + j0 * n, V + j0 * n, U + j0 * n, n, p);
         else
-            adam_rows_kernel<1><<<grid_for(n, rr, 1), kThreads, 0, s>>>(
+            adam_rows_kernel<ST, 1><<<grid_for(n, rr, 1), kThreads, 0, s>>>(
                 GC + j0 * ldgc, ldgc, M + j0 * n, V + j0 * n, U + j0 * n, n, p);
     }
     return launch_status();
+}
+
+grass_status launch_adam_rows(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
+                              int64_t r, int64_t n, float lr, float b1, float b2, float eps,
+                              int64_t t, float* U, hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    const AdamParams p = make_params(lr, b1, b2, eps, t);
+    return sdt == GRASS_F32 ? adam_rows_typed<float>(GC, ldgc, M, V, sdt, r, n, p, U, s)
+                            : adam_rows_typed<uint16_t>(GC, ldgc, M, V, sdt, r, n, p, U, s);
 }
 
 template <typename WT>
@@ -335,33 +358,38 @@ grass_status launch_scatter(void* W, grass_dtype wdt, int64_t n, int64_t ldw, co
                             : scatter_typed<uint16_t>(W, wdt, n, ldw, idx, rho, alpha, U, r, s);
 }
 
-template <typename WT>
-static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, float* M, float* V,
-                                       int64_t r, int64_t n, const AdamParams& p, void* W,
-                                       grass_dtype wdt, int64_t ldw, const int32_t* idx,
+template <typename WT, typename ST>
+static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, void* Mv, void* Vv,
+                                       grass_dtype sdt, int64_t r, int64_t n, const AdamParams& p,
+                                       void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,
                                        const float* rho, float alpha, hipStream_t s) {
-    const bool vec = f32_rows_vectorisable(GC, ldgc) && f32_rows_vectorisable(M, n) &&
-                     f32_rows_vectorisable(V, n) && w_rows_vectorisable(W, wdt, ldw);
+    ST* M = static_cast<ST*>(Mv);
+    ST* V = static_cast<ST*>(Vv);
+    const bool vec = f32_rows_vectorisable(GC, ldgc) && w_rows_vectorisable(M, sdt, n) &&
+                     w_rows_vectorisable(V, sdt, n) && w_rows_vectorisable(W, wdt, ldw);
     if (r > kMaxGridY) return GRASS_ERR_SHAPE;
     if (vec)
-        adam_scatter_kernel<WT, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+        adam_scatter_kernel<WT, ST, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
             GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
     else
-        adam_scatter_kernel<WT, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
+        adam_scatter_kernel<WT, ST, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
             GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
     return launch_status();
 }
 
-grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
-                                 int64_t n, float lr, float b1, float b2, float eps, int64_t t,
-                                 void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,
-                                 const float* rho, float alpha, hipStream_t s) {
+grass_status launch_adam_scatter(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
+                                 int64_t r, int64_t n, float lr, float b1, float b2, float eps,
+                                 int64_t t, void* W, grass_dtype wdt, int64_t ldw,
+                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s) {
     if (r == 0 || n == 0) return GRASS_OK;
     const AdamParams p = make_params(lr, b1, b2, eps, t);
-    return wdt == GRASS_F32
-               ? adam_scatter_typed<float>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
-               : adam_scatter_typed<uint16_t>(GC, ldgc, M, V, r, n, p, W, wdt, ldw, idx, rho,
-                                              alpha, s);
+    if (wdt == GRASS_F32)
+        return sdt == GRASS_F32
+                   ? adam_scatter_typed<float, float>(GC, ldgc, M, V, sdt, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
+                   : adam_scatter_typed<float, uint16_t>(GC, ldgc, M, V, sdt, r, n, p, W, wdt, ldw, idx, rho, alpha, s);
+    return sdt == GRASS_F32
+               ? adam_scatter_typed<uint16_t, float>(GC, ldgc, M, V, sdt, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
+               : adam_scatter_typed<uint16_t, uint16_t>(GC, ldgc, M, V, sdt, r, n, p, W, wdt, ldw, idx, rho, alpha, s);
 }
 
 grass_status launch_scatter_cols(void* W, grass_dtype wdt, int64_t mrows, int64_t ldw,

@@ -27,10 +27,11 @@ grass_status check_products(const void* dY, grass_dy_layout layout, int64_t ldy,
     return GRASS_OK;
 }
 
-grass_status check_adam(const float* GC, int64_t ldgc, const float* M, const float* V, int64_t r,
-                        int64_t n, float beta1, float beta2, int64_t t) {
+grass_status check_adam(const float* GC, int64_t ldgc, const void* M, const void* V,
+                        grass_dtype sdt, int64_t r, int64_t n, float beta1, float beta2, int64_t t) {
     if (r < 0 || n < 0 || ldgc < n || t < 1) return GRASS_ERR_SHAPE;
     if (!present(GC, r * n) || !present(M, r * n) || !present(V, r * n)) return GRASS_ERR_NULL;
+    if (!dtype_ok(sdt)) return GRASS_ERR_DTYPE;
     if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return GRASS_ERR_SHAPE;
     return GRASS_OK;
 }
@@ -162,10 +163,18 @@ grass_status grass_compressed_grad_group(int count, const void* const* dY, grass
 grass_status grass_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
                              int64_t n, float lr, float beta1, float beta2, float eps, int64_t t,
                              float* U, void* stream) {
-    const grass_status st = check_adam(GC, ldgc, M, V, r, n, beta1, beta2, t);
+    return grass_adam_rows_state(GC, ldgc, M, V, GRASS_F32, r, n, lr, beta1, beta2, eps, t, U,
+                                 stream);
+}
+
+grass_status grass_adam_rows_state(const float* GC, int64_t ldgc, void* M, void* V,
+                                   grass_dtype sdt, int64_t r, int64_t n, float lr, float beta1,
+                                   float beta2, float eps, int64_t t, float* U, void* stream) {
+    const grass_status st = check_adam(GC, ldgc, M, V, sdt, r, n, beta1, beta2, t);
     if (st != GRASS_OK) return st;
     if (!present(U, r * n)) return GRASS_ERR_NULL;
-    return launch_adam_rows(GC, ldgc, M, V, r, n, lr, beta1, beta2, eps, t, U, as_stream(stream));
+    return launch_adam_rows(GC, ldgc, M, V, sdt, r, n, lr, beta1, beta2, eps, t, U,
+                            as_stream(stream));
 }
 
 grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
@@ -192,12 +201,21 @@ grass_status grass_adam_scatter(const float* GC, int64_t ldgc, float* M, float* 
                                 int64_t n, float lr, float beta1, float beta2, float eps,
                                 int64_t t, void* W, grass_dtype wdt, int64_t m, int64_t ldw,
                                 const int32_t* idx, const float* rho, float alpha, void* stream) {
-    grass_status st = check_adam(GC, ldgc, M, V, r, n, beta1, beta2, t);
+    return grass_adam_scatter_state(GC, ldgc, M, V, GRASS_F32, r, n, lr, beta1, beta2, eps, t, W,
+                                    wdt, m, ldw, idx, rho, alpha, stream);
+}
+
+grass_status grass_adam_scatter_state(const float* GC, int64_t ldgc, void* M, void* V,
+                                      grass_dtype sdt, int64_t r, int64_t n, float lr, float beta1,
+                                      float beta2, float eps, int64_t t, void* W, grass_dtype wdt,
+                                      int64_t m, int64_t ldw, const int32_t* idx, const float* rho,
+                                      float alpha, void* stream) {
+    grass_status st = check_adam(GC, ldgc, M, V, sdt, r, n, beta1, beta2, t);
     if (st != GRASS_OK) return st;
     st = check_rows_of_w(W, wdt, m, n, ldw, idx, rho, r);
     if (st != GRASS_OK) return st;
-    return launch_adam_scatter(GC, ldgc, M, V, r, n, lr, beta1, beta2, eps, t, W, wdt, ldw, idx,
-                               rho, alpha, as_stream(stream));
+    return launch_adam_scatter(GC, ldgc, M, V, sdt, r, n, lr, beta1, beta2, eps, t, W, wdt, ldw,
+                               idx, rho, alpha, as_stream(stream));
 }
 
 size_t grass_dense_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,

@@ -77,19 +77,20 @@ grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_metho
                            int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
                            int32_t* idx, float* rho, void* ws, hipStream_t s);
 size_t select_workspace_bytes(int64_t m, int64_t r, grass_method method, int replacement);
-grass_status launch_adam_rows(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
-                              int64_t n, float lr, float b1, float b2, float eps, int64_t t,
-                              float* U, hipStream_t s);
+// M and V have dtype sdt (fp32, or bf16 moments rounded once per step).
+grass_status launch_adam_rows(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
+                              int64_t r, int64_t n, float lr, float b1, float b2, float eps,
+                              int64_t t, float* U, hipStream_t s);
 grass_status launch_scatter(void* W, grass_dtype wdt, int64_t n, int64_t ldw, const int32_t* idx,
                             const float* rho, float alpha, const float* U, int64_t r,
                             hipStream_t s);
 grass_status launch_scatter_cols(void* W, grass_dtype wdt, int64_t mrows, int64_t ldw,
                                  const int32_t* idx, const float* rho, float alpha, const float* U,
                                  int64_t r, hipStream_t s);
-grass_status launch_adam_scatter(const float* GC, int64_t ldgc, float* M, float* V, int64_t r,
-                                 int64_t n, float lr, float b1, float b2, float eps, int64_t t,
-                                 void* W, grass_dtype wdt, int64_t ldw, const int32_t* idx,
-                                 const float* rho, float alpha, hipStream_t s);
+grass_status launch_adam_scatter(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
+                                 int64_t r, int64_t n, float lr, float b1, float b2, float eps,
+                                 int64_t t, void* W, grass_dtype wdt, int64_t ldw,
+                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s);
 grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64_t ldg,
                                 const int32_t* idx, const float* rho, int64_t r, float* out,
                                 int64_t ldo, hipStream_t s);

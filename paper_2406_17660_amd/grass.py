@@ -27,6 +27,7 @@ EXPORTS = [
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
+    "grass_adam_rows_state", "grass_adam_scatter_state",
 ]
 
 _lib = None
@@ -65,6 +66,10 @@ def lib():
     L.grass_scatter_update_cols.argtypes = L.grass_scatter_update.argtypes
     L.grass_adam_scatter.argtypes = [vp, i64, vp, vp, i64, i64, f32, f32, f32, f32, i64, vp, i32,
                                      i64, i64, vp, vp, f32, vp]
+    L.grass_adam_rows_state.argtypes = [vp, i64, vp, vp, i32, i64, i64, f32, f32, f32, f32, i64, vp,
+                                        vp]
+    L.grass_adam_scatter_state.argtypes = [vp, i64, vp, vp, i32, i64, i64, f32, f32, f32, f32, i64,
+                                           vp, i32, i64, i64, vp, vp, f32, vp]
     L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
     L.grass_dense_workspace.restype = sz
     L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
@@ -220,13 +225,24 @@ def compressed_grad_group(dYs, X, idxs, rhos, GCs, ws, layout=DY_TxM):
     return GCs
 
 
+def _moments(M, V, r, n):
+    """Pointers and dtype code of the Adam moments (fp32, or bf16 for the 2-byte state)."""
+    for a in (M, V):
+        assert a.shape == (r, n) and a.is_contiguous() and a.is_cuda and a.dtype == M.dtype
+    return C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()), _dtype(M)
+
+
 def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, U):
     pG, r, n, ldgc = _mat(GC)
-    for a in (M, V, U):
-        assert a.shape == (r, n) and a.is_contiguous() and a.dtype == torch.float32 and a.is_cuda
-    _check(lib().grass_adam_rows(pG, ldgc, C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()), r,
-                                 n, lr, beta1, beta2, eps, t, C.c_void_p(U.data_ptr()), _stream()),
-           "grass_adam_rows")
+    pM, pV, sdt = _moments(M, V, r, n)
+    assert U.shape == (r, n) and U.is_contiguous() and U.dtype == torch.float32 and U.is_cuda
+    pU = C.c_void_p(U.data_ptr())
+    if sdt == F32:
+        _check(lib().grass_adam_rows(pG, ldgc, pM, pV, r, n, lr, beta1, beta2, eps, t, pU,
+                                     _stream()), "grass_adam_rows")
+    else:
+        _check(lib().grass_adam_rows_state(pG, ldgc, pM, pV, sdt, r, n, lr, beta1, beta2, eps, t,
+                                           pU, _stream()), "grass_adam_rows_state")
     return U
 
 
@@ -255,12 +271,15 @@ def adam_scatter(GC, M, V, lr, beta1, beta2, eps, t, W, idx, rho, alpha):
     pG, r, n, ldgc = _mat(GC)
     pW, m, nw, ldw = _mat(W)
     assert nw == n and idx.shape == (r,)
-    for a in (M, V):
-        assert a.shape == (r, n) and a.is_contiguous() and a.dtype == torch.float32 and a.is_cuda
-    _check(lib().grass_adam_scatter(pG, ldgc, C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()),
-                                    r, n, lr, beta1, beta2, eps, t, pW, _dtype(W), m, ldw,
-                                    _vec(idx, torch.int32), _vec(rho, torch.float32), alpha,
-                                    _stream()), "grass_adam_scatter")
+    pM, pV, sdt = _moments(M, V, r, n)
+    tail = (pW, _dtype(W), m, ldw, _vec(idx, torch.int32), _vec(rho, torch.float32), alpha,
+            _stream())
+    if sdt == F32:
+        _check(lib().grass_adam_scatter(pG, ldgc, pM, pV, r, n, lr, beta1, beta2, eps, t, *tail),
+               "grass_adam_scatter")
+    else:
+        _check(lib().grass_adam_scatter_state(pG, ldgc, pM, pV, sdt, r, n, lr, beta1, beta2, eps,
+                                              t, *tail), "grass_adam_scatter_state")
     return W
 
 

@@ -36,7 +36,8 @@ class GrassLayer:
 
     def __init__(self, m, n, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, g_dtype=None,
-                 layout=grass.DY_TxM, device="cuda", materialise_G=False, side="rows"):
+                 layout=grass.DY_TxM, device="cuda", materialise_G=False, side="rows",
+                 state_dtype=torch.float32):
         assert side in ("rows", "cols")
         self.side = side
         self.w_shape = (m, n)
@@ -52,8 +53,9 @@ class GrassLayer:
         dev = device
         self.idx = torch.zeros(r, dtype=torch.int32, device=dev)
         self.rho = torch.ones(r, dtype=torch.float32, device=dev)
-        self.M = torch.zeros((r, n), dtype=torch.float32, device=dev)
-        self.V = torch.zeros((r, n), dtype=torch.float32, device=dev)
+        # Adam moments: fp32, or bf16 (2 bytes per moment, rounded once per step)
+        self.M = torch.zeros((r, n), dtype=state_dtype, device=dev)
+        self.V = torch.zeros((r, n), dtype=state_dtype, device=dev)
         self.GC = torch.empty((r, n), dtype=torch.float32, device=dev)
         self.sumsq = torch.empty(m, dtype=torch.float32, device=dev)
         self.ws_sel = grass.workspace(grass.select_workspace(m, r, self.method, replacement), dev)

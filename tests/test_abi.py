@@ -158,6 +158,17 @@ def test_adam_and_scatter_validation():
              None) == grass.ERR_NULL
     assert f(FAKE, 8, FAKE, FAKE, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 0, FAKE, 0, 4, 8, FAKE, FAKE, 1.0,
              None) == grass.ERR_SHAPE
+    # the state-dtype forms: same checks plus the dtype of the moments
+    a2 = L.grass_adam_rows_state
+    assert a2(FAKE, 8, FAKE, FAKE, grass.BF16, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, None, None) == grass.ERR_NULL
+    assert a2(FAKE, 8, None, FAKE, grass.BF16, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, None) == grass.ERR_NULL
+    assert a2(FAKE, 8, FAKE, FAKE, 2, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, None) == grass.ERR_DTYPE
+    assert a2(FAKE, 8, FAKE, FAKE, grass.BF16, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 0, FAKE, None) == grass.ERR_SHAPE
+    f2 = L.grass_adam_scatter_state
+    assert f2(FAKE, 8, FAKE, FAKE, 9, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, 0, 4, 8, FAKE, FAKE, 1.0,
+              None) == grass.ERR_DTYPE
+    assert f2(FAKE, 8, FAKE, FAKE, grass.BF16, 2, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE, 0, 4, 7, FAKE,
+              FAKE, 1.0, None) == grass.ERR_SHAPE
     d = L.grass_dense_grad
     assert d(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, None, 0, 32, FAKE, 1 << 40, None) == grass.ERR_NULL
     assert d(FAKE, 0, 64, FAKE, 32, grass.BF16, 128, 64, 32, FAKE, 4, 32, FAKE, 1 << 40, None) == grass.ERR_DTYPE

@@ -482,3 +482,62 @@ def test_dense_grad_with_unaligned_widths_on_the_large_tile(monkeypatch, T, m, n
     ws = grass.workspace(grass.grad_row_stats_workspace(T, m, n, grass.BF16, grass.DY_TxM, m, n))
     grass.grad_row_stats(dY, X, ss, ws)
     assert rel_fro(ss.cpu().numpy(), ref.row_stats(want)) <= TOL_F32
+
+
+# ------------------------------------------------------------------------------ bf16 moments
+@pytest.mark.parametrize("r,n,ldgc", [(16, 256, 256), (37, 1376, 1376), (5, 333, 333), (8, 5461, 5461)])
+@pytest.mark.parametrize("t", [1, 7])
+def test_adam_rows_with_bf16_moments(r, n, ldgc, t):
+    """Moments stored in bf16: rounded once per step, the update taken from the stored values."""
+    GC, M, V = adam_inputs(r, n, 60, ldgc)
+    M, V = M.to(torch.bfloat16), V.to(torch.bfloat16)
+    if t == 1:
+        M.zero_(); V.zero_()
+    M0, V0 = to_f64(M).copy(), to_f64(V).copy()
+    Mold, Vold, g = M0.copy(), V0.copy(), to_f64(GC)
+    U = torch.full((r, n), float("nan"), device=DEV)
+    grass.adam_rows(GC, M, V, LR, B1, B2, EPS, t, U)
+    f = np.float32
+    wU = ref.adam_rows(to_f64(GC), M0, V0, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), t,
+                       state_bf16=True)
+    gM, gV = to_f64(M), to_f64(V)
+    # fp32 arithmetic before the rounding: a moment may land on the neighbouring bf16 value
+    # when its exact value is within fp32 rounding of a tie (rare, one ulp); where the two
+    # terms cancel, the fp32 error of the terms themselves is added
+    for got, want, terms in ((gM, M0, np.abs(Mold) + np.abs(g)), (gV, V0, np.abs(Vold) + g * g)):
+        off = got != want
+        assert off.mean() <= 1e-3
+        assert (np.abs(got - want) <= 1.01 * bf16_ulp(want) + 4 * 2.0 ** -24 * terms).all()
+    same = (gM == M0) & (gV == V0)
+    np.testing.assert_allclose(to_f64(U)[same], wU[same], rtol=5e-6, atol=1e-6 * LR)
+    assert rel_fro(to_f64(U), wU) <= TOL_BF16
+
+
+@pytest.mark.parametrize("wdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("m,n,r,dup", [(200, 1376, 64, True), (50, 333, 50, True), (256, 256, 16, False)])
+def test_fused_adam_scatter_with_bf16_moments(wdtype, m, n, r, dup):
+    idx, rho = make_idx(m, r, 61, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    W = randn((m, n), wdtype, 62, scale=0.02)
+    GC, M, V = adam_inputs(r, n, 63, n)
+    M, V = M.to(torch.bfloat16), V.to(torch.bfloat16)
+    # unfused with the same state dtype, then fused: identical bits
+    M1, V1, W1 = M.clone(), V.clone(), W.clone()
+    U = torch.empty((r, n), device=DEV)
+    grass.adam_rows(GC, M1, V1, LR, B1, B2, EPS, 3, U)
+    grass.scatter_update(W1, d_idx, d_rho, 0.25, U)
+    M2, V2, W2 = M.clone(), V.clone(), W.clone()
+    grass.adam_scatter(GC, M2, V2, LR, B1, B2, EPS, 3, W2, d_idx, d_rho, 0.25)
+    assert torch.equal(W1, W2) and torch.equal(M1, M2) and torch.equal(V1, V2)
+    # and against the oracle
+    f = np.float32
+    Mo, Vo = to_f64(M).copy(), to_f64(V).copy()
+    wU = ref.adam_rows(to_f64(GC), Mo, Vo, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 3,
+                       state_bf16=True)
+    Wo = to_f64(W).copy()
+    ref.scatter_update(Wo, idx, rho, 0.25, wU)
+    sel = np.unique(idx)
+    assert rel_fro(to_f64(W2)[sel], Wo[sel]) <= tol_for(wdtype)
+    assert rel_fro(to_f64(M2), Mo) <= 1e-4 and rel_fro(to_f64(V2), Vo) <= 1e-4
+    rest = np.setdiff1d(np.arange(m), sel)
+    assert np.array_equal(to_np(W2)[rest], to_np(W)[rest])

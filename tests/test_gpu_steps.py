@@ -26,7 +26,8 @@ REF_METHOD = {"topr": ref.TOPR, "uniform": ref.UNIFORM, "multi_norm": ref.MULTI_
 class OracleLayer:
     """The same Algorithm-1 bookkeeping as GrassLayer, but every step is the fp64 oracle."""
 
-    def __init__(self, W0, r, method, replacement, scale, alpha, adam, seed):
+    def __init__(self, W0, r, method, replacement, scale, alpha, adam, seed, state_bf16=False):
+        self.state_bf16 = state_bf16
         self.W = W0.copy()
         self.r, self.method, self.replacement, self.scale = r, method, replacement, scale
         self.alpha, self.adam, self.seed = alpha, adam, seed
@@ -51,12 +52,13 @@ class OracleLayer:
         self.GC = ref.compressed_grad(dY, X, self.idx, self.rho)
         self.t += 1
         U = ref.adam_rows(self.GC, self.M, self.V, float(F(a.lr)), float(F(a.beta1)),
-                          float(F(a.beta2)), float(F(a.eps)), self.t)
+                          float(F(a.beta2)), float(F(a.eps)), self.t, state_bf16=self.state_bf16)
         ref.scatter_update(self.W, self.idx, self.rho, float(F(self.alpha)), U)
 
 
 def run_config(cfg, layer, T, steps, refresh_every, method=None, replacement=None,
-               scale=grass.SCALE_PAPER, g_dtype=None, check_full_grad=True, materialise_G=False):
+               scale=grass.SCALE_PAPER, g_dtype=None, check_full_grad=True, materialise_G=False,
+               state_dtype=torch.float32):
     L = cfg.layers[layer]
     method = method or cfg.method
     replacement = cfg.replacement if replacement is None else replacement
@@ -64,9 +66,10 @@ def run_config(cfg, layer, T, steps, refresh_every, method=None, replacement=Non
     W = workloads.make_W(cfg, layer, DEV)
     W0_bits = to_np(W).copy()
     st = GrassLayer(L.m, L.n, cfg.r, T, cfg.dtype, method, replacement, scale, cfg.alpha, adam,
-                    seed=workloads.BASE_SEED + layer, g_dtype=g_dtype, materialise_G=materialise_G)
+                    seed=workloads.BASE_SEED + layer, g_dtype=g_dtype, materialise_G=materialise_G,
+                    state_dtype=state_dtype)
     orc = OracleLayer(to_f64(W), cfg.r, REF_METHOD[method], replacement, scale, cfg.alpha, adam,
-                      workloads.BASE_SEED + layer)
+                      workloads.BASE_SEED + layer, state_bf16=state_dtype == torch.bfloat16)
     tol = tol_for(cfg.dtype)
     touched = set()
     # Adam's update is ~ -lr * sign(g) early on, so an element of G_C that cancels to within
@@ -148,6 +151,13 @@ def test_config2_llama60m_multinorm_nr(layer, scale):
     two runs stores G in bf16 on refresh steps, the other takes the statistic in the GEMM."""
     run_config(workloads.CONFIGS[2], layer, 2048, 10, 5, scale=scale,
                materialise_G=(scale == grass.SCALE_PAPER))
+
+
+@pytest.mark.parametrize("layer", [0, 2])
+def test_config2_with_bf16_adam_moments(layer):
+    """The same steps with the moments kept in bf16 (2 bytes each), rounded once per step."""
+    st, _ = run_config(workloads.CONFIGS[2], layer, 2048, 6, 3, state_dtype=torch.bfloat16)
+    assert st.M.dtype == torch.bfloat16 and st.V.dtype == torch.bfloat16
 
 
 @pytest.mark.parametrize("layer", [0, 1, 2])
