@@ -236,7 +236,7 @@ def main():
                                f"{'' if cfg.replacement else '-NR'} selection of {args.side}, {args.adam_state} Adam state, "
                                f"refresh every {REFRESH_EVERY} steps",
                    "m": m, "n": n, "T": T, "r": r},
-        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_direct_kernel<false> (compressed-gradient GEMM)",
+        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_direct_kernel<false, false> (compressed-gradient GEMM)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS,
                      "traffic": measured_traffic(L.name, T),
