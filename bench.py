@@ -43,6 +43,9 @@ def parse():
     p.add_argument("--block", choices=sorted(workloads.BLOCKS), default=None,
                    help="time Algorithm 1 over all seven linear layers of one LLaMA block "
                         "(grouped q/k/v and gate/up calls) instead of the single layer")
+    p.add_argument("--layout", choices=["txm", "mxt"], default="txm",
+                   help="storage of dY: T x m (what the headline is quoted on) or m x T, whose "
+                        "selected rows are contiguous and are gathered inside the GEMM")
     p.add_argument("--adam-state", choices=["f32", "bf16"], default="f32",
                    help="dtype of the Adam moments (the headline configuration keeps them in fp32)")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,11 +187,15 @@ def main():
     dev = "cuda"
 
     dY = workloads.make_dY(cfg, args.layer, 0, dev, T=T)
+    layout = grass.DY_TxM
+    if args.layout == "mxt":
+        dY = dY.t().contiguous()
+        layout = grass.DY_MxT
     X = workloads.make_X(cfg, args.layer, 0, dev, T=T)
     W = workloads.make_W(cfg, args.layer, dev)
     adam = AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps)
     st = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
-                    seed=workloads.BASE_SEED, side=args.side,
+                    seed=workloads.BASE_SEED, side=args.side, layout=layout,
                     state_dtype=torch.bfloat16 if args.adam_state == "bf16" else torch.float32)
 
     def run(steps, gemm_events=None):
@@ -233,18 +240,20 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cid} ({cfg.name}) layer {L.name}: W {m}x{n}, "
                                f"T={T} tokens, r={r}, {cfg.method}"
-                               f"{'' if cfg.replacement else '-NR'} selection of {args.side}, {args.adam_state} Adam state, "
+                               f"{'' if cfg.replacement else '-NR'} selection of {args.side}, dY stored {args.layout}, {args.adam_state} Adam state, "
                                f"refresh every {REFRESH_EVERY} steps",
                    "m": m, "n": n, "T": T, "r": r},
-        "roofline": {"bound": "mfma", "kernel": "tn_gemm_bf16_direct_kernel<false, false> (compressed-gradient GEMM)",
+        "roofline": {"bound": "mfma",
+                     "kernel": ("tn_gemm_bf16_direct_kernel<false, false, true>" if args.layout == "mxt"
+                                else "tn_gemm_bf16_direct_kernel<false, false>") + " (compressed-gradient GEMM)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": measured_traffic(L.name, T),
+                     "traffic": measured_traffic(L.name, T) if args.layout == "txm" else None,
                      "flops_per_launch": flops, "avg_launch_ms": gemm_ms},
         "host_wall_s": wall,
     }
 
-    if not args.no_extras and args.side == "rows":
+    if not args.no_extras and args.side == "rows" and args.layout == "txm":
         detail = {}
         it = 20
         med, _ = time_calls(lambda: st.compressed_grad(dY, X), it)
@@ -282,7 +291,8 @@ def main():
                                    "A100; no per-layer timing is published")
         out["detail"] = detail
 
-    if not args.no_cpu_baseline and args.side == "rows" and args.adam_state == "f32":
+    if (not args.no_cpu_baseline and args.side == "rows" and args.adam_state == "f32"
+            and args.layout == "txm"):
         out["cpu_baseline"] = cpu_baseline(cfg, L, dY, X, st, W, args.cpu_seconds)
 
     print(json.dumps(out))

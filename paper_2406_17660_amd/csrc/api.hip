@@ -123,7 +123,7 @@ grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout,
     const size_t need = gemm_workspace_bytes(T, r, n, dt, layout, true);
     if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
     return launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, r, n, idx, rho, GC, GRASS_F32, ldgc, ws,
-                          as_stream(stream), static_cast<hipEvent_t>(ev_gemm_start),
+                          as_stream(stream), m, static_cast<hipEvent_t>(ev_gemm_start),
                           static_cast<hipEvent_t>(ev_gemm_stop));
 }
 
@@ -152,7 +152,7 @@ grass_status grass_compressed_grad_group(int count, const void* const* dY, grass
             return GRASS_ERR_SHAPE;
         if (!present(idx[i], r[i]) || !present(rho[i], r[i]) || !present(GC[i], r[i] * n))
             return GRASS_ERR_NULL;
-        seg[i] = GemmSegment{dY[i], ldy[i], idx[i], rho[i], GC[i], ldgc[i], r[i]};
+        seg[i] = GemmSegment{dY[i], ldy[i], idx[i], rho[i], GC[i], ldgc[i], r[i], m[i]};
     }
     const size_t need = gemm_group_workspace_bytes(T, r, count, n, dt, layout);
     if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
@@ -236,7 +236,7 @@ grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ld
     const size_t need = gemm_workspace_bytes(T, m, n, dt, layout, false);
     if (need > 0 && (!ws || ws_bytes < need)) return GRASS_ERR_WORKSPACE;
     return launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, m, n, nullptr, nullptr, G, gdt, ldg, ws,
-                          as_stream(stream));
+                          as_stream(stream), m);
 }
 
 size_t grass_grad_row_stats_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,

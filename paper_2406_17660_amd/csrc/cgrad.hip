@@ -28,6 +28,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 
 constexpr int kNumXcd = 8;
 
@@ -190,6 +191,9 @@ struct GemmArgs {
     int64_t lda, ldb, K, Mcols, Ncols, Mp, Np;
     int tiles_m, tiles_n, splits, ktiles_per_split;
     int a_fast, b_fast;
+    // row form of the left operand (large-tile kernel only): A is [rows of length K], row j of
+    // the product is A + a_rows[j] * lda (a_rows == nullptr: row j itself)
+    const int32_t* a_rows;
 };
 
 // kDense only tags the instantiation (dense full gradient vs compressed gradient) so that a
@@ -374,7 +378,15 @@ __device__ __forceinline__ void wait_vmcnt() {
 // each row (columns past the matrix edge excluded) and stores 256 partial row sums per
 // half-tile of columns: the row statistic of G without G ever being written.  Only valid
 // with a single K slice.
-template <bool kDense, bool kRowStats = false>
+//
+// kARows: the left operand is given as rows of length K (dY stored m x T) and the selected rows
+// are gathered by the tile loads themselves: row j of the tile is the 64 contiguous bytes
+// A[a_rows[j]][k0 .. k0+32).  Its LDS block is [256 rows][32 k] (64 bytes per row, 16-byte
+// slot c of row j stored at slot c ^ ((j / 4) % 4), so that the 16 lanes of a quarter
+// wavefront, which read one slot of 16 consecutive rows, cover all 64 banks once) and an MFMA
+// operand is a single 16-byte read per lane: no transposition is needed, the 8 consecutive k
+// a lane feeds to the matrix core are contiguous in the row.
+template <bool kDense, bool kRowStats = false, bool kARows = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     __shared__ __attribute__((aligned(1024))) uint16_t ring[kFastStages * kFastStageElems];
@@ -408,15 +420,25 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     if (colA >= g.Mcols) colA = 0;
     if (colB >= g.Ncols) colB = 0;
     // uniform tile base (advances by one K tile per issue) + constant per-lane byte offsets
-    const uint16_t* gA = g.A + kt_begin * kFastBK * g.lda;
+    const uint16_t* gA = g.A + (kARows ? kt_begin * kFastBK : kt_begin * kFastBK * g.lda);
     const uint16_t* gB = g.B + kt_begin * kFastBK * g.ldb;
     uint32_t laneA[kFastBK / 8], laneB[kFastBK / 8];
 #pragma unroll
     for (int p = 0; p < kFastBK / 8; ++p) {
-        laneA[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.lda + colA) * 2);
+        if (kARows) {
+            // pass p: this wavefront fills tile rows 64p + 16*wave .. +16, four lanes per row
+            const int trow = 64 * p + 16 * wave + (lane >> 2);
+            int64_t j = m0 + trow;
+            if (j >= g.Mcols) j = 0;  // rows past the edge only feed outputs nobody reads
+            const int64_t src = g.a_rows ? g.a_rows[j] : j;
+            const int lslot = (lane & 3) ^ ((trow >> 2) & 3);
+            laneA[p] = static_cast<uint32_t>((src * g.lda + lslot * 8) * 2);
+        } else {
+            laneA[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.lda + colA) * 2);
+        }
         laneB[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.ldb + colB) * 2);
     }
-    const int64_t tileA = kFastBK * g.lda, tileB = kFastBK * g.ldb;
+    const int64_t tileA = kARows ? kFastBK : kFastBK * g.lda, tileB = kFastBK * g.ldb;
     const int ldsrow = wave * 2;  // first LDS row this wavefront writes in a pass
 
     // Loads of K tile number `i` (counted from this workgroup's first tile) into its ring
@@ -427,7 +449,7 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     const uint32_t ring_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)ring));
     auto issue_part = [&](int i, int part) {
         const uint32_t d = ring_base + ((i % kFastStages) * kFastStageElems + ldsrow * 256) * 2;
-        if (part < kFastBK / 8)
+        if (part < kFastBK / 8)  // both forms: pass `part` of this wavefront starts 4 KiB further
             load16_to_lds(gA, laneA[part], d + part * 8 * 256 * 2);
         else
             load16_to_lds(gB, laneB[part - kFastBK / 8],
@@ -449,7 +471,10 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     int offA[4], offB[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        offA[i] = rrow * 256 + ((((wr * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
+        if (kARows)  // row wr*128 + 32i + lane%32, slot (k16/8 + lane/32) ^ ((row/4)%4); k16 added later
+            offA[i] = (wr * 128 + i * 32 + (lane & 31)) * kFastBK + ((h ^ (((lane & 31) >> 2) & 3)) * 8);
+        else
+            offA[i] = rrow * 256 + ((((wr * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
         offB[i] = kFastOperandElems + rrow * 256 +
                   ((((wc * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
     }
@@ -466,12 +491,19 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     struct Frags { bf16x8 a[4], b[4]; };
     // Quarter `part` of the fragment reads of a slice, in the order the MFMAs consume them
     // (a0 b0 | b1 b2 | b3 a1 | a2 a3): two fragments = four transposing LDS reads.
+    auto read_a = [&](int i, int k16, int a) -> bf16x8 {
+        if (kARows) {  // slots 2, 3 hold k16 = 16: flipping bit 1 of the slot = element offset ^ 16
+            const uint16_t* sa = ring + (i % kFastStages) * kFastStageElems + (offA[a] ^ k16);
+            return *reinterpret_cast<const lds_bf16x8*>((lds_void_t*)sa);
+        }
+        return read_frag_swz(ring + (i % kFastStages) * kFastStageElems + k16 * 256 + offA[a]);
+    };
     auto read_quarter = [&](Frags& f, int i, int k16, int part) {
         const uint16_t* st = ring + (i % kFastStages) * kFastStageElems + k16 * 256;
-        if (part == 0) { f.a[0] = read_frag_swz(st + offA[0]); f.b[0] = read_frag_swz(st + offB[0]); }
+        if (part == 0) { f.a[0] = read_a(i, k16, 0); f.b[0] = read_frag_swz(st + offB[0]); }
         else if (part == 1) { f.b[1] = read_frag_swz(st + offB[1]); f.b[2] = read_frag_swz(st + offB[2]); }
-        else if (part == 2) { f.b[3] = read_frag_swz(st + offB[3]); f.a[1] = read_frag_swz(st + offA[1]); }
-        else { f.a[2] = read_frag_swz(st + offA[2]); f.a[3] = read_frag_swz(st + offA[3]); }
+        else if (part == 2) { f.b[3] = read_frag_swz(st + offB[3]); f.a[1] = read_a(i, k16, 1); }
+        else { f.a[2] = read_a(i, k16, 2); f.a[3] = read_a(i, k16, 3); }
     };
     auto read_frags = [&](Frags& f, int i, int k16) {
 #pragma unroll
@@ -852,6 +884,7 @@ grass_status launch_grad_row_stats(const void* dY, grass_dy_layout layout, int64
         g.splits = 1;
         g.ktiles_per_split = static_cast<int>(T / kFastBK);
         g.a_fast = g.b_fast = 1;
+        g.a_rows = nullptr;
         const int64_t items = static_cast<int64_t>(g.tiles_m) * g.tiles_n;
         const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
         if (chunk * kNumXcd > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
@@ -866,7 +899,7 @@ grass_status launch_grad_row_stats(const void* dY, grass_dy_layout layout, int64
     if (m > 65535) return GRASS_ERR_SHAPE;
     float* G = reinterpret_cast<float*>(base);
     const grass_status st = launch_tn_gemm(dY, layout, ldy, X, ldx, dt, T, m, n, nullptr, nullptr, G,
-                                           GRASS_F32, n, base + g_bytes, s);
+                                           GRASS_F32, n, base + g_bytes, s, m);
     if (st != GRASS_OK) return st;
     return launch_row_stats(G, GRASS_F32, m, n, n, sumsq, s);
 }
@@ -927,7 +960,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     }
 
     const bool gathered = count > 1 || seg[0].idx != nullptr;
-    const bool pack = needs_pack(layout, gathered, total);
+    bool pack = needs_pack(layout, gathered, total);
     if (count > 1) {
         // One panel pays off while a slice of partial tiles of the joint problem still fits
         // the caches (fewer, fuller launches).  Beyond that every set fills the machine on its
@@ -959,6 +992,15 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                             (kFastBK + 1) * (copy_x ? nb : ldx) * 2 < (int64_t{1} << 32);
         if (!(a_ok && b_ok && off_ok && T >= kFastBK && total >= 8 && n >= 8)) tile = kTile128;
     }
+    // dY stored m x T: the selected rows are contiguous, so the large-tile kernel gathers them
+    // itself (no packing pass) when K is whole tiles and its 32-bit row offsets reach every row
+    bool a_rows_form = false;
+    if (tile == kTile256 && layout == GRASS_DY_MxT && count == 1 && T % kFastBK == 0 &&
+        aligned_to(dY0, 16) && ldy0 % 8 == 0 && getenv("GRASS_GEMM_PACK_MXT") == nullptr) {
+        const int64_t src_rows = seg[0].idx ? seg[0].src_rows : total;
+        a_rows_form = src_rows > 0 && src_rows * ldy0 * 2 + 64 < (int64_t{1} << 32);
+    }
+    if (a_rows_form) pack = false;
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
     const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
     const Plan p = plan_for(tile, T, total, n, pack);  // sized for all T rows; K tiling per tile kind
@@ -1000,6 +1042,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         g.Mcols = total;
         g.a_fast = aligned_to(dY0, 16) && ldy0 % 8 == 0;
     }
+    g.a_rows = a_rows_form ? seg[0].idx : nullptr;
     if (copy_x) {
         uint16_t* xa = reinterpret_cast<uint16_t*>(base + p.pack_bytes + round_up(p.partial_bytes, 256));
         const int chunks = static_cast<int>((nb / 2 + 1023) / 1024);
@@ -1032,7 +1075,9 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     const unsigned grid = static_cast<unsigned>(chunk * kNumXcd);
     hipError_t le;
     if (tile == kTile256) {
-        if (gathered)
+        if (a_rows_form)
+            tn_gemm_bf16_direct_kernel<false, false, true><<<grid, 256, 0, s>>>(g);
+        else if (gathered)
             tn_gemm_bf16_direct_kernel<false><<<grid, 256, 0, s>>>(g);
         else
             tn_gemm_bf16_direct_kernel<true><<<grid, 256, 0, s>>>(g);
@@ -1090,9 +1135,9 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
                             const int32_t* idx, const float* rho, void* C, grass_dtype odt,
-                            int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start,
-                            hipEvent_t ev_stop) {
-    const GemmSegment one{dY, ldy, idx, rho, C, ldc, mrows};
+                            int64_t ldc, void* ws, hipStream_t s, int64_t src_rows,
+                            hipEvent_t ev_start, hipEvent_t ev_stop) {
+    const GemmSegment one{dY, ldy, idx, rho, C, ldc, mrows, src_rows};
     return launch_tn_gemm_segments(&one, 1, layout, X, ldx, dt, T, n, odt, ws, s, ev_start, ev_stop);
 }
 

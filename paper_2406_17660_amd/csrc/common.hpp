@@ -101,8 +101,8 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
                             const int32_t* idx, const float* rho, void* C, grass_dtype odt,
-                            int64_t ldc, void* ws, hipStream_t s, hipEvent_t ev_start = nullptr,
-                            hipEvent_t ev_stop = nullptr);
+                            int64_t ldc, void* ws, hipStream_t s, int64_t src_rows,
+                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // The same product for several row sets that share X (one packed panel, one GEMM).
 struct GemmSegment {
@@ -113,6 +113,7 @@ struct GemmSegment {
     void* C;             // its rows x n output
     int64_t ldc;
     int64_t rows;
+    int64_t src_rows;    // rows of dY's matrix that idx may name (m); bounds address arithmetic
 };
 size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
                                   grass_dtype dt, grass_dy_layout layout);

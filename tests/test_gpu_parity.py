@@ -541,3 +541,54 @@ def test_fused_adam_scatter_with_bf16_moments(wdtype, m, n, r, dup):
     assert rel_fro(to_f64(M2), Mo) <= 1e-4 and rel_fro(to_f64(V2), Vo) <= 1e-4
     rest = np.setdiff1d(np.arange(m), sel)
     assert np.array_equal(to_np(W2)[rest], to_np(W)[rest])
+
+
+# ------------------------------------------------------------------------------ dY stored m x T
+@pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 224, 1056])
+def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T):
+    """dY stored m x T with T a whole number of K tiles: the large-tile kernel gathers the
+    selected rows itself (no packing pass); prologue, steady loop and drain at every length."""
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    m, n, r = 300, 264, 260
+    dY = randn((T, m), torch.bfloat16, 71, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 72)
+    idx, rho = make_idx(m, r, 73, True)
+    dYt = dY.t().contiguous()
+    got = to_f64(gpu_cgrad(dYt, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV),
+                           grass.DY_MxT))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert np.isfinite(got).all()
+    assert rel_fro(got, want) <= 2e-5
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("T,m,n,r,pad", [
+    (2048, 1024, 512, 512, 0),     # exact tiles
+    (1024, 5000, 520, 700, 0),     # rows spread over a tall matrix, 700 = 2 tiles + 188
+    (512, 640, 1376, 257, 64),     # one row past a tile boundary, padded leading dimension
+    (8192, 600, 264, 8, 0),        # a handful of rows, several K slices
+])
+def test_row_gathering_gemm_shapes_and_agreement_with_packing(monkeypatch, T, m, n, r, pad):
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    dYt = randn((m, T), torch.bfloat16, 75, scale=0.1, ld=T + pad)
+    X = randn((T, n), torch.bfloat16, 76)
+    idx, rho = make_idx(m, r, 77, False)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    got = gpu_cgrad(dYt, X, d_idx, d_rho, grass.DY_MxT)
+    want = ref.compressed_grad(to_np(dYt), to_np(X), idx, rho, ref.DY_MxT)
+    assert rel_fro(to_f64(got), want) <= 2e-5
+    assert np.abs(to_f64(got) - want).max() <= 1e-4 * np.abs(want).max()
+    # the packing path multiplies the same values in the same order inside a tile
+    monkeypatch.setenv("GRASS_GEMM_PACK_MXT", "1")
+    packed = gpu_cgrad(dYt, X, d_idx, d_rho, grass.DY_MxT)
+    assert rel_fro(to_f64(packed), want) <= 2e-5
+    assert (got - packed).abs().max().item() <= 1e-5 * float(np.abs(want).max())
+
+
+def test_dense_gradient_from_m_by_T_storage_without_packing(monkeypatch):
+    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    T, m, n = 1024, 520, 264
+    dY = randn((T, m), torch.bfloat16, 78, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 79)
+    G = gpu_dense(dY.t().contiguous(), X, torch.float32, grass.DY_MxT)
+    assert rel_fro(to_f64(G), ref.full_grad(to_np(dY), to_np(X))) <= 2e-5
