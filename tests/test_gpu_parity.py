@@ -592,3 +592,51 @@ def test_dense_gradient_from_m_by_T_storage_without_packing(monkeypatch):
     X = randn((T, n), torch.bfloat16, 79)
     G = gpu_dense(dY.t().contiguous(), X, torch.float32, grass.DY_MxT)
     assert rel_fro(to_f64(G), ref.full_grad(to_np(dY), to_np(X))) <= 2e-5
+
+
+# ------------------------------------------------------------------------------ largest sizes
+def test_most_rows_one_launch_takes():
+    """r = 65535, the most rows the row-indexed launches take (a grid dimension): compressed
+    gradient, Adam, scatter and the fused form against the oracle; r = 65536 is refused."""
+    T, m, n, r = 64, 70000, 24, 65535
+    dY = randn((T, m), torch.bfloat16, 91, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 92)
+    idx, rho = make_idx(m, r, 93, False)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    GC = gpu_cgrad(dY, X, d_idx, d_rho)
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert rel_fro(to_f64(GC), want) <= 2e-5
+    M = torch.zeros((r, n), device=DEV)
+    V = torch.zeros((r, n), device=DEV)
+    W = randn((m, n), torch.bfloat16, 94, scale=0.02)
+    W0 = to_f64(W).copy()
+    grass.adam_scatter(GC, M, V, LR, B1, B2, EPS, 1, W, d_idx, d_rho, 0.25)
+    f = np.float32
+    Mo, Vo = np.zeros((r, n)), np.zeros((r, n))
+    U = ref.adam_rows(to_f64(GC), Mo, Vo, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 1)
+    Wo = W0.copy()
+    ref.scatter_update(Wo, idx, rho, 0.25, U)
+    assert rel_fro(to_f64(W)[idx], Wo[idx]) <= TOL_BF16
+    assert rel_fro(to_f64(M), Mo) <= TOL_F32 and rel_fro(to_f64(V), Vo) <= TOL_F32
+    rest = np.setdiff1d(np.arange(m), idx)
+    assert np.array_equal(to_f64(W)[rest], W0[rest])
+    big = torch.zeros(65536, dtype=torch.int32, device=DEV)
+    with pytest.raises(grass.GrassError) as e:
+        grass.scatter_update(W, big, torch.ones(65536, device=DEV), 1.0, torch.zeros((65536, n), device=DEV))
+    assert e.value.code == grass.ERR_SHAPE
+
+
+def test_row_stats_and_selection_of_a_million_rows():
+    m, n, r = 1 << 20, 8, 1500
+    G = randn((m, n), torch.float32, 95)
+    ss = torch.empty(m, device=DEV)
+    grass.row_stats(G, ss)
+    want = ref.row_stats(to_np(G))
+    assert rel_fro(ss.cpu().numpy(), want) <= TOL_F32
+    host = ss.cpu().numpy()
+    for method, repl in [(grass.SEL_TOPR, False), (grass.SEL_MULTI_NORM, True), (grass.SEL_MULTI_NORM, False)]:
+        idx, rho, status = gpu_select(ss, r, method, repl, seed=17, refresh_id=3)
+        w_idx, w_rho, _ = ref.select_rows(host, r, method, repl, seed=17, refresh_id=3)
+        assert status == grass.OK
+        assert np.array_equal(idx.cpu().numpy(), w_idx), (method, repl)
+        assert np.array_equal(rho.cpu().numpy(), w_rho)
