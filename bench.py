@@ -260,7 +260,7 @@ def main():
         detail["compressed_grad_call_ms"] = med  # pack + GEMM + split-K reduce
         detail["compressed_grad_call_tflops"] = flops / (med * 1e-3) / 1e12
         st.adam_t = 0
-        med, _ = time_calls(lambda: st.adam_scatter(W), it)
+        med, _ = time_calls(lambda: st.adam_scatter(W), 100, warmup=10)
         esz = 2 if cfg.dtype == torch.bfloat16 else 4
         ab = r * n * (4 + 4 * st.M.element_size() + 2 * esz)
         detail["adam_scatter_ms"] = med

@@ -19,7 +19,7 @@ constexpr int kThreads = 256;
 
 struct AdamParams {
     float b1, one_minus_b1, b2, one_minus_b2;
-    float c1, c2;  // bias corrections 1 - beta^t
+    float inv_c1, inv_c2;  // reciprocals of the bias corrections 1 - beta^t
     float lr, eps;
 };
 
@@ -37,9 +37,11 @@ template <typename ST>
 __device__ __forceinline__ float adam_elem(float g, float& m, float& v, const AdamParams& p) {
     m = as_stored<ST>(p.b1 * m + p.one_minus_b1 * g);
     v = as_stored<ST>(p.b2 * v + p.one_minus_b2 * g * g);
-    const float ms = m / p.c1;
-    const float vs = v / p.c2;
-    return -p.lr * ms / (sqrtf(vs) + p.eps);
+    const float ms = m * p.inv_c1;
+    const float vs = v * p.inv_c2;
+    // hardware square root and reciprocal (about 1 ulp each): the kernel is otherwise bound by
+    // memory and the correctly rounded sequences would make its arithmetic show
+    return -p.lr * ms * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vs) + p.eps);
 }
 
 template <int VEC>
@@ -166,8 +168,11 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(
     }
 }
 
-// Adam on every row of the run, then one write of W; U stays in registers.
-template <typename WT, typename ST, int VEC>
+// Adam on every row of the run, then one write of W; U stays in registers.  A thread owns
+// UNROLL vectors of VEC columns, kThreads * VEC columns apart, and issues the loads of all of
+// them before it computes: the row index has to be fetched before anything else can start,
+// so the more bytes a wavefront then has in flight the better that latency is amortised.
+template <typename WT, typename ST, int VEC, int UNROLL>
 __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
     const float* __restrict__ GC, int64_t ldgc, ST* __restrict__ M, ST* __restrict__ V,
     int64_t n, int64_t r, AdamParams p, WT* __restrict__ W, int64_t ldw,
@@ -175,43 +180,60 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
     const int64_t j = blockIdx.y;
     const int32_t row = idx[j];
     if (j > 0 && idx[j - 1] == row) return;
-    int cnt;
-    const int64_t c = thread_col<VEC>(n, cnt);
-    if (cnt == 0) return;
-    WT* wp = W + static_cast<int64_t>(row) * ldw + c;
-    if (cnt == VEC) {
-        WVec<WT, VEC> wv;
-        wv.load(wp);  // issued first: independent of the Adam loads below
-        float acc[VEC];
+    const int64_t c0 = (static_cast<int64_t>(blockIdx.x) * kThreads * UNROLL + threadIdx.x) * VEC;
+    constexpr int64_t kStride = static_cast<int64_t>(kThreads) * VEC;
+    if (c0 >= n) return;
+    WT* wrow = W + static_cast<int64_t>(row) * ldw;
+    if (c0 + (UNROLL - 1) * kStride + VEC <= n) {  // every vector of this thread is whole
+        WVec<WT, VEC> wv[UNROLL];
+        float acc[UNROLL][VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        for (int u = 0; u < UNROLL; ++u) {
+            wv[u].load(wrow + c0 + u * kStride);  // issued first: independent of the Adam loads
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[u][e] = 0.f;
+        }
         for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
-            F32Vec<VEC> gv;
-            WVec<ST, VEC> mv, vv;
-            gv.load(GC + jj * ldgc + c);
-            mv.load(M + jj * n + c);
-            vv.load(V + jj * n + c);
+            F32Vec<VEC> gv[UNROLL];
+            WVec<ST, VEC> mv[UNROLL], vv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                gv[u].load(GC + jj * ldgc + c0 + u * kStride);
+                mv[u].load(M + jj * n + c0 + u * kStride);
+                vv[u].load(V + jj * n + c0 + u * kStride);
+            }
             const float s = rho[jj];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += s * adam_elem<ST>(gv.x[e], mv.x[e], vv.x[e], p);
-            mv.store(M + jj * n + c);
-            vv.store(V + jj * n + c);
+            for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    acc[u][e] += s * adam_elem<ST>(gv[u].x[e], mv[u].x[e], vv[u].x[e], p);
+                mv[u].store(M + jj * n + c0 + u * kStride);
+                vv[u].store(V + jj * n + c0 + u * kStride);
+            }
         }
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) wv.x[e] += alpha * acc[e];
-        wv.store(wp);
-    } else {
-        for (int e = 0; e < cnt; ++e) {
+        for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) wv[u].x[e] += alpha * acc[u][e];
+            wv[u].store(wrow + c0 + u * kStride);
+        }
+        return;
+    }
+    // ragged end of the row: element by element
+    for (int u = 0; u < UNROLL; ++u)
+        for (int e = 0; e < VEC; ++e) {
+            const int64_t c = c0 + u * kStride + e;
+            if (c >= n) return;
             float acc = 0.f;
             for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
-                float mm = load_as_f32(M + jj * n + c + e), vv = load_as_f32(V + jj * n + c + e);
-                acc += rho[jj] * adam_elem<ST>(GC[jj * ldgc + c + e], mm, vv, p);
-                store_from_f32(M + jj * n + c + e, mm);
-                store_from_f32(V + jj * n + c + e, vv);
+                float mm = load_as_f32(M + jj * n + c), vv = load_as_f32(V + jj * n + c);
+                acc += rho[jj] * adam_elem<ST>(GC[jj * ldgc + c], mm, vv, p);
+                store_from_f32(M + jj * n + c, mm);
+                store_from_f32(V + jj * n + c, vv);
             }
-            store_from_f32(wp + e, load_as_f32(wp + e) + alpha * acc);
+            store_from_f32(wrow + c, load_as_f32(wrow + c) + alpha * acc);
         }
-    }
 }
 
 template <typename GT, int VEC>
@@ -280,8 +302,8 @@ AdamParams make_params(float lr, float b1, float b2, float eps, int64_t t) {
     p.one_minus_b1 = 1.0f - b1;
     p.b2 = b2;
     p.one_minus_b2 = 1.0f - b2;
-    p.c1 = static_cast<float>(1.0 - pow(static_cast<double>(b1), static_cast<double>(t)));
-    p.c2 = static_cast<float>(1.0 - pow(static_cast<double>(b2), static_cast<double>(t)));
+    p.inv_c1 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(b1), static_cast<double>(t))));
+    p.inv_c2 = static_cast<float>(1.0 / (1.0 - pow(static_cast<double>(b2), static_cast<double>(t))));
     p.lr = lr;
     p.eps = eps;
     return p;
@@ -368,11 +390,20 @@ static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, void* Mv, 
     const bool vec = f32_rows_vectorisable(GC, ldgc) && w_rows_vectorisable(M, sdt, n) &&
                      w_rows_vectorisable(V, sdt, n) && w_rows_vectorisable(W, wdt, ldw);
     if (r > kMaxGridY) return GRASS_ERR_SHAPE;
-    if (vec)
-        adam_scatter_kernel<WT, ST, 4><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+    // wide rows: four vectors per thread (more bytes in flight per wavefront); narrow rows keep
+    // one so that a row still spreads over several workgroups
+    const int unroll = n >= 4096 ? 4 : (n >= 2048 ? 2 : 1);
+    if (vec && unroll == 4)
+        adam_scatter_kernel<WT, ST, 4, 4><<<grid_for(n, r, 16), kThreads, 0, s>>>(
+            GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
+    else if (vec && unroll == 2)
+        adam_scatter_kernel<WT, ST, 4, 2><<<grid_for(n, r, 8), kThreads, 0, s>>>(
+            GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
+    else if (vec)
+        adam_scatter_kernel<WT, ST, 4, 1><<<grid_for(n, r, 4), kThreads, 0, s>>>(
             GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
     else
-        adam_scatter_kernel<WT, ST, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
+        adam_scatter_kernel<WT, ST, 1, 1><<<grid_for(n, r, 1), kThreads, 0, s>>>(
             GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
     return launch_status();
 }
