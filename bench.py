@@ -3,12 +3,15 @@
 
 One "step" is one pass of Algorithm 1 for one linear layer over one synthetic token batch
 that is already resident in HBM: on steps with t = 0 (mod K, K = 200 as in the paper's
-pretraining runs) the refresh work (full gradient, row statistics, selection, state reset),
-(row statistic taken in the epilogue of the full-gradient GEMM, G itself is not stored),
-and on every step the compressed gradient, Adam on r x n, and the scatter into W.  The
+pretraining runs) the refresh work (row statistic of the full gradient, taken in the epilogue
+of the full-gradient GEMM so that G itself is not stored; selection; state reset), and on
+every step the compressed gradient, Adam on r x n, and the scatter into W.  The
 timed region starts at t = 0, so it always contains exactly one refresh per 200 steps.
 
-Prints ONE JSON line (see README / DESIGN for the fields).  Only one GPU is supported.
+Prints ONE JSON line: metric, value (layer steps per second), ms_per_step, the workload, a
+`roofline` object for the dominant kernel (the compressed-gradient GEMM, timed with HIP events
+around its launches) and a `cpu_baseline` object (the fp64 oracle on the host cores, on a bounded
+sample).  Only one GPU is supported.
 """
 import argparse
 import json
