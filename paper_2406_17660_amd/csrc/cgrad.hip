@@ -842,7 +842,12 @@ hipError_t launch_gemm_kernel(const GemmArgs& g, unsigned grid, hipStream_t s) {
 
 bool fused_stats_shape_ok(int64_t T, int64_t m, int64_t n, grass_dtype dt, grass_dy_layout layout,
                           int64_t ldy, int64_t ldx) {
-    return dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kFastBK && T % kFastBK == 0 &&
+    // the squares need complete sums, so the fused form cannot split K: it only pays when the
+    // output tiles alone fill most of the 256 compute units
+    const int64_t tiles = ((m + kFastBM - 1) / kFastBM) * ((n + kFastBN - 1) / kFastBN);
+    const char* force = getenv("GRASS_FUSED_STATS");  // "1": whenever the shape allows (tests)
+    return (tiles >= 192 || (force && force[0] == '1')) && dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kFastBK &&
+           T % kFastBK == 0 &&
            m >= 8 && n >= 8 && m % 8 == 0 && n % 8 == 0 && ldy % 8 == 0 && ldx % 8 == 0 &&
            (kFastBK + 1) * ldy * 2 < (int64_t{1} << 32) && (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
 }

@@ -348,7 +348,13 @@ def test_compressed_grad_large_tile_chosen_by_shape():
     (torch.bfloat16, grass.DY_MxT, 512, 256, 256, 0),      # transposed storage: via fp32 G
     (torch.float32, grass.DY_TxM, 512, 256, 256, 0),       # fp32 inputs: via fp32 G
 ])
-def test_grad_row_stats_without_storing_G(dtype, layout, T, m, n, pad):
+@pytest.mark.parametrize("force_fused", [True, False])
+def test_grad_row_stats_without_storing_G(monkeypatch, force_fused, dtype, layout, T, m, n, pad):
+    """The fused form is chosen by itself only for layers with enough output tiles to fill
+    the machine; here it is forced so that small shapes exercise it, and the same shapes also
+    run the way the launcher would choose (fp32 G inside the workspace, then the statistic)."""
+    if force_fused:
+        monkeypatch.setenv("GRASS_FUSED_STATS", "1")
     dY = randn((T, m), dtype, 31, scale=0.1, ld=m + pad)
     X = randn((T, n), dtype, 32, ld=n + pad)
     dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
@@ -364,9 +370,11 @@ def test_grad_row_stats_without_storing_G(dtype, layout, T, m, n, pad):
 
 
 def test_grad_row_stats_small_workspace_is_enough_when_fused():
-    """The point of the fused form: no m x n buffer.  4096 x 4096 needs well under 1 MB."""
+    """The point of the fused form: no m x n buffer.  4096 x 4096 needs well under 1 MB; a
+    small layer (too few tiles to fill the machine without splitting K) keeps G in the workspace."""
     assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.BF16) < 1 << 20
     assert grass.grad_row_stats_workspace(131072, 4096, 4096, grass.F32) > 4096 * 4096 * 4
+    assert grass.grad_row_stats_workspace(65536, 512, 512, grass.BF16) > 512 * 512 * 4
 
 
 # ------------------------------------------------------------------------------ column projection
