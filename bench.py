@@ -142,9 +142,13 @@ def bench_block(args, cfg):
     T = args.tokens or cfg.T
     shapes, groups = workloads.llama_block(hidden, inter)
     dY, X, W = workloads.make_block_inputs(cfg, shapes, groups, "cuda", T=T)
+    layout = grass.DY_TxM
+    if args.layout == "mxt":
+        dY = {name: g.t().contiguous() for name, g in dY.items()}
+        layout = grass.DY_MxT
     blk = GrassBlock(shapes, groups, cfg.r, T, cfg.dtype, cfg.method, cfg.replacement,
                      alpha=cfg.alpha, adam=AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps),
-                     seed=workloads.BASE_SEED)
+                     seed=workloads.BASE_SEED, layout=layout)
     sched = RewarmSchedule(base_lr=cfg.lr, K=REFRESH_EVERY, rewarm=REFRESH_EVERY)
     blk.refresh(dY, X)  # set-up: refresh-step workspaces are allocated outside the timed region
     for _ in range(args.warmup):
@@ -167,7 +171,8 @@ def bench_block(args, cfg):
         "dtype": "bf16" if cfg.dtype == torch.bfloat16 else "f32", "data": "synthetic",
         "config": {"workload": f"LLaMA-{args.block} block: q,k,v,o {hidden}x{hidden}, gate,up "
                                f"{inter}x{hidden}, down {hidden}x{inter}; T={T}, r={cfg.r}, "
-                               f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection"},
+                               f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection, "
+                               f"dY stored {args.layout}"},
         "compressed_grad_tflops_incl_gather_and_reduce_and_adam": flops * args.steps / (ms * 1e-3) / 1e12,
     }))
 

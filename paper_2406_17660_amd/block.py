@@ -62,23 +62,25 @@ class GrassBlock:
 
     def __init__(self, shapes, groups, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, device="cuda",
-                 reset_state=True):
+                 reset_state=True, layout=grass.DY_TxM):
         self.adam = adam or AdamHyper()
         self.reset_state = reset_state
+        self.layout = layout  # storage of every dY handed to refresh() / step()
         named = [n for g in groups for n in g]
         assert len(set(named)) == len(named) and set(named) <= set(shapes)
         self.groups = [tuple(g) for g in groups] + [(n,) for n in shapes if n not in named]
         self.layers = {}
         for k, (name, (m, n)) in enumerate(shapes.items()):
             self.layers[name] = GrassLayer(m, n, min(r, m), T, dtype, method, replacement, scale,
-                                           alpha, self.adam, seed + k, device=device)
+                                           alpha, self.adam, seed + k, device=device, layout=layout)
         self.ws = {}
         dt = grass.F32 if dtype == torch.float32 else grass.BF16
         for g in self.groups:
             ns = {self.layers[name].n for name in g}
             assert len(ns) == 1, "layers of a group read the same activations"
             rs = [self.layers[name].r for name in g]
-            self.ws[g] = grass.workspace(grass.cgrad_group_workspace(T, ns.pop(), rs, dt), device)
+            self.ws[g] = grass.workspace(grass.cgrad_group_workspace(T, ns.pop(), rs, dt, layout),
+                                         device)
         self.t = 0
 
     def refresh(self, dY, X):
@@ -93,7 +95,7 @@ class GrassBlock:
             members = [self.layers[name] for name in g]
             grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
                                         [l.rho for l in members], [l.GC for l in members],
-                                        self.ws[g])
+                                        self.ws[g], self.layout)
             for name, l in zip(g, members):
                 if lr is not None:
                     l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)

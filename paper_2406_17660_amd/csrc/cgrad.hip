@@ -50,22 +50,25 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
 // of `out` are ldo apart (several matrices may fill adjacent column ranges of one panel).
 // Thread = 4 adjacent j; 2^tpr_log2 threads cover the columns of one row of t (a narrow panel,
 // r = 128 say, puts several rows of t side by side in a workgroup instead of idling most of
-// it), and every thread loops over kPackRows values of t.  Wave stores are contiguous.
+// it), and every thread loops over rows_per_thread (4 .. kPackRows) values of t: fewer when
+// the matrix is small, so that the launch still has a few thousand workgroups to hide the
+// latency of the gather.  Wave stores are contiguous.
 constexpr int kPackRows = 16;
 __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restrict__ dY, int64_t ldy,
                                                        int64_t T, const int32_t* __restrict__ idx,
                                                        int64_t r, int64_t rp, int64_t ldo,
-                                                       int tpr_log2, uint16_t* __restrict__ out) {
+                                                       int tpr_log2, int rows_per_thread,
+                                                       uint16_t* __restrict__ out) {
     const int tpr = 1 << tpr_log2, rows_per_pass = 256 >> tpr_log2;
     const int64_t j0 = (static_cast<int64_t>(blockIdx.x) * tpr + (threadIdx.x & (tpr - 1))) * 4;
     if (j0 >= rp) return;
     int64_t col[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) col[e] = j0 + e < r ? (idx ? idx[j0 + e] : j0 + e) : -1;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kPackRows * rows_per_pass +
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_thread * rows_per_pass +
                        (threadIdx.x >> tpr_log2);
 #pragma unroll 4
-    for (int tt = 0; tt < kPackRows; ++tt) {
+    for (int tt = 0; tt < rows_per_thread; ++tt) {
         const int64_t t = t0 + static_cast<int64_t>(tt) * rows_per_pass;
         if (t >= T) break;
         const uint16_t* row = dY + t * ldy;
@@ -1027,13 +1030,17 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                 if (layout == GRASS_DY_TxM) {
                     int tpr_log2 = 8;  // threads per row of t: the power of two covering width / 4
                     while (tpr_log2 > 0 && (int64_t{4} << (tpr_log2 - 1)) >= width) --tpr_log2;
-                    const int64_t rows_per_wg = static_cast<int64_t>(kPackRows) * (256 >> tpr_log2);
-                    const dim3 grid(static_cast<unsigned>((width + (int64_t{4} << tpr_log2) - 1) /
-                                                          (int64_t{4} << tpr_log2)),
+                    const int64_t gx = (width + (int64_t{4} << tpr_log2) - 1) / (int64_t{4} << tpr_log2);
+                    const int64_t passes = (T + (256 >> tpr_log2) - 1) / (256 >> tpr_log2);
+                    int64_t rpt = passes * gx / 2048;  // aim at >= 2048 workgroups
+                    rpt = rpt < 4 ? 4 : (rpt > kPackRows ? kPackRows : rpt);
+                    const int64_t rows_per_wg = rpt * (256 >> tpr_log2);
+                    const dim3 grid(static_cast<unsigned>(gx),
                                     static_cast<unsigned>((T + rows_per_wg - 1) / rows_per_wg));
                     pack_txm_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(seg[i].dY),
                                                          seg[i].ldy, T, seg[i].idx, seg[i].rows,
-                                                         width, p.rp, tpr_log2, panel + off);
+                                                         width, p.rp, tpr_log2,
+                                                         static_cast<int>(rpt), panel + off);
                 } else {
                     const dim3 grid(static_cast<unsigned>((width + 63) / 64),
                                     static_cast<unsigned>((T + 63) / 64));

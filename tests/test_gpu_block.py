@@ -22,10 +22,10 @@ def draw(shape, seed, scale=1.0):
     return (torch.randn(shape, generator=g, device=DEV) * scale).to(torch.bfloat16)
 
 
-@pytest.mark.parametrize("method,replacement,reset", [("topr", False, True),
-                                                      ("multi_norm", False, False),
-                                                      ("multi_norm", True, True)])
-def test_block_training_steps_match_layerwise_oracle(method, replacement, reset):
+@pytest.mark.parametrize("method,replacement,reset,layout", [
+    ("topr", False, True, grass.DY_TxM), ("multi_norm", False, False, grass.DY_TxM),
+    ("multi_norm", True, True, grass.DY_TxM), ("multi_norm", True, True, grass.DY_MxT)])
+def test_block_training_steps_match_layerwise_oracle(method, replacement, reset, layout):
     hidden, inter, T, r, K, steps = 128, 344, 640, 24, 3, 7
     shapes = {"q": (hidden, hidden), "k": (hidden, hidden), "v": (hidden, hidden),
               "o": (hidden, hidden), "gate": (inter, hidden), "up": (inter, hidden),
@@ -34,7 +34,7 @@ def test_block_training_steps_match_layerwise_oracle(method, replacement, reset)
     adam = AdamHyper(lr=1e-3)
     sched = RewarmSchedule(base_lr=2e-3, warmup=4, total=20, min_ratio=0.1, K=K, rewarm=3)
     blk = GrassBlock(shapes, groups, r, T, torch.bfloat16, method, replacement, alpha=0.25,
-                     adam=adam, seed=77, reset_state=reset)
+                     adam=adam, seed=77, reset_state=reset, layout=layout)
     W = {name: draw(s, 500 + i, 0.05) for i, (name, s) in enumerate(shapes.items())}
     W0 = {name: to_np(w).copy() for name, w in W.items()}
     orc = {name: OracleLayer(to_f64(W[name]), min(r, shapes[name][0]), REF_METHOD[method],
@@ -46,7 +46,8 @@ def test_block_training_steps_match_layerwise_oracle(method, replacement, reset)
         X = {g: draw((T, shapes[g[0]][1]), 1000 + 10 * t + gi) for gi, g in enumerate(blk.groups)}
         dY = {name: draw((T, s[0]), 2000 + 10 * t + i, 0.1) for i, (name, s) in enumerate(shapes.items())}
         refreshed = sched.is_refresh(t)
-        blk.train_step(dY, X, W, sched)
+        dY_dev = dY if layout == grass.DY_TxM else {k: v.t().contiguous() for k, v in dY.items()}
+        blk.train_step(dY_dev, X, W, sched)
         lr = sched.lr(t)
         for g in blk.groups:
             Xh = to_np(X[g])
