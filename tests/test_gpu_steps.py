@@ -259,6 +259,39 @@ def test_config5_full_size_sampled(layer):
     assert np.array_equal(to_np(W)[rest], W0_bits[rest])
 
 
+def test_config5_full_size_row_gathering_gemm_sampled():
+    """The 7B attention layer with dY stored m x T (bench.py --layout mxt): the GEMM gathers the
+    selected rows itself.  Sampled entries against the oracle, and the whole r x n result
+    against the T x m path (same products, different summation order)."""
+    cfg = workloads.CONFIGS[5]
+    L = cfg.layers[0]
+    T, m, n, r = cfg.T, L.m, L.n, cfg.r
+    dY = workloads.make_dY(cfg, 0, 0, DEV)
+    X = workloads.make_X(cfg, 0, 0, DEV)
+    rng = np.random.default_rng(55)
+    idx = np.sort(rng.choice(m, r, replace=True)).astype(np.int32)  # duplicates included
+    rho = rng.uniform(0.5, 2.0, r).astype(np.float32)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    GC_t = torch.empty((r, n), device=DEV)
+    ws = grass.workspace(grass.cgrad_workspace(T, m, n, r, grass.BF16, grass.DY_MxT))
+    dYt = dY.t().contiguous()
+    grass.compressed_grad(dYt, X, d_idx, d_rho, GC_t, ws, grass.DY_MxT)
+    js = np.arange(3, r, 61)
+    cols = np.arange(5, n, 191)
+    sel_cols = torch.from_numpy(idx[js].astype(np.int64)).to(DEV)
+    want = ref.compressed_grad(to_np(dY[:, sel_cols].contiguous()),
+                               np.ascontiguousarray(to_np(X)[:, cols]),
+                               np.arange(len(js), dtype=np.int32), rho[js])
+    got = to_f64(GC_t)[np.ix_(js, cols)]
+    assert rel_fro(got, want) <= 2e-5
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+    del dYt
+    GC = torch.empty((r, n), device=DEV)
+    ws = grass.workspace(grass.cgrad_workspace(T, m, n, r, grass.BF16))
+    grass.compressed_grad(dY, X, d_idx, d_rho, GC, ws)
+    assert rel_fro(to_f64(GC_t), to_f64(GC)) <= 2e-6
+
+
 # ------------------------------------------------------------------------------ column projection
 @pytest.mark.parametrize("method,replacement", [("topr", False), ("multi_norm", True)])
 def test_column_projection_steps(method, replacement):
