@@ -261,6 +261,13 @@ def main():
         "host_wall_s": wall,
     }
 
+    if not args.no_extras:
+        # context for the fraction above: what a kernel of nothing but this matrix instruction
+        # sustains on this very machine (its clock under that load varies from box to box)
+        probe = grass.probe_mfma_rate()
+        out["roofline"]["mfma_only_kernel_tflops_this_box"] = probe
+        out["roofline"]["frac_of_mfma_only_kernel"] = gemm_tflops / probe
+
     if not args.no_extras and args.side == "rows" and args.layout == "txm":
         detail = {}
         it = 20

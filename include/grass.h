@@ -275,6 +275,19 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
                                const int32_t* idx, const float* rho, int64_t r, float* out,
                                int64_t ldo, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement aid (not a step of the method; for benchmarks that want to state what the
+ * matrix cores of the machine at hand sustain).  Launches a kernel that does nothing but
+ * issue the bf16 matrix instruction of the compressed-gradient GEMM on every compute unit
+ * (non-zero operands in registers, no memory traffic): 256 workgroups x 4 wavefronts x
+ * `iters` x 16 instructions.  `out` (device, at least 65536 floats, `out_floats` says how
+ * many) receives one value per thread so that the work cannot be optimised away; `*flops`
+ * (host) receives the number of floating-point operations the launch performs.  The caller
+ * times the launch on `stream`.
+ * Errors: NULL, SHAPE (iters < 1, out too small). */
+grass_status grass_probe_mfma_rate(float* out, size_t out_floats, int iters, double* flops,
+                                   void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -270,4 +270,13 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
     return launch_gather_rows(G, gdt, n, ldg, idx, rho, r, out, ldo, as_stream(stream));
 }
 
+grass_status grass_probe_mfma_rate(float* out, size_t out_floats, int iters, double* flops,
+                                   void* stream) {
+    if (!out || !flops) return GRASS_ERR_NULL;
+    if (iters < 1 || out_floats < static_cast<size_t>(kProbeWorkgroups) * 256) return GRASS_ERR_SHAPE;
+    // 4 wavefronts per workgroup, 16 instructions of 32 x 32 x 16 multiply-adds per iteration
+    *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+    return launch_probe_mfma_rate(out, iters, as_stream(stream));
+}
+
 }  // extern "C"

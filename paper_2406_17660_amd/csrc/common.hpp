@@ -104,6 +104,11 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
                             int64_t ldc, void* ws, hipStream_t s, int64_t src_rows,
                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
+// Measurement aid: kProbeWorkgroups workgroups of 256 threads, each wavefront issuing
+// 16 * iters matrix instructions; `out` takes kProbeWorkgroups * 256 floats.
+constexpr int kProbeWorkgroups = 256;
+grass_status launch_probe_mfma_rate(float* out, int iters, hipStream_t s);
+
 // The same product for several row sets that share X (one packed panel, one GEMM).
 struct GemmSegment {
     const void* dY;      // this set's left operand

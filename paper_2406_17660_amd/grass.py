@@ -27,7 +27,7 @@ EXPORTS = [
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
-    "grass_adam_rows_state", "grass_adam_scatter_state",
+    "grass_adam_rows_state", "grass_adam_scatter_state", "grass_probe_mfma_rate",
 ]
 
 _lib = None
@@ -78,6 +78,7 @@ def lib():
     L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
     L.grass_grad_row_stats_workspace.restype = sz
     L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
+    L.grass_probe_mfma_rate.argtypes = [vp, sz, i32, C.POINTER(C.c_double), vp]
     L.grass_cgrad_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
     L.grass_cgrad_group_workspace.restype = sz
     L.grass_compressed_grad_group.argtypes = [i32, vp, i32, vp, vp, i64, i32, i64, vp, i64, vp,
@@ -331,3 +332,21 @@ def gather_rows(G, idx, rho, out):
 def workspace(nbytes: int, device="cuda"):
     """A device byte buffer of at least `nbytes` (torch owns the memory)."""
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def probe_mfma_rate(iters=20000):
+    """TFLOP/s of a kernel that only issues the GEMM's bf16 matrix instruction on every compute
+    unit (measurement aid: what the matrix cores of this machine sustain under that load)."""
+    out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    flops = C.c_double(0.0)
+
+    def launch():
+        _check(lib().grass_probe_mfma_rate(C.c_void_p(out.data_ptr()), out.numel(), iters,
+                                           C.byref(flops), _stream()), "grass_probe_mfma_rate")
+    launch()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    launch()
+    b.record()
+    torch.cuda.synchronize()
+    return flops.value / (a.elapsed_time(b) * 1e-3) / 1e12

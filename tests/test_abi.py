@@ -178,6 +178,16 @@ def test_adam_and_scatter_validation():
     assert g(FAKE, 0, 4, 8, 8, FAKE, FAKE, 2, FAKE, 7, None) == grass.ERR_SHAPE
 
 
+def test_probe_validation():
+    import ctypes as C
+    f = grass.lib().grass_probe_mfma_rate
+    flops = C.c_double(0.0)
+    assert f(None, 1 << 16, 10, C.byref(flops), None) == grass.ERR_NULL
+    assert f(FAKE, 1 << 16, 10, None, None) == grass.ERR_NULL
+    assert f(FAKE, 1 << 16, 0, C.byref(flops), None) == grass.ERR_SHAPE
+    assert f(FAKE, 1000, 10, C.byref(flops), None) == grass.ERR_SHAPE
+
+
 def test_grad_row_stats_validation():
     L = grass.lib()
     f = L.grass_grad_row_stats

@@ -53,3 +53,9 @@ def test_step_replayed_from_a_graph_equals_eager_step(layout, T, m, n, r):
         got = (W, st.M, st.V, st.GC)
         for a, b in zip(got, want):
             assert torch.equal(a, b), f"replay {replay} differs from the eager step"
+
+
+def test_matrix_core_probe_reports_a_plausible_rate():
+    """The measurement aid runs and lands between a tenth of and just above the datasheet peak."""
+    rate = grass.probe_mfma_rate(iters=2000)
+    assert 250.0 < rate < 2600.0
