@@ -67,6 +67,13 @@ def sumsq_case(m, kind, seed):
         s = np.zeros(m)
     elif kind == "tiny":
         s = rng.standard_normal(m) ** 2 * 1e-40  # denormals
+    elif kind == "wide":
+        s = 10.0 ** rng.uniform(-30, 30, m)  # sixty decades: most quantised weights are 1
+    elif kind == "one_hot":
+        s = np.zeros(m)
+        s[m // 3] = 7.0  # a single row carries all the weight
+    elif kind == "equal":
+        s = np.full(m, 3.25)
     else:
         raise ValueError(kind)
     return s.astype(np.float32)
@@ -76,7 +83,8 @@ def sumsq_case(m, kind, seed):
 @pytest.mark.parametrize("m,r,kind", [(1, 1, "chi2"), (5, 3, "chi2"), (64, 64, "lognormal"),
                                       (65, 17, "ties"), (1000, 128, "chi2"), (1000, 999, "ties"),
                                       (4097, 1024, "lognormal"), (512, 128, "zeros"),
-                                      (300, 100, "tiny"), (13824, 1024, "chi2")])
+                                      (300, 100, "tiny"), (13824, 1024, "chi2"),
+                                      (2000, 300, "wide"), (777, 50, "one_hot"), (640, 640, "equal")])
 def test_select_rows_bit_exact(method, replacement, m, r, kind):
     ss = sumsq_case(m, kind, 7 * m + r)
     d_ss = torch.from_numpy(ss).to(DEV)
