@@ -51,6 +51,8 @@ def parse():
                         "selected rows are contiguous and are gathered inside the GEMM")
     p.add_argument("--adam-state", choices=["f32", "bf16"], default="f32",
                    help="dtype of the Adam moments (the headline configuration keeps them in fp32)")
+    p.add_argument("--concurrent-groups", action="store_true",
+                   help="with --block: every group of layers on a HIP stream of its own")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
     p.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -148,7 +150,8 @@ def bench_block(args, cfg):
         layout = grass.DY_MxT
     blk = GrassBlock(shapes, groups, cfg.r, T, cfg.dtype, cfg.method, cfg.replacement,
                      alpha=cfg.alpha, adam=AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps),
-                     seed=workloads.BASE_SEED, layout=layout)
+                     seed=workloads.BASE_SEED, layout=layout,
+                     concurrent_groups=args.concurrent_groups)
     sched = RewarmSchedule(base_lr=cfg.lr, K=REFRESH_EVERY, rewarm=REFRESH_EVERY)
     blk.refresh(dY, X)  # set-up: refresh-step workspaces are allocated outside the timed region
     for _ in range(args.warmup):
@@ -172,7 +175,8 @@ def bench_block(args, cfg):
         "config": {"workload": f"LLaMA-{args.block} block: q,k,v,o {hidden}x{hidden}, gate,up "
                                f"{inter}x{hidden}, down {hidden}x{inter}; T={T}, r={cfg.r}, "
                                f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection, "
-                               f"dY stored {args.layout}"},
+                               f"dY stored {args.layout}"
+                               f"{', groups on concurrent streams' if args.concurrent_groups else ''}"},
         "compressed_grad_tflops_incl_gather_and_reduce_and_adam": flops * args.steps / (ms * 1e-3) / 1e12,
     }))
 

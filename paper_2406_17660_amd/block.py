@@ -62,7 +62,13 @@ class GrassBlock:
 
     def __init__(self, shapes, groups, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, device="cuda",
-                 reset_state=True, layout=grass.DY_TxM):
+                 reset_state=True, layout=grass.DY_TxM, concurrent_groups=False):
+        # concurrent_groups: issue every group on a HIP stream of its own (default priority),
+        # forked from and joined back into the caller's stream.  The groups are independent
+        # (own inputs, state and workspaces); small layers, whose kernels do not fill the
+        # machine, then overlap instead of queueing behind each other's launch gaps and tails.
+        self.streams = None
+        self.concurrent_groups = concurrent_groups
         self.adam = adam or AdamHyper()
         self.reset_state = reset_state
         self.layout = layout  # storage of every dY handed to refresh() / step()
@@ -89,17 +95,34 @@ class GrassBlock:
             for name in g:
                 self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state)
 
+    def _step_group(self, g, dY, X, W, lr):
+        members = [self.layers[name] for name in g]
+        grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
+                                    [l.rho for l in members], [l.GC for l in members],
+                                    self.ws[g], self.layout)
+        for name, l in zip(g, members):
+            if lr is not None:
+                l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
+            l.adam_scatter(W[name])
+
     def step(self, dY, X, W, lr=None):
         """One regular step of every layer: grouped G_C, then Adam and the row update."""
-        for g in self.groups:
-            members = [self.layers[name] for name in g]
-            grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
-                                        [l.rho for l in members], [l.GC for l in members],
-                                        self.ws[g], self.layout)
-            for name, l in zip(g, members):
-                if lr is not None:
-                    l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
-                l.adam_scatter(W[name])
+        if not self.concurrent_groups:
+            for g in self.groups:
+                self._step_group(g, dY, X, W, lr)
+            return
+        if self.streams is None:
+            self.streams = [torch.cuda.Stream() for _ in self.groups]
+        main = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for g, side in zip(self.groups, self.streams):
+            side.wait_event(fork)
+            with torch.cuda.stream(side):
+                self._step_group(g, dY, X, W, lr)
+                joined = torch.cuda.Event()
+                joined.record(side)
+            main.wait_event(joined)
 
     def train_step(self, dY, X, W, schedule: RewarmSchedule):
         """Step t of Algorithm 1 under `schedule`: refresh when t = 0 mod K, then update."""

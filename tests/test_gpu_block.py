@@ -22,10 +22,11 @@ def draw(shape, seed, scale=1.0):
     return (torch.randn(shape, generator=g, device=DEV) * scale).to(torch.bfloat16)
 
 
-@pytest.mark.parametrize("method,replacement,reset,layout", [
-    ("topr", False, True, grass.DY_TxM), ("multi_norm", False, False, grass.DY_TxM),
-    ("multi_norm", True, True, grass.DY_TxM), ("multi_norm", True, True, grass.DY_MxT)])
-def test_block_training_steps_match_layerwise_oracle(method, replacement, reset, layout):
+@pytest.mark.parametrize("method,replacement,reset,layout,concurrent", [
+    ("topr", False, True, grass.DY_TxM, False), ("multi_norm", False, False, grass.DY_TxM, False),
+    ("multi_norm", True, True, grass.DY_TxM, True), ("multi_norm", True, True, grass.DY_MxT, False),
+    ("topr", False, True, grass.DY_MxT, True)])
+def test_block_training_steps_match_layerwise_oracle(method, replacement, reset, layout, concurrent):
     hidden, inter, T, r, K, steps = 128, 344, 640, 24, 3, 7
     shapes = {"q": (hidden, hidden), "k": (hidden, hidden), "v": (hidden, hidden),
               "o": (hidden, hidden), "gate": (inter, hidden), "up": (inter, hidden),
@@ -34,7 +35,8 @@ def test_block_training_steps_match_layerwise_oracle(method, replacement, reset,
     adam = AdamHyper(lr=1e-3)
     sched = RewarmSchedule(base_lr=2e-3, warmup=4, total=20, min_ratio=0.1, K=K, rewarm=3)
     blk = GrassBlock(shapes, groups, r, T, torch.bfloat16, method, replacement, alpha=0.25,
-                     adam=adam, seed=77, reset_state=reset, layout=layout)
+                     adam=adam, seed=77, reset_state=reset, layout=layout,
+                     concurrent_groups=concurrent)
     W = {name: draw(s, 500 + i, 0.05) for i, (name, s) in enumerate(shapes.items())}
     W0 = {name: to_np(w).copy() for name, w in W.items()}
     orc = {name: OracleLayer(to_f64(W[name]), min(r, shapes[name][0]), REF_METHOD[method],
