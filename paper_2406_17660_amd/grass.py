@@ -101,7 +101,13 @@ def _check(code, where):
         raise GrassError(code, where)
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream():
+    """Handle of torch's current stream on the current device (every call is issued there)."""
+    if _raw_stream is not None:  # the same handle without building a Stream object per call
+        return C.c_void_p(_raw_stream(torch.cuda.current_device()))
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
