@@ -656,3 +656,30 @@ def test_row_stats_and_selection_of_a_million_rows():
         assert status == grass.OK
         assert np.array_equal(idx.cpu().numpy(), w_idx), (method, repl)
         assert np.array_equal(rho.cpu().numpy(), w_rho)
+
+
+def test_compressed_grad_group_too_large_for_a_joint_panel_runs_set_by_set():
+    """Three sets whose joint slice of partial tiles would exceed the cached size: the group
+    call falls back to one GEMM per set inside the same call.  Sampled rows against the oracle."""
+    T, n, ms, rs = 512, 2048, (1100, 1300, 1100), (1024, 1024, 1000)
+    X = randn((T, n), torch.bfloat16, 81)
+    dYs, idxs, rhos, host = [], [], [], []
+    for i, (m, r) in enumerate(zip(ms, rs)):
+        dY = randn((T, m), torch.bfloat16, 82 + i, scale=0.1)
+        idx, rho = make_idx(m, r, 86 + i, duplicates=False)
+        host.append((dY, idx, rho))
+        dYs.append(dY)
+        idxs.append(torch.from_numpy(idx).to(DEV))
+        rhos.append(torch.from_numpy(rho).to(DEV))
+    GCs = [torch.full((r, n), float("nan"), dtype=torch.float32, device=DEV) for r in rs]
+    ws = grass.workspace(grass.cgrad_group_workspace(T, n, rs, grass.BF16))
+    grass.compressed_grad_group(dYs, X, idxs, rhos, GCs, ws)
+    Xh = to_np(X)
+    for (dY, idx, rho), GC in zip(host, GCs):
+        assert torch.isfinite(GC).all()
+        js = np.arange(1, len(idx), 67)
+        want = ref.compressed_grad(to_np(dY), Xh, idx[js], rho[js])
+        got = to_f64(GC)[js]
+        assert rel_fro(got, want) <= 2e-5
+        single = gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV))
+        assert torch.equal(single, GC)  # the very same launches as the single call
