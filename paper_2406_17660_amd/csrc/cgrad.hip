@@ -105,6 +105,55 @@ __global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restric
     }
 }
 
+// The same gather-and-transpose with 16-byte accesses on both sides, for rows that allow them
+// (dYt 16-byte aligned, ldy and ldo multiples of 8).  A workgroup turns 64 (j) x 256 (t): each
+// lane loads 8 consecutive t of one selected row (a wavefront reads 2 x 512 contiguous bytes),
+// the block goes to LDS as [j][t], and the transposing 8-byte LDS read hands every lane four
+// consecutive j of one t, so a lane stores 8 values of j (16 bytes) of its own panel row per
+// step.  LDS rows are padded by 16 elements: the four rows one 16-lane read touches then fall
+// into different banks.
+constexpr int kPackWideJ = 64, kPackWideT = 256, kPackWideLd = kPackWideT + 16;
+__global__ __launch_bounds__(256) void pack_mxt_wide_kernel(const uint16_t* __restrict__ dYt,
+                                                            int64_t ldy, int64_t T,
+                                                            const int32_t* __restrict__ idx,
+                                                            int64_t r, int64_t rp, int64_t ldo,
+                                                            uint16_t* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kPackWideJ * kPackWideLd];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * kPackWideJ;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kPackWideT;
+    const int chunk = threadIdx.x & 31;  // 8 values of t each
+#pragma unroll
+    for (int pass = 0; pass < kPackWideJ / 8; ++pass) {
+        const int jj = pass * 8 + (threadIdx.x >> 5);
+        const int64_t j = j0 + jj, t = t0 + chunk * 8;
+        s16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (j < r && t < T) {
+            const uint16_t* src = dYt + static_cast<int64_t>(idx ? idx[j] : j) * ldy + t;
+            if (t + 8 <= T) {
+                v = *reinterpret_cast<const s16x8*>(src);
+            } else {
+                for (int e = 0; e < 8; ++e)
+                    if (t + e < T) v[e] = static_cast<short>(src[e]);
+            }
+        }
+        *reinterpret_cast<s16x8*>(tile + jj * kPackWideLd + chunk * 8) = v;
+    }
+    __syncthreads();
+    // wavefront w owns t = 64w .. 64w+63 of the block; lane L ends up with t = 64w + L
+    const int grp = lane >> 4, i = lane & 15;
+    const uint16_t* src = tile + (i >> 2) * kPackWideLd + w * 64 + grp * 16 + 4 * (i & 3);
+    const int64_t t = t0 + w * 64 + lane;
+    uint16_t* dst = out + (t < T ? t : 0) * ldo + j0;
+#pragma unroll
+    for (int j8 = 0; j8 < kPackWideJ; j8 += 8) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + j8 * kPackWideLd));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + (j8 + 4) * kPackWideLd));
+        if (t < T && j0 + j8 < rp)  // rp is a multiple of 8: whole vectors only
+            *reinterpret_cast<s16x8*>(dst + j8) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+}
+
 // out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np even, rows of `out` np apart): a copy
 // of a matrix whose rows start at odd element offsets (n not a multiple of 8, as in the
 // 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM can take.  `in` itself
@@ -1041,6 +1090,13 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                                                          seg[i].ldy, T, seg[i].idx, seg[i].rows,
                                                          width, p.rp, tpr_log2,
                                                          static_cast<int>(rpt), panel + off);
+                } else if (aligned_to(seg[i].dY, 16) && seg[i].ldy % 8 == 0 && p.rp % 8 == 0 &&
+                           width % 8 == 0) {
+                    const dim3 grid(static_cast<unsigned>((width + kPackWideJ - 1) / kPackWideJ),
+                                    static_cast<unsigned>((T + kPackWideT - 1) / kPackWideT));
+                    pack_mxt_wide_kernel<<<grid, 256, 0, s>>>(
+                        static_cast<const uint16_t*>(seg[i].dY), seg[i].ldy, T, seg[i].idx,
+                        seg[i].rows, width, p.rp, panel + off);
                 } else {
                     const dim3 grid(static_cast<unsigned>((width + 63) / 64),
                                     static_cast<unsigned>((T + 63) / 64));
