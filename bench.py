@@ -51,6 +51,8 @@ def parse():
                         "selected rows are contiguous and are gathered inside the GEMM")
     p.add_argument("--adam-state", choices=["f32", "bf16"], default="f32",
                    help="dtype of the Adam moments (the headline configuration keeps them in fp32)")
+    p.add_argument("--graph", action="store_true",
+                   help="with --block: capture the regular step into a HIP graph and replay it")
     p.add_argument("--concurrent-groups", action="store_true",
                    help="with --block: every group of layers on a HIP stream of its own")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -154,9 +156,11 @@ def bench_block(args, cfg):
                      concurrent_groups=args.concurrent_groups)
     sched = RewarmSchedule(base_lr=cfg.lr, K=REFRESH_EVERY, rewarm=REFRESH_EVERY)
     blk.refresh(dY, X)  # set-up: refresh-step workspaces are allocated outside the timed region
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1)):
         blk.step(dY, X, W)
     torch.cuda.synchronize()
+    if args.graph:
+        blk.capture(dY, X, W)
     blk.t = 0
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
@@ -176,7 +180,8 @@ def bench_block(args, cfg):
                                f"{inter}x{hidden}, down {hidden}x{inter}; T={T}, r={cfg.r}, "
                                f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection, "
                                f"dY stored {args.layout}"
-                               f"{', groups on concurrent streams' if args.concurrent_groups else ''}"},
+                               f"{', groups on concurrent streams' if args.concurrent_groups else ''}"
+                               f"{', regular steps replayed from a HIP graph' if args.graph else ''}"},
         "compressed_grad_tflops_incl_gather_and_reduce_and_adam": flops * args.steps / (ms * 1e-3) / 1e12,
     }))
 

@@ -276,6 +276,25 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
                                int64_t ldo, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * The fused Adam + update for callers that capture a step into a HIP graph and replay it.
+ * Adam's step count t and the learning rate change every step, and a captured launch keeps
+ * its arguments; here the three values that depend on them are read from device memory:
+ *   step_scalars[0] = lr,  [1] = 1 / (1 - beta1^t),  [2] = 1 / (1 - beta2^t).
+ * grass_adam_step_scalars computes them on the host (`scalars`: host array of 3 floats, the
+ * same double-precision evaluation the other Adam calls use); the caller copies them to the
+ * device array before each replay (from pinned memory with a copy that is part of the graph,
+ * or with a copy ahead of it on the same stream).  Everything else is grass_adam_scatter_state.
+ * Errors: as grass_adam_scatter_state; NULL for a missing array; SHAPE for t < 1. */
+grass_status grass_adam_step_scalars(float lr, float beta1, float beta2, int64_t t,
+                                     float* scalars);
+grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* M, void* V,
+                                           grass_dtype sdt, int64_t r, int64_t n, float beta1,
+                                           float beta2, float eps, const float* step_scalars,
+                                           void* W, grass_dtype wdt, int64_t m, int64_t ldw,
+                                           const int32_t* idx, const float* rho, float alpha,
+                                           void* stream);
+
+/* ---------------------------------------------------------------------------
  * Measurement aid (not a step of the method; for benchmarks that want to state what the
  * matrix cores of the machine at hand sustain).  Launches a kernel that does nothing but
  * issue the bf16 matrix instruction of the compressed-gradient GEMM on every compute unit

@@ -88,6 +88,7 @@ class GrassBlock:
             self.ws[g] = grass.workspace(grass.cgrad_group_workspace(T, ns.pop(), rs, dt, layout),
                                          device)
         self.t = 0
+        self.graph = None
 
     def refresh(self, dY, X):
         """compute_P (+ update_state) for every layer.  dY: {name: tensor}, X: {group: tensor}."""
@@ -95,7 +96,7 @@ class GrassBlock:
             for name in g:
                 self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state)
 
-    def _step_group(self, g, dY, X, W, lr):
+    def _step_group(self, g, dY, X, W, lr, step_scalars=None):
         members = [self.layers[name] for name in g]
         grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
                                     [l.rho for l in members], [l.GC for l in members],
@@ -103,13 +104,13 @@ class GrassBlock:
         for name, l in zip(g, members):
             if lr is not None:
                 l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
-            l.adam_scatter(W[name])
+            l.adam_scatter(W[name], step_scalars)
 
-    def step(self, dY, X, W, lr=None):
+    def step(self, dY, X, W, lr=None, step_scalars=None):
         """One regular step of every layer: grouped G_C, then Adam and the row update."""
         if not self.concurrent_groups:
             for g in self.groups:
-                self._step_group(g, dY, X, W, lr)
+                self._step_group(g, dY, X, W, lr, step_scalars)
             return
         if self.streams is None:
             self.streams = [torch.cuda.Stream() for _ in self.groups]
@@ -119,7 +120,7 @@ class GrassBlock:
         for g, side in zip(self.groups, self.streams):
             side.wait_event(fork)
             with torch.cuda.stream(side):
-                self._step_group(g, dY, X, W, lr)
+                self._step_group(g, dY, X, W, lr, step_scalars)
                 joined = torch.cuda.Event()
                 joined.record(side)
             main.wait_event(joined)
@@ -128,5 +129,52 @@ class GrassBlock:
         """Step t of Algorithm 1 under `schedule`: refresh when t = 0 mod K, then update."""
         if schedule.is_refresh(self.t):
             self.refresh(dY, X)
-        self.step(dY, X, W, schedule.lr(self.t))
+        if self.graph is not None:
+            self.replay(schedule.lr(self.t))
+        else:
+            self.step(dY, X, W, schedule.lr(self.t))
         self.t += 1
+
+    # -- the regular step as a HIP graph ---------------------------------------------------
+    def capture(self, dY, X, W, slots=64):
+        """Capture one regular step over the tensors given (they, the state and the workspaces
+        must stay where they are) into a HIP graph.  Afterwards train_step() replays it; the
+        refresh steps stay eager (they rewrite idx and rho in place, which the graph reads).
+        Run one eager step first so that every lazily created handle exists.
+
+        The learning rate and Adam's bias corrections reach the kernels through a 3-float
+        device array.  Each replay is preceded by a copy into it from a pinned host slot of its
+        own (a ring of `slots`, each guarded by an event), so the host can run ahead of the GPU.
+        """
+        dev = next(iter(W.values())).device
+        self.scalars = torch.zeros(3, dtype=torch.float32, device=dev)
+        self.slots = [torch.zeros(3, dtype=torch.float32).pin_memory() for _ in range(slots)]
+        self.slot_events = [None] * slots
+        self.slot = 0
+        saved = {name: l.adam_t for name, l in self.layers.items()}
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(dY, X, W, None, self.scalars)
+        for name, l in self.layers.items():  # the capture itself runs nothing
+            l.adam_t = saved[name]
+        self.graph = graph
+
+    def replay(self, lr):
+        ts = {l.adam_t for l in self.layers.values()}
+        assert len(ts) == 1, "all layers of a block share Adam's step count"
+        t = ts.pop() + 1
+        k = self.slot
+        if self.slot_events[k] is not None:
+            self.slot_events[k].synchronize()  # the copy that last read this slot has run
+        vals = grass.adam_step_scalars(lr, self.adam.beta1, self.adam.beta2, t)
+        for i in range(3):
+            self.slots[k][i] = vals[i]
+        self.scalars.copy_(self.slots[k], non_blocking=True)
+        ev = torch.cuda.Event()
+        ev.record()
+        self.slot_events[k] = ev
+        self.slot = (k + 1) % len(self.slots)
+        self.graph.replay()
+        for l in self.layers.values():
+            l.adam_t = t

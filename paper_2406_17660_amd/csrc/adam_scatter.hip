@@ -21,7 +21,20 @@ struct AdamParams {
     float b1, one_minus_b1, b2, one_minus_b2;
     float inv_c1, inv_c2;  // reciprocals of the bias corrections 1 - beta^t
     float lr, eps;
+    // When set: device array {lr, inv_c1, inv_c2} that replaces the three values above, so that
+    // a captured launch can be replayed for later steps (the caller rewrites the array).
+    const float* step_scalars;
 };
+
+// The values of this step: from the launch arguments, or from device memory.
+__device__ __forceinline__ AdamParams resolve(AdamParams p) {
+    if (p.step_scalars) {
+        p.lr = p.step_scalars[0];
+        p.inv_c1 = p.step_scalars[1];
+        p.inv_c2 = p.step_scalars[2];
+    }
+    return p;
+}
 
 // What a moment becomes when it is stored: itself in fp32, the nearest bf16 value otherwise.
 template <typename ST>
@@ -105,7 +118,8 @@ __device__ __forceinline__ int64_t thread_col(int64_t n, int& cnt) {
 template <typename ST, int VEC>
 __global__ __launch_bounds__(kThreads) void adam_rows_kernel(
     const float* __restrict__ GC, int64_t ldgc, ST* __restrict__ M, ST* __restrict__ V,
-    float* __restrict__ U, int64_t n, AdamParams p) {
+    float* __restrict__ U, int64_t n, AdamParams p_in) {
+    const AdamParams p = resolve(p_in);
     const int64_t j = blockIdx.y;
     int cnt;
     const int64_t c = thread_col<VEC>(n, cnt);
@@ -175,8 +189,9 @@ __global__ __launch_bounds__(kThreads) void scatter_kernel(
 template <typename WT, typename ST, int VEC, int UNROLL>
 __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
     const float* __restrict__ GC, int64_t ldgc, ST* __restrict__ M, ST* __restrict__ V,
-    int64_t n, int64_t r, AdamParams p, WT* __restrict__ W, int64_t ldw,
+    int64_t n, int64_t r, AdamParams p_in, WT* __restrict__ W, int64_t ldw,
     const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha) {
+    const AdamParams p = resolve(p_in);
     const int64_t j = blockIdx.y;
     const int32_t row = idx[j];
     if (j > 0 && idx[j - 1] == row) return;
@@ -296,8 +311,11 @@ __global__ __launch_bounds__(256) void scatter_cols_kernel(
     }
 }
 
-AdamParams make_params(float lr, float b1, float b2, float eps, int64_t t) {
+AdamParams make_params(float lr, float b1, float b2, float eps, int64_t t,
+                       const float* step_scalars) {
     AdamParams p;
+    p.step_scalars = step_scalars;
+    if (t < 1) t = 1;  // unused when step_scalars is set
     p.b1 = b1;
     p.one_minus_b1 = 1.0f - b1;
     p.b2 = b2;
@@ -348,7 +366,7 @@ grass_status launch_adam_rows(const float* GC, int64_t ldgc, void* M, void* V, g
                               int64_t r, int64_t n, float lr, float b1, float b2, float eps,
                               int64_t t, float* U, hipStream_t s) {
     if (r == 0 || n == 0) return GRASS_OK;
-    const AdamParams p = make_params(lr, b1, b2, eps, t);
+    const AdamParams p = make_params(lr, b1, b2, eps, t, nullptr);
     return sdt == GRASS_F32 ? adam_rows_typed<float>(GC, ldgc, M, V, sdt, r, n, p, U, s)
                             : adam_rows_typed<uint16_t>(GC, ldgc, M, V, sdt, r, n, p, U, s);
 }
@@ -411,9 +429,10 @@ static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, void* Mv, 
 grass_status launch_adam_scatter(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
                                  int64_t r, int64_t n, float lr, float b1, float b2, float eps,
                                  int64_t t, void* W, grass_dtype wdt, int64_t ldw,
-                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s) {
+                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s,
+                                 const float* step_scalars) {
     if (r == 0 || n == 0) return GRASS_OK;
-    const AdamParams p = make_params(lr, b1, b2, eps, t);
+    const AdamParams p = make_params(lr, b1, b2, eps, t, step_scalars);
     if (wdt == GRASS_F32)
         return sdt == GRASS_F32
                    ? adam_scatter_typed<float, float>(GC, ldgc, M, V, sdt, r, n, p, W, wdt, ldw, idx, rho, alpha, s)
@@ -458,6 +477,13 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
     if (r == 0 || n == 0) return GRASS_OK;
     return gdt == GRASS_F32 ? gather_typed<float>(G, gdt, n, ldg, idx, rho, r, out, ldo, s)
                             : gather_typed<uint16_t>(G, gdt, n, ldg, idx, rho, r, out, ldo, s);
+}
+
+void adam_step_scalars(float lr, float b1, float b2, int64_t t, float out[3]) {
+    const AdamParams p = make_params(lr, b1, b2, 0.f, t, nullptr);
+    out[0] = p.lr;
+    out[1] = p.inv_c1;
+    out[2] = p.inv_c2;
 }
 
 }  // namespace grass

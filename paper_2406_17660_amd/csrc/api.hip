@@ -218,6 +218,30 @@ grass_status grass_adam_scatter_state(const float* GC, int64_t ldgc, void* M, vo
                                idx, rho, alpha, as_stream(stream));
 }
 
+grass_status grass_adam_step_scalars(float lr, float beta1, float beta2, int64_t t,
+                                     float* scalars) {
+    if (!scalars) return GRASS_ERR_NULL;
+    if (t < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        return GRASS_ERR_SHAPE;
+    adam_step_scalars(lr, beta1, beta2, t, scalars);
+    return GRASS_OK;
+}
+
+grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* M, void* V,
+                                           grass_dtype sdt, int64_t r, int64_t n, float beta1,
+                                           float beta2, float eps, const float* step_scalars,
+                                           void* W, grass_dtype wdt, int64_t m, int64_t ldw,
+                                           const int32_t* idx, const float* rho, float alpha,
+                                           void* stream) {
+    if (!step_scalars) return GRASS_ERR_NULL;
+    grass_status st = check_adam(GC, ldgc, M, V, sdt, r, n, beta1, beta2, 1);
+    if (st != GRASS_OK) return st;
+    st = check_rows_of_w(W, wdt, m, n, ldw, idx, rho, r);
+    if (st != GRASS_OK) return st;
+    return launch_adam_scatter(GC, ldgc, M, V, sdt, r, n, 0.f, beta1, beta2, eps, 1, W, wdt, ldw,
+                               idx, rho, alpha, as_stream(stream), step_scalars);
+}
+
 size_t grass_dense_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
                              grass_dy_layout layout) {
     if (T < 0 || m < 0 || n < 0) return 0;

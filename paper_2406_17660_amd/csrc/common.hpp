@@ -90,7 +90,11 @@ grass_status launch_scatter_cols(void* W, grass_dtype wdt, int64_t mrows, int64_
 grass_status launch_adam_scatter(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
                                  int64_t r, int64_t n, float lr, float b1, float b2, float eps,
                                  int64_t t, void* W, grass_dtype wdt, int64_t ldw,
-                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s);
+                                 const int32_t* idx, const float* rho, float alpha, hipStream_t s,
+                                 const float* step_scalars = nullptr);
+// {lr, 1/(1-b1^t), 1/(1-b2^t)}: what the Adam kernels read from device memory when a captured
+// step is replayed (step_scalars != nullptr above; lr and t of the call are then ignored).
+void adam_step_scalars(float lr, float b1, float b2, int64_t t, float out[3]);
 grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64_t ldg,
                                 const int32_t* idx, const float* rho, int64_t r, float* out,
                                 int64_t ldo, hipStream_t s);

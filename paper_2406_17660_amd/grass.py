@@ -28,6 +28,7 @@ EXPORTS = [
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
     "grass_adam_rows_state", "grass_adam_scatter_state", "grass_probe_mfma_rate",
+    "grass_adam_step_scalars", "grass_adam_scatter_replayable",
 ]
 
 _lib = None
@@ -70,6 +71,9 @@ def lib():
                                         vp]
     L.grass_adam_scatter_state.argtypes = [vp, i64, vp, vp, i32, i64, i64, f32, f32, f32, f32, i64,
                                            vp, i32, i64, i64, vp, vp, f32, vp]
+    L.grass_adam_step_scalars.argtypes = [f32, f32, f32, i64, C.POINTER(C.c_float)]
+    L.grass_adam_scatter_replayable.argtypes = [vp, i64, vp, vp, i32, i64, i64, f32, f32, f32, vp,
+                                                vp, i32, i64, i64, vp, vp, f32, vp]
     L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
     L.grass_dense_workspace.restype = sz
     L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
@@ -287,6 +291,28 @@ def adam_scatter(GC, M, V, lr, beta1, beta2, eps, t, W, idx, rho, alpha):
     else:
         _check(lib().grass_adam_scatter_state(pG, ldgc, pM, pV, sdt, r, n, lr, beta1, beta2, eps,
                                               t, *tail), "grass_adam_scatter_state")
+    return W
+
+
+def adam_step_scalars(lr, beta1, beta2, t):
+    """(lr, 1/(1-beta1^t), 1/(1-beta2^t)) as the float32 values the Adam kernels use."""
+    out = (C.c_float * 3)()
+    _check(lib().grass_adam_step_scalars(lr, beta1, beta2, t, out), "grass_adam_step_scalars")
+    return [out[0], out[1], out[2]]
+
+
+def adam_scatter_replayable(GC, M, V, beta1, beta2, eps, step_scalars, W, idx, rho, alpha):
+    """grass_adam_scatter with lr and the bias corrections read from the device array
+    `step_scalars` (3 floats), for steps that are captured into a graph and replayed."""
+    pG, r, n, ldgc = _mat(GC)
+    pW, m, nw, ldw = _mat(W)
+    assert nw == n and idx.shape == (r,)
+    pM, pV, sdt = _moments(M, V, r, n)
+    assert step_scalars.is_cuda and step_scalars.dtype == torch.float32 and step_scalars.numel() >= 3
+    _check(lib().grass_adam_scatter_replayable(
+        pG, ldgc, pM, pV, sdt, r, n, beta1, beta2, eps, C.c_void_p(step_scalars.data_ptr()), pW,
+        _dtype(W), m, ldw, _vec(idx, torch.int32), _vec(rho, torch.float32), alpha, _stream()),
+        "grass_adam_scatter_replayable")
     return W
 
 

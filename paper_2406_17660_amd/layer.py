@@ -109,10 +109,17 @@ class GrassLayer:
         return grass.compressed_grad(dY, X, self.idx, self.rho, self.GC, self.ws_gemm, self.layout,
                                      gemm_events)
 
-    def adam_scatter(self, W):
+    def adam_scatter(self, W, step_scalars=None):
+        """Adam on the compressed gradient and the update of W.  With `step_scalars` (device
+        array written by the caller from grass.adam_step_scalars) the launch does not depend on
+        this step's learning rate and count and can be replayed from a captured graph."""
         self.adam_t += 1
         a = self.adam
         assert tuple(W.shape) == self.w_shape
+        if step_scalars is not None:
+            assert self.side == "rows"
+            return grass.adam_scatter_replayable(self.GC, self.M, self.V, a.beta1, a.beta2, a.eps,
+                                                 step_scalars, W, self.idx, self.rho, self.alpha)
         if self.side == "cols":  # Adam on r x m, then the update of r columns of W
             if not hasattr(self, "U"):
                 self.U = torch.empty_like(self.GC)

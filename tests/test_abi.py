@@ -178,6 +178,30 @@ def test_adam_and_scatter_validation():
     assert g(FAKE, 0, 4, 8, 8, FAKE, FAKE, 2, FAKE, 7, None) == grass.ERR_SHAPE
 
 
+def test_replayable_adam_validation_and_step_scalars():
+    import ctypes as C
+    L = grass.lib()
+    out = (C.c_float * 3)()
+    assert L.grass_adam_step_scalars(1e-3, 0.9, 0.999, 1, out) == grass.OK
+    # t = 1: the corrections are 1 / (1 - beta); float32 of the double-precision value
+    import numpy as np
+    assert out[0] == np.float32(1e-3)
+    assert out[1] == np.float32(1.0 / (1.0 - float(np.float32(0.9))))
+    assert out[2] == np.float32(1.0 / (1.0 - float(np.float32(0.999))))
+    assert L.grass_adam_step_scalars(1e-3, 0.9, 0.999, 0, out) == grass.ERR_SHAPE
+    assert L.grass_adam_step_scalars(1e-3, 1.0, 0.999, 1, out) == grass.ERR_SHAPE
+    assert L.grass_adam_step_scalars(1e-3, 0.9, 0.999, 1, None) == grass.ERR_NULL
+    f = L.grass_adam_scatter_replayable
+    args = [FAKE, 8, FAKE, FAKE, grass.F32, 2, 8, 0.9, 0.999, 1e-8, FAKE, FAKE, 0, 4, 8, FAKE, FAKE,
+            1.0, None]
+    bad = list(args); bad[10] = None
+    assert f(*bad) == grass.ERR_NULL
+    bad = list(args); bad[4] = 7
+    assert f(*bad) == grass.ERR_DTYPE
+    bad = list(args); bad[14] = 7
+    assert f(*bad) == grass.ERR_SHAPE
+
+
 def test_probe_validation():
     import ctypes as C
     f = grass.lib().grass_probe_mfma_rate

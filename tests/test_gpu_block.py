@@ -75,3 +75,49 @@ def test_block_training_steps_match_layerwise_oracle(method, replacement, reset,
         rest = np.setdiff1d(np.arange(m), sel)
         assert np.array_equal(to_np(W[name])[rest], W0[name][rest])
         assert not np.array_equal(to_np(W[name])[sel], W0[name][sel])
+
+
+@pytest.mark.parametrize("concurrent", [False, True])
+def test_block_steps_replayed_from_a_graph_equal_eager_steps(concurrent):
+    """The regular step captured once and replayed (learning rate and bias corrections fed
+    through device memory), refresh steps eager in between: same bits as the all-eager run."""
+    hidden, inter, T, r, K, steps = 128, 344, 640, 24, 3, 8
+    shapes = {"q": (hidden, hidden), "k": (hidden, hidden), "v": (hidden, hidden),
+              "o": (hidden, hidden), "gate": (inter, hidden), "up": (inter, hidden),
+              "down": (hidden, inter)}
+    groups = [("q", "k", "v"), ("gate", "up")]
+    sched = RewarmSchedule(base_lr=2e-3, warmup=4, total=20, min_ratio=0.1, K=K, rewarm=3)
+
+    def make():
+        blk = GrassBlock(shapes, groups, r, T, torch.bfloat16, "multi_norm", True, alpha=0.25,
+                         adam=AdamHyper(lr=1e-3), seed=9, concurrent_groups=concurrent)
+        W = {name: draw(s, 600 + i, 0.05) for i, (name, s) in enumerate(shapes.items())}
+        # inputs live in fixed buffers that are refilled every step (a graph replays addresses)
+        X = {g: torch.empty((T, shapes[g[0]][1]), dtype=torch.bfloat16, device=DEV) for g in blk.groups}
+        dY = {name: torch.empty((T, s[0]), dtype=torch.bfloat16, device=DEV) for name, s in shapes.items()}
+        return blk, W, X, dY
+
+    def fill(blk, X, dY, t):
+        for gi, g in enumerate(blk.groups):
+            X[g].copy_(draw(tuple(X[g].shape), 3000 + 10 * t + gi))
+        for i, name in enumerate(shapes):
+            dY[name].copy_(draw(tuple(dY[name].shape), 4000 + 10 * t + i, 0.1))
+
+    eager, We, Xe, dYe = make()
+    for t in range(steps):
+        fill(eager, Xe, dYe, t)
+        eager.train_step(dYe, Xe, We, sched)
+
+    replayed, Wg, Xg, dYg = make()
+    for t in range(steps):
+        fill(replayed, Xg, dYg, t)
+        replayed.train_step(dYg, Xg, Wg, sched)
+        if t == 0:
+            replayed.capture(dYg, Xg, Wg, slots=2)  # two slots: the ring wraps several times
+    assert replayed.graph is not None
+    torch.cuda.synchronize()
+    for name in shapes:
+        a, b = eager.layers[name], replayed.layers[name]
+        assert a.adam_t == b.adam_t
+        assert torch.equal(a.idx, b.idx) and torch.equal(a.M, b.M) and torch.equal(a.V, b.V), name
+        assert torch.equal(We[name], Wg[name]), name
