@@ -408,9 +408,9 @@ static grass_status adam_scatter_typed(const float* GC, int64_t ldgc, void* Mv, 
     const bool vec = f32_rows_vectorisable(GC, ldgc) && w_rows_vectorisable(M, sdt, n) &&
                      w_rows_vectorisable(V, sdt, n) && w_rows_vectorisable(W, wdt, ldw);
     if (r > kMaxGridY) return GRASS_ERR_SHAPE;
-    // wide rows: four vectors per thread (more bytes in flight per wavefront); narrow rows keep
-    // one so that a row still spreads over several workgroups
-    const int unroll = n >= 4096 ? 4 : (n >= 2048 ? 2 : 1);
+    // One vector per thread.  Two or four per thread are a few percent faster when the state is
+    // warm in the last-level cache and slower inside a real step, where it comes from HBM.
+    const int unroll = 1;
     if (vec && unroll == 4)
         adam_scatter_kernel<WT, ST, 4, 4><<<grid_for(n, r, 16), kThreads, 0, s>>>(
             GC, ldgc, M, V, n, r, p, static_cast<WT*>(W), ldw, idx, rho, alpha);
