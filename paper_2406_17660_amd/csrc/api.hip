@@ -19,11 +19,12 @@ hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 grass_status check_products(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t m, int64_t n) {
     if (T < 0 || m < 0 || n < 0 || ldx < n) return GRASS_ERR_SHAPE;
+    // sizes first: the products below then fit 64 bits
+    if (m >= (int64_t{1} << 31) || n >= (int64_t{1} << 31) || T >= (int64_t{1} << 31))
+        return GRASS_ERR_SHAPE;
     if (!present(dY, T * m) || !present(X, T * n)) return GRASS_ERR_NULL;
     if (!dtype_ok(dt) || !layout_ok(layout)) return GRASS_ERR_DTYPE;
     if (ldy < (layout == GRASS_DY_TxM ? m : T)) return GRASS_ERR_SHAPE;
-    if (m >= (int64_t{1} << 31) || n >= (int64_t{1} << 31) || T >= (int64_t{1} << 40))
-        return GRASS_ERR_SHAPE;
     return GRASS_OK;
 }
 
