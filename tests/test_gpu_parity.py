@@ -683,3 +683,107 @@ def test_compressed_grad_group_too_large_for_a_joint_panel_runs_set_by_set():
         assert rel_fro(got, want) <= 2e-5
         single = gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV))
         assert torch.equal(single, GC)  # the very same launches as the single call
+
+
+# ------------------------------------------------------------------------------ seeded sweep of shapes
+def _sweep_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        T = int(rng.choice([1, 7, 31, 32, 33, 64, 95, 128, 200, 257, 512, 700]))
+        m = int(rng.integers(1, 600))
+        n = int(rng.integers(1, 600))
+        r = int(rng.integers(0, min(m, 300) + 1))
+        pad_y, pad_x = int(rng.choice([0, 0, 3, 8])), int(rng.choice([0, 0, 5, 8]))
+        layout = int(rng.integers(0, 2))
+        tile = [None, "128", "256"][int(rng.integers(0, 3))]
+        cases.append((k, T, m, n, r, pad_y, pad_x, layout, tile))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,m,n,r,pad_y,pad_x,layout,tile", _sweep_cases(48, 2406))
+def test_compressed_grad_and_dense_grad_shape_sweep(monkeypatch, k, T, m, n, r, pad_y, pad_x, layout, tile):
+    """Seeded random shapes, paddings, layouts and forced tiles: every combination of packing,
+    aligning copy, K tail and tile kind the launcher can take."""
+    if tile:
+        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    X = randn((T, n), torch.bfloat16, 9000 + k, ld=n + pad_x)
+    if layout == grass.DY_TxM:
+        dY_dev = randn((T, m), torch.bfloat16, 9100 + k, scale=0.1, ld=m + pad_y)
+        dY_host = to_np(dY_dev)
+    else:
+        dY_dev = randn((m, T), torch.bfloat16, 9100 + k, scale=0.1, ld=T + pad_y)
+        dY_host = np.ascontiguousarray(to_np(dY_dev).T)
+    idx, rho = make_idx(m, r, 9200 + k, duplicates=bool(k % 2))
+    got = to_f64(gpu_cgrad(dY_dev, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), layout))
+    want = ref.compressed_grad(dY_host, to_np(X), idx, rho)
+    assert got.shape == want.shape and np.isfinite(got).all()
+    if want.size:
+        assert np.abs(got - want).max() <= 1e-4 * max(np.abs(want).max(), 1e-30) + 1e-30
+    G = to_f64(gpu_dense(dY_dev, X, torch.float32, layout))
+    wantG = ref.full_grad(dY_host, to_np(X))
+    assert np.abs(G - wantG).max() <= 1e-4 * max(np.abs(wantG).max(), 1e-30) + 1e-30
+
+
+def _update_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(count):
+        m = int(rng.integers(1, 400))
+        n = int(rng.choice([1, 3, 4, 8, 63, 64, 100, 256, 333, 1024, 1031, 2052]))
+        r = int(rng.integers(0, min(m, 150) + 1))
+        out.append((k, m, n, r, int(rng.choice([0, 0, 1, 4])), bool(rng.integers(0, 2)),
+                    [torch.float32, torch.bfloat16][int(rng.integers(0, 2))],
+                    [torch.float32, torch.bfloat16][int(rng.integers(0, 2))]))
+    return out
+
+
+@pytest.mark.parametrize("k,m,n,r,pad,dup,wdtype,sdtype", _update_cases(32, 1766))
+def test_adam_scatter_and_column_update_shape_sweep(k, m, n, r, pad, dup, wdtype, sdtype):
+    """Seeded random shapes for the fused Adam + row update (both state dtypes) and for the
+    column update: vector and element paths, padded leading dimensions, duplicate rows."""
+    idx, rho = make_idx(m, r, 7000 + k, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    W = randn((m, n), wdtype, 7100 + k, scale=0.02, ld=n + pad)
+    W0, W0_bits = to_f64(W).copy(), to_np(W).copy()
+    GC, M, V = adam_inputs(r, n, 7200 + k, n + pad) if r else (torch.zeros((0, n), device=DEV),) * 3
+    M, V = M.to(sdtype).contiguous(), V.to(sdtype).contiguous()
+    Mo, Vo = to_f64(M).copy(), to_f64(V).copy()
+    grass.adam_scatter(GC, M, V, LR, B1, B2, EPS, 2, W, d_idx, d_rho, 0.25)
+    f = np.float32
+    U = ref.adam_rows(to_f64(GC), Mo, Vo, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 2,
+                      state_bf16=sdtype == torch.bfloat16)
+    Wo = W0.copy()
+    ref.scatter_update(Wo, idx, rho, 0.25, U)
+    sel = np.unique(idx)
+    if len(sel):
+        assert rel_fro(to_f64(W)[sel], Wo[sel]) <= tol_for(wdtype)
+        assert rel_fro(to_f64(M), Mo) <= (1e-2 if sdtype == torch.bfloat16 else TOL_F32)
+        assert rel_fro(to_f64(V), Vo) <= (1e-2 if sdtype == torch.bfloat16 else TOL_F32)
+    rest = np.setdiff1d(np.arange(m), sel)
+    assert np.array_equal(to_np(W)[rest], W0_bits[rest])
+    # column form on the transposed weight: W2 is n x m, columns idx of it are updated
+    if n <= 1100:
+        W2 = randn((n, m), wdtype, 7300 + k, scale=0.02, ld=m + pad)
+        W2o, W2_bits = to_f64(W2).copy(), to_np(W2).copy()
+        U32 = torch.from_numpy(U.astype(np.float32)).to(DEV).contiguous()
+        grass.scatter_update_cols(W2, d_idx, d_rho, 0.25, U32)
+        ref.scatter_update_cols(W2o, idx, rho, 0.25, U.astype(np.float32).astype(np.float64))
+        got = to_f64(W2)
+        if len(sel):
+            assert rel_fro(got[:, sel], W2o[:, sel]) <= tol_for(wdtype)
+        assert np.array_equal(to_np(W2)[:, rest], W2_bits[:, rest])
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_select_rows_random_sizes_bit_exact(case):
+    rng = np.random.default_rng(4100 + case)
+    m = int(rng.choice([1, 2, 63, 64, 65, 100, 1000, 4095, 4096, 4097, 20000, 70001]))
+    method, repl = METHODS[case % len(METHODS)]
+    with_repl = repl and method != grass.SEL_TOPR
+    r = int(rng.integers(0, 2000)) if with_repl else int(rng.integers(0, min(m, 2000) + 1))
+    ss = sumsq_case(m, ["chi2", "lognormal", "ties", "wide"][case % 4], 4200 + case)
+    idx, rho, status = gpu_select(torch.from_numpy(ss).to(DEV), r, method, repl, seed=case, refresh_id=case * 7)
+    w_idx, w_rho, _ = ref.select_rows(ss, r, method, repl, seed=case, refresh_id=case * 7)
+    assert status == grass.OK
+    assert np.array_equal(idx.cpu().numpy(), w_idx) and np.array_equal(rho.cpu().numpy(), w_rho)
