@@ -1,0 +1,152 @@
+// Gather / transpose / align passes that prepare the GEMM operands (all HBM-bound).
+// Included by cgrad.hip only (device code shares one translation unit with its launchers).
+#pragma once
+#include "common.hpp"
+#include "gemm_common.hpp"
+
+namespace grass {
+namespace {
+
+// ------------------------------------------------------------------------------ pack
+// out[t, j] = dY[t, idx[j]] (j < r; idx == nullptr: column j itself), 0 for r <= j < rp; rows
+// of `out` are ldo apart (several matrices may fill adjacent column ranges of one panel).
+// Thread = 4 adjacent j; 2^tpr_log2 threads cover the columns of one row of t (a narrow panel,
+// r = 128 say, puts several rows of t side by side in a workgroup instead of idling most of
+// it), and every thread loops over rows_per_thread (4 .. kPackRows) values of t: fewer when
+// the matrix is small, so that the launch still has a few thousand workgroups to hide the
+// latency of the gather.  Wave stores are contiguous.
+constexpr int kPackRows = 16;
+__global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restrict__ dY, int64_t ldy,
+                                                       int64_t T, const int32_t* __restrict__ idx,
+                                                       int64_t r, int64_t rp, int64_t ldo,
+                                                       int tpr_log2, int rows_per_thread,
+                                                       uint16_t* __restrict__ out) {
+    const int tpr = 1 << tpr_log2, rows_per_pass = 256 >> tpr_log2;
+    const int64_t j0 = (static_cast<int64_t>(blockIdx.x) * tpr + (threadIdx.x & (tpr - 1))) * 4;
+    if (j0 >= rp) return;
+    int64_t col[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) col[e] = j0 + e < r ? (idx ? idx[j0 + e] : j0 + e) : -1;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_thread * rows_per_pass +
+                       (threadIdx.x >> tpr_log2);
+#pragma unroll 4
+    for (int tt = 0; tt < rows_per_thread; ++tt) {
+        const int64_t t = t0 + static_cast<int64_t>(tt) * rows_per_pass;
+        if (t >= T) break;
+        const uint16_t* row = dY + t * ldy;
+        uint16_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? row[col[e]] : static_cast<uint16_t>(0);
+        uint2 w;
+        w.x = v[0] | (static_cast<uint32_t>(v[1]) << 16);
+        w.y = v[2] | (static_cast<uint32_t>(v[3]) << 16);
+        *reinterpret_cast<uint2*>(out + t * ldo + j0) = w;
+    }
+}
+
+// out[t, j] = dYt[idx[j] (or j), t]: gather of rows of the m x T matrix, transposed through
+// a 64 x 64 LDS tile so that both the reads (along t) and the writes (along j) coalesce.
+__global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restrict__ dYt, int64_t ldy,
+                                                       int64_t T, const int32_t* __restrict__ idx,
+                                                       int64_t r, int64_t rp, int64_t ldo,
+                                                       uint16_t* __restrict__ out) {
+    __shared__ uint16_t tile[64][66];
+    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * 64;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int jj = w; jj < 64; jj += 4) {
+        const int64_t j = j0 + jj, t = t0 + lane;
+        uint16_t v = 0;
+        if (j < r && t < T) v = dYt[static_cast<int64_t>(idx ? idx[j] : j) * ldy + t];
+        tile[jj][lane] = v;
+    }
+    __syncthreads();
+    for (int tt = w; tt < 64; tt += 4) {
+        const int64_t t = t0 + tt, j = j0 + lane;
+        if (t < T && j < rp) out[t * ldo + j] = tile[lane][tt];
+    }
+}
+
+// The same gather-and-transpose with 16-byte accesses on both sides, for rows that allow them
+// (dYt 16-byte aligned, ldy and ldo multiples of 8).  A workgroup turns 64 (j) x 256 (t): each
+// lane loads 8 consecutive t of one selected row (a wavefront reads 2 x 512 contiguous bytes),
+// the block goes to LDS as [j][t], and the transposing 8-byte LDS read hands every lane four
+// consecutive j of one t, so a lane stores 8 values of j (16 bytes) of its own panel row per
+// step.  LDS rows are padded by 16 elements: the four rows one 16-lane read touches then fall
+// into different banks.
+constexpr int kPackWideJ = 64, kPackWideT = 256, kPackWideLd = kPackWideT + 16;
+__global__ __launch_bounds__(256) void pack_mxt_wide_kernel(const uint16_t* __restrict__ dYt,
+                                                            int64_t ldy, int64_t T,
+                                                            const int32_t* __restrict__ idx,
+                                                            int64_t r, int64_t rp, int64_t ldo,
+                                                            uint16_t* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kPackWideJ * kPackWideLd];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * kPackWideJ;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kPackWideT;
+    const int chunk = threadIdx.x & 31;  // 8 values of t each
+#pragma unroll
+    for (int pass = 0; pass < kPackWideJ / 8; ++pass) {
+        const int jj = pass * 8 + (threadIdx.x >> 5);
+        const int64_t j = j0 + jj, t = t0 + chunk * 8;
+        s16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (j < r && t < T) {
+            const uint16_t* src = dYt + static_cast<int64_t>(idx ? idx[j] : j) * ldy + t;
+            if (t + 8 <= T) {
+                v = *reinterpret_cast<const s16x8*>(src);
+            } else {
+                for (int e = 0; e < 8; ++e)
+                    if (t + e < T) v[e] = static_cast<short>(src[e]);
+            }
+        }
+        *reinterpret_cast<s16x8*>(tile + jj * kPackWideLd + chunk * 8) = v;
+    }
+    __syncthreads();
+    // wavefront w owns t = 64w .. 64w+63 of the block; lane L ends up with t = 64w + L
+    const int grp = lane >> 4, i = lane & 15;
+    const uint16_t* src = tile + (i >> 2) * kPackWideLd + w * 64 + grp * 16 + 4 * (i & 3);
+    const int64_t t = t0 + w * 64 + lane;
+    uint16_t* dst = out + (t < T ? t : 0) * ldo + j0;
+#pragma unroll
+    for (int j8 = 0; j8 < kPackWideJ; j8 += 8) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + j8 * kPackWideLd));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(src + (j8 + 4) * kPackWideLd));
+        if (t < T && j0 + j8 < rp)  // rp is a multiple of 8: whole vectors only
+            *reinterpret_cast<s16x8*>(dst + j8) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+}
+
+// out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np even, rows of `out` np apart): a copy
+// of a matrix whose rows start at odd element offsets (n not a multiple of 8, as in the
+// 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM can take.  `in` itself
+// is 4-byte aligned.  A thread moves one 32-bit pair at a time; a row that starts in the upper
+// half of an aligned word is read as two words and shifted.
+__global__ __launch_bounds__(256) void align_rows_kernel(const uint16_t* __restrict__ in, int64_t ld,
+                                                         int64_t n, int64_t np, int chunks,
+                                                         uint16_t* __restrict__ out) {
+    const int64_t t = blockIdx.x / chunks;
+    const int chunk = blockIdx.x % chunks;
+    const uint16_t* row = in + t * ld;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(row);
+    const bool upper = (a & 2) != 0;
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(a - (upper ? 2 : 0));
+    uint32_t* o = reinterpret_cast<uint32_t*>(out + t * np);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t d = static_cast<int64_t>(chunk) * 1024 + i * 256 + threadIdx.x;
+        const int64_t c = 2 * d;
+        if (c >= np) break;
+        uint32_t v;
+        if (upper ? c + 2 < n : c + 1 < n) {  // every word touched lies inside the row
+            v = upper ? (w[d] >> 16) | (w[d + 1] << 16) : w[d];
+        } else {
+            const uint32_t lo = c < n ? row[c] : 0u, hi = c + 1 < n ? row[c + 1] : 0u;
+            v = lo | (hi << 16);
+        }
+        o[d] = v;
+    }
+}
+
+
+}  // namespace
+}  // namespace grass
