@@ -278,6 +278,46 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
                                int64_t ldo, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * The regular step of Algorithm 1 in one call ("G_C <- P^T grad; Delta <- opt.update(G_C);
+ * W <- W + alpha P Delta"), for `count` weight matrices that read the same activations X
+ * (count = 1: one layer).  Per layer it computes exactly what grass_compressed_grad followed
+ * by grass_adam_scatter_state computes; the split-K reduction of the matrix product, Adam and
+ * the row update run as one kernel that reads the product's partial tiles directly, so G_C
+ * is not written unless the layer asks for it (GC != NULL), and one launch and one pass over
+ * r x n are saved per layer.
+ *
+ * `layers`: HOST array of `count` descriptors (1 <= count <= GRASS_MAX_GROUP); the pointers
+ * inside are device pointers.  T, n, dt, layout, X, the moment dtype `sdt`, the weight dtype
+ * `wdt`, the Adam scalars and alpha are shared.  `step_scalars`: NULL, or the device array of
+ * grass_adam_step_scalars (lr and t are then ignored; for captured steps).
+ * `ws` must hold grass_step_group_workspace(...) bytes.  ev_gemm_start / ev_gemm_stop: NULL, or
+ * hipEvent_t handles recorded around the matrix-multiply kernel(s) as in
+ * grass_compressed_grad_timed.
+ * Errors: the union of those of the two calls it replaces. */
+typedef struct {
+    const void* dY;      /* T x m (or m x T), dtype dt                                   */
+    int64_t ldy;
+    int64_t m;           /* rows of W = features of dY                                   */
+    int64_t r;           /* selected rows                                                */
+    const int32_t* idx;  /* r ascending row indices                                      */
+    const float* rho;    /* r scales                                                     */
+    float* GC;           /* optional output, r x n fp32 (NULL: G_C is not stored)        */
+    int64_t ldgc;        /* its leading dimension (ignored when GC is NULL)              */
+    void* M;             /* r x n moments of dtype sdt, dense, updated in place          */
+    void* V;
+    void* W;             /* m x n weights of dtype wdt, updated in place                 */
+    int64_t ldw;
+} grass_step_layer;
+size_t grass_step_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
+                                  grass_dtype dt, grass_dy_layout layout);
+grass_status grass_step_group(int count, const grass_step_layer* layers, grass_dy_layout layout,
+                              const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t n,
+                              grass_dtype sdt, grass_dtype wdt, float lr, float beta1, float beta2,
+                              float eps, int64_t t, const float* step_scalars, float alpha,
+                              void* ws, size_t ws_bytes, void* stream, void* ev_gemm_start,
+                              void* ev_gemm_stop);
+
+/* ---------------------------------------------------------------------------
  * The fused Adam + update for callers that capture a step into a HIP graph and replay it.
  * Adam's step count t and the learning rate change every step, and a captured launch keeps
  * its arguments; here the three values that depend on them are read from device memory:

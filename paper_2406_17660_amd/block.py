@@ -62,13 +62,14 @@ class GrassBlock:
 
     def __init__(self, shapes, groups, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, device="cuda",
-                 reset_state=True, layout=grass.DY_TxM, concurrent_groups=False):
+                 reset_state=True, layout=grass.DY_TxM, concurrent_groups=False, store_GC=True):
         # concurrent_groups: issue every group on a HIP stream of its own (default priority),
         # forked from and joined back into the caller's stream.  The groups are independent
         # (own inputs, state and workspaces); small layers, whose kernels do not fill the
         # machine, then overlap instead of queueing behind each other's launch gaps and tails.
         self.streams = None
         self.concurrent_groups = concurrent_groups
+        self.store_GC = store_GC  # False: the compressed gradients are never written out
         self.adam = adam or AdamHyper()
         self.reset_state = reset_state
         self.layout = layout  # storage of every dY handed to refresh() / step()
@@ -85,7 +86,7 @@ class GrassBlock:
             ns = {self.layers[name].n for name in g}
             assert len(ns) == 1, "layers of a group read the same activations"
             rs = [self.layers[name].r for name in g]
-            self.ws[g] = grass.workspace(grass.cgrad_group_workspace(T, ns.pop(), rs, dt, layout),
+            self.ws[g] = grass.workspace(grass.step_group_workspace(T, ns.pop(), rs, dt, layout),
                                          device)
         self.t = 0
         self.graph = None
@@ -97,14 +98,20 @@ class GrassBlock:
                 self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state)
 
     def _step_group(self, g, dY, X, W, lr, step_scalars=None):
+        """One library call for the group: grouped G_C, Adam and the row updates."""
         members = [self.layers[name] for name in g]
-        grass.compressed_grad_group([dY[name] for name in g], X[g], [l.idx for l in members],
-                                    [l.rho for l in members], [l.GC for l in members],
-                                    self.ws[g], self.layout)
-        for name, l in zip(g, members):
+        for l in members:
             if lr is not None:
                 l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
-            l.adam_scatter(W[name], step_scalars)
+            l.adam_t += 1
+        a, t = members[0].adam, members[0].adam_t
+        assert all(l.adam_t == t for l in members)
+        grass.step_group([dY[name] for name in g], X[g], [l.idx for l in members],
+                         [l.rho for l in members], [l.M for l in members], [l.V for l in members],
+                         [W[name] for name in g], a.lr, a.beta1, a.beta2, a.eps, t, members[0].alpha,
+                         self.ws[g], self.layout,
+                         GCs=[l.GC for l in members] if self.store_GC else None,
+                         step_scalars=step_scalars)
 
     def step(self, dY, X, W, lr=None, step_scalars=None):
         """One regular step of every layer: grouped G_C, then Adam and the row update."""

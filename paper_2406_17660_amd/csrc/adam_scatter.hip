@@ -251,6 +251,74 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
         }
 }
 
+// The tail of a regular step in one kernel: split-K reduction of the GEMM's partial tiles, Adam
+// and the row update.  A workgroup owns one compressed row j and 256 columns, four per lane.
+// Its four wavefronts each add a contiguous quarter of the slices (the same column vector);
+// the quarters meet in LDS and the first wavefront scales the sum by rho (that is G_C, written
+// out only if the caller wants it), runs Adam on it and accumulates the update.  Runs of equal
+// idx are walked by their first member, as in adam_scatter_kernel.  Fixed order: deterministic.
+template <typename WT, typename ST>
+__global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
+    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
+    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
+    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
+    float* __restrict__ GC, int64_t ldgc) {
+    __shared__ float4 quarter[4][64];
+    const AdamParams p = resolve(p_in);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t j = blockIdx.y;
+    const int32_t row = idx[j];
+    if (j > 0 && idx[j - 1] == row) return;  // whole workgroup: no barrier is skipped by part of it
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + lane * 4;
+    const bool live = c < n;  // n % 4 == 0: a live lane owns four whole columns
+    const int per = (slices + 3) / 4;
+    const int k0 = w * per, k1 = k0 + per < slices ? k0 + per : slices;
+    const int64_t slice_stride = Mp * Np;
+    WVec<WT, 4> wv;
+    if (w == 0 && live) wv.load(W + static_cast<int64_t>(row) * ldw + c);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live) {
+            const float* src = part + (static_cast<int64_t>(k0) * Mp + jj) * Np + c;
+#pragma unroll 4
+            for (int k = k0; k < k1; ++k, src += slice_stride) {
+                const float4 v = *reinterpret_cast<const float4*>(src);
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+        }
+        quarter[w][lane] = s;
+        __syncthreads();
+        if (w == 0 && live) {
+            const float sc = rho[jj];
+            F32Vec<4> g;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g.x[e] = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = quarter[q][lane];
+                g.x[0] += v.x; g.x[1] += v.y; g.x[2] += v.z; g.x[3] += v.w;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g.x[e] *= sc;
+            if (GC) g.store(GC + jj * ldgc + c);
+            WVec<ST, 4> mv, vv;
+            mv.load(M + jj * n + c);
+            vv.load(V + jj * n + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+            mv.store(M + jj * n + c);
+            vv.store(V + jj * n + c);
+        }
+        __syncthreads();  // the quarters are rewritten for the next member of the run
+    }
+    if (w == 0 && live) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
+        wv.store(W + static_cast<int64_t>(row) * ldw + c);
+    }
+}
+
 template <typename GT, int VEC>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     const GT* __restrict__ G, int64_t ldg, const int32_t* __restrict__ idx,
@@ -477,6 +545,89 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
     if (r == 0 || n == 0) return GRASS_OK;
     return gdt == GRASS_F32 ? gather_typed<float>(G, gdt, n, ldg, idx, rho, r, out, ldo, s)
                             : gather_typed<uint16_t>(G, gdt, n, ldg, idx, rho, r, out, ldo, s);
+}
+
+bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc) {
+    return n % 4 == 0 && w_rows_vectorisable(t.M, t.sdt, n) && w_rows_vectorisable(t.V, t.sdt, n) &&
+           w_rows_vectorisable(t.W, t.wdt, t.ldw) && (!GC || f32_rows_vectorisable(GC, ldgc));
+}
+
+// The same for a handful of slices: every thread adds all slices of its own four columns (the
+// loads are independent, nothing goes through LDS) and all four wavefronts run Adam, so the
+// kernel keeps as many bytes in flight as adam_scatter_kernel does.
+template <typename WT, typename ST>
+__global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
+    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
+    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
+    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
+    float* __restrict__ GC, int64_t ldgc) {
+    const AdamParams p = resolve(p_in);
+    const int64_t j = blockIdx.y;
+    const int32_t row = idx[j];
+    if (j > 0 && idx[j - 1] == row) return;
+    const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (c >= n) return;  // n % 4 == 0: four whole columns or none
+    const int64_t slice_stride = Mp * Np;
+    WVec<WT, 4> wv;
+    wv.load(W + static_cast<int64_t>(row) * ldw + c);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+        WVec<ST, 4> mv, vv;
+        mv.load(M + jj * n + c);
+        vv.load(V + jj * n + c);
+        const float* src = part + jj * Np + c;
+        F32Vec<4> g;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g.x[e] = 0.f;
+#pragma unroll 8
+        for (int k = 0; k < slices; ++k, src += slice_stride) {
+            const float4 v = *reinterpret_cast<const float4*>(src);
+            g.x[0] += v.x; g.x[1] += v.y; g.x[2] += v.z; g.x[3] += v.w;
+        }
+        const float sc = rho[jj];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g.x[e] *= sc;
+        if (GC) g.store(GC + jj * ldgc + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+        mv.store(M + jj * n + c);
+        vv.store(V + jj * n + c);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
+    wv.store(W + static_cast<int64_t>(row) * ldw + c);
+}
+
+template <typename WT, typename ST>
+static void reduce_adam_scatter_typed(const float* part, int slices, int64_t Mp, int64_t Np,
+                                      int64_t r, int64_t n, const AdamParams& p, const StepTail& t,
+                                      const int32_t* idx, const float* rho, float* GC,
+                                      int64_t ldgc, hipStream_t s) {
+    if (slices <= 8) {
+        reduce_adam_scatter_few_kernel<WT, ST><<<grid_for(n, r, 4), kThreads, 0, s>>>(
+            part, slices, Mp, Np, n, r, p, static_cast<ST*>(t.M), static_cast<ST*>(t.V),
+            static_cast<WT*>(t.W), t.ldw, idx, rho, t.alpha, GC, ldgc);
+        return;
+    }
+    const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(r));
+    reduce_adam_scatter_kernel<WT, ST><<<grid, kThreads, 0, s>>>(
+        part, slices, Mp, Np, n, r, p, static_cast<ST*>(t.M), static_cast<ST*>(t.V),
+        static_cast<WT*>(t.W), t.ldw, idx, rho, t.alpha, GC, ldgc);
+}
+
+grass_status launch_reduce_adam_scatter(const float* part, int slices, int64_t Mp, int64_t Np,
+                                        int64_t r, int64_t n, const StepTail& t,
+                                        const int32_t* idx, const float* rho, float* GC,
+                                        int64_t ldgc, hipStream_t s) {
+    if (r == 0 || n == 0) return GRASS_OK;
+    if (r > kMaxGridY) return GRASS_ERR_SHAPE;
+    const AdamParams p = make_params(t.lr, t.beta1, t.beta2, t.eps, t.t, t.step_scalars);
+    const bool wf = t.wdt == GRASS_F32, sf = t.sdt == GRASS_F32;
+    if (wf && sf) reduce_adam_scatter_typed<float, float>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
+    else if (wf) reduce_adam_scatter_typed<float, uint16_t>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
+    else if (sf) reduce_adam_scatter_typed<uint16_t, float>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
+    else reduce_adam_scatter_typed<uint16_t, uint16_t>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
+    return launch_status();
 }
 
 void adam_step_scalars(float lr, float b1, float b2, int64_t t, float out[3]) {

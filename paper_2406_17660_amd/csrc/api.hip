@@ -219,6 +219,64 @@ grass_status grass_adam_scatter_state(const float* GC, int64_t ldgc, void* M, vo
                                idx, rho, alpha, as_stream(stream));
 }
 
+static size_t scratch_gc_bytes(int64_t r, int64_t n) {
+    return (static_cast<size_t>(r) * n * 4 + 255) / 256 * 256;
+}
+
+size_t grass_step_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
+                                  grass_dtype dt, grass_dy_layout layout) {
+    if (T < 0 || n < 0 || count < 1 || count > GRASS_MAX_GROUP || !r) return 0;
+    size_t extra = 256;  // a G_C for every layer that does not name one (the two-kernel route)
+    for (int i = 0; i < count; ++i) {
+        if (r[i] < 0 || r[i] > kMaxGridRows) return 0;
+        extra += scratch_gc_bytes(r[i], n);
+    }
+    return gemm_group_workspace_bytes(T, r, count, n, dt, layout) + extra;
+}
+
+grass_status grass_step_group(int count, const grass_step_layer* layers, grass_dy_layout layout,
+                              const void* X, int64_t ldx, grass_dtype dt, int64_t T, int64_t n,
+                              grass_dtype sdt, grass_dtype wdt, float lr, float beta1, float beta2,
+                              float eps, int64_t t, const float* step_scalars, float alpha,
+                              void* ws, size_t ws_bytes, void* stream, void* ev_gemm_start,
+                              void* ev_gemm_stop) {
+    if (count < 1 || count > GRASS_MAX_GROUP) return GRASS_ERR_SHAPE;
+    if (!layers) return GRASS_ERR_NULL;
+    GemmSegment seg[GRASS_MAX_GROUP];
+    StepTail tail[GRASS_MAX_GROUP];
+    int64_t rows[GRASS_MAX_GROUP];
+    for (int i = 0; i < count; ++i) {
+        const grass_step_layer& L = layers[i];
+        grass_status st = check_products(L.dY, layout, L.ldy, X, ldx, dt, T, L.m, n);
+        if (st != GRASS_OK) return st;
+        if (L.r < 0 || L.r > kMaxGridRows || (L.GC && L.ldgc < n)) return GRASS_ERR_SHAPE;
+        // any non-null stand-in passes the presence test of G_C when the layer does not name one
+        st = check_adam(L.GC ? L.GC : reinterpret_cast<const float*>(L.M), L.GC ? L.ldgc : n, L.M,
+                        L.V, sdt, L.r, n, beta1, beta2, step_scalars ? 1 : t);
+        if (st != GRASS_OK) return st;
+        st = check_rows_of_w(L.W, wdt, L.m, n, L.ldw, L.idx, L.rho, L.r);
+        if (st != GRASS_OK) return st;
+        rows[i] = L.r;
+    }
+    const size_t gemm_bytes = gemm_group_workspace_bytes(T, rows, count, n, dt, layout);
+    size_t need = gemm_bytes + 256;
+    for (int i = 0; i < count; ++i) need += scratch_gc_bytes(rows[i], n);
+    if (!ws || ws_bytes < need) return GRASS_ERR_WORKSPACE;
+    char* scratch = static_cast<char*>(ws) + gemm_bytes;
+    scratch += (256 - reinterpret_cast<uintptr_t>(scratch) % 256) % 256;
+    for (int i = 0; i < count; ++i) {
+        const grass_step_layer& L = layers[i];
+        tail[i] = StepTail{L.M, L.V, sdt, lr, beta1, beta2, eps, step_scalars ? 1 : t,
+                           step_scalars, L.W, wdt, L.ldw, alpha};
+        seg[i] = GemmSegment{L.dY, L.ldy, L.idx, L.rho, L.GC ? static_cast<void*>(L.GC) : scratch,
+                             L.GC ? L.ldgc : n, L.r, L.m, &tail[i], L.GC != nullptr};
+        if (!L.GC) scratch += scratch_gc_bytes(L.r, n);
+    }
+    return launch_tn_gemm_segments(seg, count, layout, X, ldx, dt, T, n, GRASS_F32, ws,
+                                   as_stream(stream), static_cast<hipEvent_t>(ev_gemm_start),
+                                   static_cast<hipEvent_t>(ev_gemm_stop));
+}
+
 grass_status grass_adam_step_scalars(float lr, float beta1, float beta2, int64_t t,
                                      float* scalars) {
     if (!scalars) return GRASS_ERR_NULL;

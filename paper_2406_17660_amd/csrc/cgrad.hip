@@ -220,6 +220,15 @@ size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int
     return joint > need ? joint : need;
 }
 
+// Adam and the row update from a G_C that has been written to seg.C (two-kernel route).
+grass_status run_tail_unfused(const GemmSegment& q, int64_t n, hipStream_t s) {
+    if (!q.tail || q.rows == 0) return GRASS_OK;
+    const StepTail& t = *q.tail;
+    return launch_adam_scatter(static_cast<const float*>(q.C), q.ldc, t.M, t.V, t.sdt, q.rows, n,
+                               t.lr, t.beta1, t.beta2, t.eps, t.t, t.W, t.wdt, t.ldw, q.idx, q.rho,
+                               t.alpha, s, t.step_scalars);
+}
+
 // C_i = scale_i * (A_i^T X) for `count` row sets that share X.  The sets are packed side by
 // side into one panel (each starts at a multiple of 8 columns), one GEMM covers the panel,
 // and the partial tiles are reduced into each set's own output.
@@ -249,6 +258,10 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                     ldx, T, g.rows, n, g.idx, g.rho, static_cast<uint16_t*>(g.C), g.ldc);
         }
         if (ev_stop) (void)hipEventRecord(ev_stop, s);
+        for (int i = 0; i < count; ++i) {
+            const grass_status st = run_tail_unfused(seg[i], n, s);
+            if (st != GRASS_OK) return st;
+        }
         return launch_status();
     }
 
@@ -418,7 +431,14 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     int64_t off = 0;
     for (int i = 0; i < count; ++i) {
         const GemmSegment& q = seg[i];
-        if (q.rows > 0) {
+        if (q.rows > 0 && q.tail && odt == GRASS_F32 &&
+            reduce_adam_scatter_ok(*q.tail, n, q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc)) {
+            // reduction, Adam and the row update in one kernel, straight from the partial tiles
+            const grass_status st = launch_reduce_adam_scatter(
+                partial + off * p.Np, slices, p.Mp, p.Np, q.rows, n, *q.tail, q.idx, q.rho,
+                q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc, s);
+            if (st != GRASS_OK) return st;
+        } else if (q.rows > 0) {
             const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
             const float* part = partial + off * p.Np;
             if (slices > kManySlices && p.Np % 128 == 0) {
@@ -434,6 +454,8 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             else
                 splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
                     part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+            const grass_status st = run_tail_unfused(q, n, s);
+            if (st != GRASS_OK) return st;
         }
         off += (q.rows + 7) / 8 * 8;
     }

@@ -113,6 +113,30 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
 constexpr int kProbeWorkgroups = 256;
 grass_status launch_probe_mfma_rate(float* out, int iters, hipStream_t s);
 
+// What follows the compressed gradient in a regular step (Adam on r x n, update of the rows of
+// W).  Given to the GEMM launcher, the split-K reduction, Adam and the update run as one kernel
+// that reads the partial tiles directly; G_C is then only written when the segment names an
+// output for it.
+struct StepTail {
+    void* M;
+    void* V;
+    grass_dtype sdt;
+    float lr, beta1, beta2, eps;
+    int64_t t;
+    const float* step_scalars;  // device {lr, 1/(1-b1^t), 1/(1-b2^t)} or nullptr
+    void* W;
+    grass_dtype wdt;
+    int64_t ldw;
+    float alpha;
+};
+// True when M, V, W (and GC, if given) allow the 16-byte accesses of the fused kernel.
+bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc);
+// part: partial tiles [slices][Mp][Np] (already offset to this segment's first row).
+grass_status launch_reduce_adam_scatter(const float* part, int slices, int64_t Mp, int64_t Np,
+                                        int64_t r, int64_t n, const StepTail& t,
+                                        const int32_t* idx, const float* rho, float* GC,
+                                        int64_t ldgc, hipStream_t s);
+
 // The same product for several row sets that share X (one packed panel, one GEMM).
 struct GemmSegment {
     const void* dY;      // this set's left operand
@@ -123,6 +147,11 @@ struct GemmSegment {
     int64_t ldc;
     int64_t rows;
     int64_t src_rows;    // rows of dY's matrix that idx may name (m); bounds address arithmetic
+    // regular step: Adam + update after (fused with) the reduction.  C must then be a valid
+    // rows x n fp32 buffer in any case (the unfused route goes through it); c_wanted says
+    // whether the caller asked for G_C, i.e. whether the fused kernel has to write it.
+    const StepTail* tail = nullptr;
+    bool c_wanted = true;
 };
 size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
                                   grass_dtype dt, grass_dy_layout layout);

@@ -29,9 +29,17 @@ EXPORTS = [
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
     "grass_adam_rows_state", "grass_adam_scatter_state", "grass_probe_mfma_rate",
     "grass_adam_step_scalars", "grass_adam_scatter_replayable",
+    "grass_step_group_workspace", "grass_step_group",
 ]
 
 _lib = None
+
+
+class StepLayer(C.Structure):
+    """grass_step_layer of include/grass.h."""
+    _fields_ = [("dY", C.c_void_p), ("ldy", C.c_int64), ("m", C.c_int64), ("r", C.c_int64),
+                ("idx", C.c_void_p), ("rho", C.c_void_p), ("GC", C.c_void_p), ("ldgc", C.c_int64),
+                ("M", C.c_void_p), ("V", C.c_void_p), ("W", C.c_void_p), ("ldw", C.c_int64)]
 
 
 class GrassError(RuntimeError):
@@ -74,6 +82,10 @@ def lib():
     L.grass_adam_step_scalars.argtypes = [f32, f32, f32, i64, C.POINTER(C.c_float)]
     L.grass_adam_scatter_replayable.argtypes = [vp, i64, vp, vp, i32, i64, i64, f32, f32, f32, vp,
                                                 vp, i32, i64, i64, vp, vp, f32, vp]
+    L.grass_step_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
+    L.grass_step_group_workspace.restype = sz
+    L.grass_step_group.argtypes = [i32, vp, i32, vp, i64, i32, i64, i64, i32, i32, f32, f32, f32,
+                                   f32, i64, vp, f32, vp, sz, vp, vp, vp]
     L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
     L.grass_dense_workspace.restype = sz
     L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
@@ -90,7 +102,7 @@ def lib():
     for name in EXPORTS:
         if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
                         "grass_dense_workspace", "grass_grad_row_stats_workspace",
-                        "grass_cgrad_group_workspace"):
+                        "grass_cgrad_group_workspace", "grass_step_group_workspace"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -241,6 +253,44 @@ def _moments(M, V, r, n):
     for a in (M, V):
         assert a.shape == (r, n) and a.is_contiguous() and a.is_cuda and a.dtype == M.dtype
     return C.c_void_p(M.data_ptr()), C.c_void_p(V.data_ptr()), _dtype(M)
+
+
+def step_group_workspace(T, n, rs, dtype, layout=DY_TxM) -> int:
+    return int(lib().grass_step_group_workspace(T, n, len(rs), _i64_array(rs), dtype, layout))
+
+
+def step_group(dYs, X, idxs, rhos, Ms, Vs, Ws, lr, beta1, beta2, eps, t, alpha, ws, layout=DY_TxM,
+               GCs=None, step_scalars=None, gemm_events=None):
+    """The regular step (compressed gradient, Adam, row update) of several layers sharing X in
+    one call; GCs: optional list with a tensor (G_C is stored there) or None per layer."""
+    count = len(dYs)
+    pX, T, n, ldx = _mat(X)
+    arr = (StepLayer * count)()
+    sdt = wdt = None
+    for i in range(count):
+        pY, ry, cy, ldy = _mat(dYs[i])
+        assert (ry if layout == DY_TxM else cy) == T and dYs[i].dtype == X.dtype
+        m = cy if layout == DY_TxM else ry
+        r = idxs[i].shape[0]
+        pW, mw, nw, ldw = _mat(Ws[i])
+        assert (mw, nw) == (m, n)
+        pM, pV, sd = _moments(Ms[i], Vs[i], r, n)
+        assert sdt in (None, sd) and wdt in (None, _dtype(Ws[i]))
+        sdt, wdt = sd, _dtype(Ws[i])
+        gc = GCs[i] if GCs is not None else None
+        if gc is not None:
+            pG, gr, gcols, ldgc = _mat(gc)
+            assert (gr, gcols) == (r, n) and gc.dtype == torch.float32
+        arr[i] = StepLayer(pY.value, ldy, m, r, _vec(idxs[i], torch.int32).value,
+                           _vec(rhos[i], torch.float32).value, pG.value if gc is not None else None,
+                           ldgc if gc is not None else 0, pM.value, pV.value, pW.value, ldw)
+    wp, wb = _ws(ws)
+    sc = C.c_void_p(step_scalars.data_ptr()) if step_scalars is not None else None
+    e0, e1 = ((C.c_void_p(e.cuda_event) for e in gemm_events) if gemm_events is not None
+              else (None, None))
+    _check(lib().grass_step_group(count, arr, layout, pX, ldx, _dtype(X), T, n, sdt, wdt, lr, beta1,
+                                  beta2, eps, t, sc, alpha, wp, wb, _stream(), e0, e1),
+           "grass_step_group")
 
 
 def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, U):

@@ -37,7 +37,7 @@ class GrassLayer:
     def __init__(self, m, n, r, T, dtype, method="topr", replacement=False,
                  scale=grass.SCALE_PAPER, alpha=0.25, adam=None, seed=0, g_dtype=None,
                  layout=grass.DY_TxM, device="cuda", materialise_G=False, side="rows",
-                 state_dtype=torch.float32):
+                 state_dtype=torch.float32, store_GC=True):
         assert side in ("rows", "cols")
         self.side = side
         self.w_shape = (m, n)
@@ -59,7 +59,11 @@ class GrassLayer:
         self.GC = torch.empty((r, n), dtype=torch.float32, device=dev)
         self.sumsq = torch.empty(m, dtype=torch.float32, device=dev)
         self.ws_sel = grass.workspace(grass.select_workspace(m, r, self.method, replacement), dev)
-        self.ws_gemm = grass.workspace(grass.cgrad_workspace(T, m, n, r, self.dt, layout), dev)
+        # one workspace serves both the separate calls and the one-call step
+        self.ws_gemm = grass.workspace(max(grass.cgrad_workspace(T, m, n, r, self.dt, layout),
+                                           grass.step_group_workspace(T, n, [r], self.dt, layout)),
+                                       dev)
+        self.store_GC = store_GC  # False: the one-call step does not write G_C at all
         self.ws_dense = None  # allocated on first refresh: only refresh steps need it
         self.G = None
         self.ws_stats = None
@@ -130,5 +134,16 @@ class GrassLayer:
                                   self.adam_t, W, self.idx, self.rho, self.alpha)
 
     def step(self, dY, X, W, gemm_events=None):
-        self.compressed_grad(dY, X, gemm_events)
-        self.adam_scatter(W)
+        """The regular step.  Row selection: one library call (grass_step_group) in which the
+        reduction of the product, Adam and the row update are one kernel.  Column selection:
+        the three separate calls."""
+        if self.side == "cols":
+            self.compressed_grad(dY, X, gemm_events)
+            self.adam_scatter(W)
+            return
+        self.adam_t += 1
+        a = self.adam
+        assert tuple(W.shape) == self.w_shape
+        grass.step_group([dY], X, [self.idx], [self.rho], [self.M], [self.V], [W], a.lr, a.beta1,
+                         a.beta2, a.eps, self.adam_t, self.alpha, self.ws_gemm, self.layout,
+                         GCs=[self.GC] if self.store_GC else None, gemm_events=gemm_events)

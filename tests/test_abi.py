@@ -202,6 +202,45 @@ def test_replayable_adam_validation_and_step_scalars():
     assert f(*bad) == grass.ERR_SHAPE
 
 
+def test_step_group_validation():
+    import ctypes as C
+    L = grass.lib()
+    f = L.grass_step_group
+    big = 1 << 40
+
+    def layer(**kw):
+        d = dict(dY=FAKE, ldy=64, m=64, r=8, idx=FAKE, rho=FAKE, GC=None, ldgc=0, M=FAKE, V=FAKE,
+                 W=FAKE, ldw=32)
+        d.update(kw)
+        return grass.StepLayer(d["dY"], d["ldy"], d["m"], d["r"], d["idx"], d["rho"], d["GC"],
+                               d["ldgc"], d["M"], d["V"], d["W"], d["ldw"])
+
+    def call(layers, count=None, ldx=32, dt=grass.BF16, T=128, n=32, sdt=grass.F32, wdt=grass.BF16,
+             t=1, scal=None, ws=FAKE, wsb=big):
+        arr = (grass.StepLayer * len(layers))(*layers)
+        return f(len(layers) if count is None else count, arr, 0, FAKE, ldx, dt, T, n, sdt, wdt, 1e-3,
+                 0.9, 0.999, 1e-8, t, scal, 0.25, ws, wsb, None, None, None)
+
+    assert call([layer()], count=0) == grass.ERR_SHAPE
+    assert call([layer()], count=9) == grass.ERR_SHAPE
+    assert call([layer(dY=None)]) == grass.ERR_NULL
+    assert call([layer(M=None)]) == grass.ERR_NULL
+    assert call([layer(W=None)]) == grass.ERR_NULL
+    assert call([layer(idx=None)]) == grass.ERR_NULL
+    assert call([layer(ldy=63)]) == grass.ERR_SHAPE
+    assert call([layer(ldw=31)]) == grass.ERR_SHAPE
+    assert call([layer(GC=FAKE, ldgc=31)]) == grass.ERR_SHAPE
+    assert call([layer()], t=0) == grass.ERR_SHAPE
+    assert call([layer()], sdt=5) == grass.ERR_DTYPE
+    assert call([layer()], wdt=5) == grass.ERR_DTYPE
+    assert call([layer()], ws=None) == grass.ERR_WORKSPACE
+    assert call([layer()], wsb=1024) == grass.ERR_WORKSPACE
+    i64 = (C.c_int64 * 2)(256, 256)
+    a = L.grass_step_group_workspace(4096, 512, 2, i64, grass.BF16, 0)
+    b = L.grass_cgrad_group_workspace(4096, 512, 2, i64, grass.BF16, 0)
+    assert a >= b + 2 * 256 * 512 * 4  # room for a G_C per layer that does not name one
+
+
 def test_probe_validation():
     import ctypes as C
     f = grass.lib().grass_probe_mfma_rate

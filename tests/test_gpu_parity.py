@@ -787,3 +787,56 @@ def test_select_rows_random_sizes_bit_exact(case):
     w_idx, w_rho, _ = ref.select_rows(ss, r, method, repl, seed=case, refresh_id=case * 7)
     assert status == grass.OK
     assert np.array_equal(idx.cpu().numpy(), w_idx) and np.array_equal(rho.cpu().numpy(), w_rho)
+
+
+# ------------------------------------------------------------------------------ the whole regular step in one call
+@pytest.mark.parametrize("dtype,wdtype,sdtype", [(torch.bfloat16, torch.bfloat16, torch.float32),
+                                                 (torch.bfloat16, torch.float32, torch.bfloat16),
+                                                 (torch.float32, torch.float32, torch.float32)])
+@pytest.mark.parametrize("T,n,ms,rs,want_gc,tile", [
+    (512, 256, (256,), (16,), True, None),                   # one layer, G_C requested
+    (4096, 512, (300, 520, 64), (130, 129, 0), False, None), # group, many K slices, an empty set
+    (1056, 264, (300, 520), (130, 129), True, "256"),        # large tile, K tail
+    (777, 334, (130, 90), (40, 9), False, None),             # n % 4 != 0: the two-kernel route
+    (640, 1024, (400,), (256,), False, "256"),               # duplicates walk runs across the tile
+])
+def test_step_group_equals_the_separate_calls_and_the_oracle(monkeypatch, dtype, wdtype, sdtype, T, n,
+                                                             ms, rs, want_gc, tile):
+    if tile:
+        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    X = randn((T, n), dtype, 120)
+    dYs, idxs, rhos, Ms, Vs, Ws, host = [], [], [], [], [], [], []
+    for i, (m, r) in enumerate(zip(ms, rs)):
+        dY = randn((T, m), dtype, 121 + i, scale=0.1)
+        idx, rho = make_idx(m, r, 130 + i, duplicates=True)
+        GC_, M, V = adam_inputs(r, n, 140 + i, n) if r else (None, torch.zeros((0, n), device=DEV),
+                                                             torch.zeros((0, n), device=DEV))
+        M, V = M.to(sdtype).contiguous(), V.to(sdtype).contiguous()
+        W = randn((m, n), wdtype, 150 + i, scale=0.02)
+        host.append((dY, idx, rho, to_f64(M).copy(), to_f64(V).copy(), to_f64(W).copy(), to_np(W).copy()))
+        dYs.append(dY); idxs.append(torch.from_numpy(idx).to(DEV)); rhos.append(torch.from_numpy(rho).to(DEV))
+        Ms.append(M); Vs.append(V); Ws.append(W)
+    GCs = [torch.full((r, n), float("nan"), device=DEV) for r in rs] if want_gc else None
+    dt = grass.F32 if dtype == torch.float32 else grass.BF16
+    ws = grass.workspace(grass.step_group_workspace(T, n, rs, dt))
+    grass.step_group(dYs, X, idxs, rhos, Ms, Vs, Ws, LR, B1, B2, EPS, 3, 0.25, ws, GCs=GCs)
+    f = np.float32
+    for i, (dY, idx, rho, M0, V0, W0, W0_bits) in enumerate(host):
+        if rs[i] == 0:
+            assert np.array_equal(to_np(Ws[i]), W0_bits)
+            continue
+        GC = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+        if want_gc:
+            assert rel_fro(to_f64(GCs[i]), GC) <= 2e-5
+        # Adam is ill-conditioned where G_C cancels: feed the oracle the fp32 G_C of the GPU when known
+        g_in = to_f64(GCs[i]) if want_gc else GC
+        U = ref.adam_rows(g_in, M0, V0, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 3,
+                          state_bf16=sdtype == torch.bfloat16)
+        Wo = W0.copy()
+        ref.scatter_update(Wo, idx, rho, 0.25, U)
+        sel = np.unique(idx)
+        state_tol = 1e-2 if sdtype == torch.bfloat16 else 2e-5
+        assert rel_fro(to_f64(Ms[i]), M0) <= state_tol and rel_fro(to_f64(Vs[i]), V0) <= state_tol
+        assert rel_fro(to_f64(Ws[i])[sel], Wo[sel]) <= tol_for(wdtype)
+        rest = np.setdiff1d(np.arange(ms[i]), sel)
+        assert np.array_equal(to_np(Ws[i])[rest], W0_bits[rest])
