@@ -319,6 +319,52 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
     }
 }
 
+// The same for a handful of slices: every thread adds all slices of its own four columns (the
+// loads are independent, nothing goes through LDS) and all four wavefronts run Adam, so the
+// kernel keeps as many bytes in flight as adam_scatter_kernel does.
+template <typename WT, typename ST>
+__global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
+    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
+    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
+    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
+    float* __restrict__ GC, int64_t ldgc) {
+    const AdamParams p = resolve(p_in);
+    const int64_t j = blockIdx.y;
+    const int32_t row = idx[j];
+    if (j > 0 && idx[j - 1] == row) return;
+    const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (c >= n) return;  // n % 4 == 0: four whole columns or none
+    const int64_t slice_stride = Mp * Np;
+    WVec<WT, 4> wv;
+    wv.load(W + static_cast<int64_t>(row) * ldw + c);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+        WVec<ST, 4> mv, vv;
+        mv.load(M + jj * n + c);
+        vv.load(V + jj * n + c);
+        const float* src = part + jj * Np + c;
+        F32Vec<4> g;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g.x[e] = 0.f;
+#pragma unroll 8
+        for (int k = 0; k < slices; ++k, src += slice_stride) {
+            const float4 v = *reinterpret_cast<const float4*>(src);
+            g.x[0] += v.x; g.x[1] += v.y; g.x[2] += v.z; g.x[3] += v.w;
+        }
+        const float sc = rho[jj];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) g.x[e] *= sc;
+        if (GC) g.store(GC + jj * ldgc + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+        mv.store(M + jj * n + c);
+        vv.store(V + jj * n + c);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
+    wv.store(W + static_cast<int64_t>(row) * ldw + c);
+}
+
 template <typename GT, int VEC>
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(
     const GT* __restrict__ G, int64_t ldg, const int32_t* __restrict__ idx,
@@ -550,52 +596,6 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
 bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc) {
     return n % 4 == 0 && w_rows_vectorisable(t.M, t.sdt, n) && w_rows_vectorisable(t.V, t.sdt, n) &&
            w_rows_vectorisable(t.W, t.wdt, t.ldw) && (!GC || f32_rows_vectorisable(GC, ldgc));
-}
-
-// The same for a handful of slices: every thread adds all slices of its own four columns (the
-// loads are independent, nothing goes through LDS) and all four wavefronts run Adam, so the
-// kernel keeps as many bytes in flight as adam_scatter_kernel does.
-template <typename WT, typename ST>
-__global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
-    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
-    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
-    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
-    float* __restrict__ GC, int64_t ldgc) {
-    const AdamParams p = resolve(p_in);
-    const int64_t j = blockIdx.y;
-    const int32_t row = idx[j];
-    if (j > 0 && idx[j - 1] == row) return;
-    const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
-    if (c >= n) return;  // n % 4 == 0: four whole columns or none
-    const int64_t slice_stride = Mp * Np;
-    WVec<WT, 4> wv;
-    wv.load(W + static_cast<int64_t>(row) * ldw + c);
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
-        WVec<ST, 4> mv, vv;
-        mv.load(M + jj * n + c);
-        vv.load(V + jj * n + c);
-        const float* src = part + jj * Np + c;
-        F32Vec<4> g;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) g.x[e] = 0.f;
-#pragma unroll 8
-        for (int k = 0; k < slices; ++k, src += slice_stride) {
-            const float4 v = *reinterpret_cast<const float4*>(src);
-            g.x[0] += v.x; g.x[1] += v.y; g.x[2] += v.z; g.x[3] += v.w;
-        }
-        const float sc = rho[jj];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) g.x[e] *= sc;
-        if (GC) g.store(GC + jj * ldgc + c);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
-        mv.store(M + jj * n + c);
-        vv.store(V + jj * n + c);
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
-    wv.store(W + static_cast<int64_t>(row) * ldw + c);
 }
 
 template <typename WT, typename ST>
