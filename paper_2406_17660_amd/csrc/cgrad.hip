@@ -326,16 +326,12 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                     int tpr_log2 = 8;  // threads per row of t: the power of two covering width / 4
                     while (tpr_log2 > 0 && (int64_t{4} << (tpr_log2 - 1)) >= width) --tpr_log2;
                     const int64_t gx = (width + (int64_t{4} << tpr_log2) - 1) / (int64_t{4} << tpr_log2);
-                    const int64_t passes = (T + (256 >> tpr_log2) - 1) / (256 >> tpr_log2);
-                    int64_t rpt = passes * gx / 2048;  // aim at >= 2048 workgroups
-                    rpt = rpt < 4 ? 4 : (rpt > kPackRows ? kPackRows : rpt);
-                    const int64_t rows_per_wg = rpt * (256 >> tpr_log2);
-                    const dim3 grid(static_cast<unsigned>(gx),
-                                    static_cast<unsigned>((T + rows_per_wg - 1) / rows_per_wg));
+                    const int64_t rows_per_wg = static_cast<int64_t>(kPackRows) * (256 >> tpr_log2);
+                    const dim3 grid(static_cast<unsigned>((T + rows_per_wg - 1) / rows_per_wg),
+                                    static_cast<unsigned>(gx));
                     pack_txm_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(seg[i].dY),
                                                          seg[i].ldy, T, seg[i].idx, seg[i].rows,
-                                                         width, p.rp, tpr_log2,
-                                                         static_cast<int>(rpt), panel + off);
+                                                         width, p.rp, tpr_log2, panel + off);
                 } else if (aligned_to(seg[i].dY, 16) && seg[i].ldy % 8 == 0 && p.rp % 8 == 0 &&
                            width % 8 == 0) {
                     const dim3 grid(static_cast<unsigned>((width + kPackWideJ - 1) / kPackWideJ),

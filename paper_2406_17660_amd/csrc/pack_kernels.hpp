@@ -12,25 +12,26 @@ namespace {
 // of `out` are ldo apart (several matrices may fill adjacent column ranges of one panel).
 // Thread = 4 adjacent j; 2^tpr_log2 threads cover the columns of one row of t (a narrow panel,
 // r = 128 say, puts several rows of t side by side in a workgroup instead of idling most of
-// it), and every thread loops over rows_per_thread (4 .. kPackRows) values of t: fewer when
-// the matrix is small, so that the launch still has a few thousand workgroups to hide the
-// latency of the gather.  Wave stores are contiguous.
-constexpr int kPackRows = 16;
+// it), and every thread handles kPackRows values of t, all of whose loads are issued before
+// the first store.  Four measured best at the 7B layer: 8 or 16 rows per thread leave fewer
+// workgroups to hide the latency of the gather (5 - 8 % slower), 1 or 2 do not amortise the
+// loads of idx.  Wave stores are contiguous.
+constexpr int kPackRows = 4;
 __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restrict__ dY, int64_t ldy,
                                                        int64_t T, const int32_t* __restrict__ idx,
                                                        int64_t r, int64_t rp, int64_t ldo,
-                                                       int tpr_log2, int rows_per_thread,
-                                                       uint16_t* __restrict__ out) {
+                                                       int tpr_log2, uint16_t* __restrict__ out) {
     const int tpr = 1 << tpr_log2, rows_per_pass = 256 >> tpr_log2;
-    const int64_t j0 = (static_cast<int64_t>(blockIdx.x) * tpr + (threadIdx.x & (tpr - 1))) * 4;
+    // blockIdx.x runs over t (it can be large), blockIdx.y over the blocks of j
+    const int64_t j0 = (static_cast<int64_t>(blockIdx.y) * tpr + (threadIdx.x & (tpr - 1))) * 4;
     if (j0 >= rp) return;
     int64_t col[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) col[e] = j0 + e < r ? (idx ? idx[j0 + e] : j0 + e) : -1;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_thread * rows_per_pass +
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kPackRows * rows_per_pass +
                        (threadIdx.x >> tpr_log2);
-#pragma unroll 4
-    for (int tt = 0; tt < rows_per_thread; ++tt) {
+#pragma unroll
+    for (int tt = 0; tt < kPackRows; ++tt) {
         const int64_t t = t0 + static_cast<int64_t>(tt) * rows_per_pass;
         if (t >= T) break;
         const uint16_t* row = dY + t * ldy;

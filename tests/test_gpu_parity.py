@@ -840,3 +840,16 @@ def test_step_group_equals_the_separate_calls_and_the_oracle(monkeypatch, dtype,
         assert rel_fro(to_f64(Ws[i])[sel], Wo[sel]) <= tol_for(wdtype)
         rest = np.setdiff1d(np.arange(ms[i]), sel)
         assert np.array_equal(to_np(Ws[i])[rest], W0_bits[rest])
+
+
+@pytest.mark.parametrize("layout", [grass.DY_TxM, grass.DY_MxT])
+def test_compressed_grad_very_long_token_batch(layout):
+    """T = 300001 (beyond the paper's 262144 tokens per step): launch grids indexed by t stay legal."""
+    T, m, n, r = 300001, 72, 64, 9
+    dY = randn((T, m), torch.bfloat16, 171, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 172)
+    idx, rho = make_idx(m, r, 173, False)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    got = to_f64(gpu_cgrad(dY_dev, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), layout))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert rel_fro(got, want) <= 2e-5
