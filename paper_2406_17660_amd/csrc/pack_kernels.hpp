@@ -12,10 +12,10 @@ namespace {
 // of `out` are ldo apart (several matrices may fill adjacent column ranges of one panel).
 // Thread = 4 adjacent j; 2^tpr_log2 threads cover the columns of one row of t (a narrow panel,
 // r = 128 say, puts several rows of t side by side in a workgroup instead of idling most of
-// it), and every thread handles kPackRows values of t, all of whose loads are issued before
-// the first store.  Four measured best at the 7B layer: 8 or 16 rows per thread leave fewer
-// workgroups to hide the latency of the gather (5 - 8 % slower), 1 or 2 do not amortise the
-// loads of idx.  Wave stores are contiguous.
+// it), and every thread handles kPackRows values of t, one after the other.  Four measured
+// best at the 7B layer: 8 or 16 rows per thread leave fewer workgroups to hide the latency
+// of the gather (5 - 8 % slower), 1 or 2 do not amortise the loads of idx, and issuing the
+// loads of all rows before the first store is 12 % slower.  Wave stores are contiguous.
 constexpr int kPackRows = 4;
 __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restrict__ dY, int64_t ldy,
                                                        int64_t T, const int32_t* __restrict__ idx,
