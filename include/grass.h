@@ -30,7 +30,8 @@
  *     scatter_update, adam_scatter, gather_rows, dense_grad's m) accept at most
  *     65535 rows and return GRASS_ERR_SHAPE beyond that.
  *   - r = 0, n = 0 or T = 0 are legal where they make sense (see each call) and
- *     produce the empty / zero result.  T, m and n are below 2^31.
+ *     produce the empty / zero result.  Every size (T, m, n, r) is below 2^31;
+ *     GRASS_ERR_SHAPE (0 from a workspace query) beyond that.
  *   - No call records a memset or an event (the _timed call excepted) or allocates, so
  *     calls can be captured into a HIP graph.
  */

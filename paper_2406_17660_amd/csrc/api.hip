@@ -12,6 +12,8 @@ constexpr int64_t kMaxGridRows = 65535;  // rows are carried in blockIdx.y
 
 // A pointer may be NULL only when the array it names has no elements.
 bool present(const void* p, int64_t elems) { return p != nullptr || elems <= 0; }
+// Every size of the interface is below 2^31, so that products of two of them fit 64 bits.
+bool small(int64_t v) { return v < (int64_t{1} << 31); }
 bool dtype_ok(grass_dtype d) { return d == GRASS_F32 || d == GRASS_BF16; }
 bool layout_ok(grass_dy_layout l) { return l == GRASS_DY_TxM || l == GRASS_DY_MxT; }
 hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
@@ -20,8 +22,7 @@ grass_status check_products(const void* dY, grass_dy_layout layout, int64_t ldy,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t m, int64_t n) {
     if (T < 0 || m < 0 || n < 0 || ldx < n) return GRASS_ERR_SHAPE;
     // sizes first: the products below then fit 64 bits
-    if (m >= (int64_t{1} << 31) || n >= (int64_t{1} << 31) || T >= (int64_t{1} << 31))
-        return GRASS_ERR_SHAPE;
+    if (!small(m) || !small(n) || !small(T)) return GRASS_ERR_SHAPE;
     if (!present(dY, T * m) || !present(X, T * n)) return GRASS_ERR_NULL;
     if (!dtype_ok(dt) || !layout_ok(layout)) return GRASS_ERR_DTYPE;
     if (ldy < (layout == GRASS_DY_TxM ? m : T)) return GRASS_ERR_SHAPE;
@@ -30,7 +31,7 @@ grass_status check_products(const void* dY, grass_dy_layout layout, int64_t ldy,
 
 grass_status check_adam(const float* GC, int64_t ldgc, const void* M, const void* V,
                         grass_dtype sdt, int64_t r, int64_t n, float beta1, float beta2, int64_t t) {
-    if (r < 0 || n < 0 || ldgc < n || t < 1) return GRASS_ERR_SHAPE;
+    if (r < 0 || n < 0 || ldgc < n || t < 1 || !small(r) || !small(n)) return GRASS_ERR_SHAPE;
     if (!present(GC, r * n) || !present(M, r * n) || !present(V, r * n)) return GRASS_ERR_NULL;
     if (!dtype_ok(sdt)) return GRASS_ERR_DTYPE;
     if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return GRASS_ERR_SHAPE;
@@ -39,7 +40,8 @@ grass_status check_adam(const float* GC, int64_t ldgc, const void* M, const void
 
 grass_status check_rows_of_w(const void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
                              const int32_t* idx, const float* rho, int64_t r) {
-    if (m < 0 || n < 0 || r < 0 || ldw < n || r > kMaxGridRows) return GRASS_ERR_SHAPE;
+    if (m < 0 || n < 0 || r < 0 || ldw < n || r > kMaxGridRows || !small(m) || !small(n))
+        return GRASS_ERR_SHAPE;
     if (!present(W, m * n) || !present(idx, r) || !present(rho, r)) return GRASS_ERR_NULL;
     if (!dtype_ok(wdt)) return GRASS_ERR_DTYPE;
     if (r > 0 && m == 0) return GRASS_ERR_SHAPE;
@@ -65,7 +67,7 @@ const char* grass_status_string(grass_status s) {
 
 grass_status grass_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n, int64_t ldg,
                              float* sumsq, void* stream) {
-    if (m < 0 || n < 0 || ldg < n || m >= (int64_t{1} << 31)) return GRASS_ERR_SHAPE;
+    if (m < 0 || n < 0 || ldg < n || !small(m) || !small(n)) return GRASS_ERR_SHAPE;
     if (!present(G, m * n) || !present(sumsq, m)) return GRASS_ERR_NULL;
     if (!dtype_ok(dt)) return GRASS_ERR_DTYPE;
     return launch_row_stats(G, dt, m, n, ldg, sumsq, as_stream(stream));
@@ -84,8 +86,7 @@ grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_m
     if (method < GRASS_SEL_TOPR || method > GRASS_SEL_MULTI_NORM2) return GRASS_ERR_DTYPE;
     if (scale < GRASS_SCALE_PAPER || scale > GRASS_SCALE_INV_SQRT_RQ) return GRASS_ERR_DTYPE;
     if (method == GRASS_SEL_TOPR && scale == GRASS_SCALE_INV_SQRT_RQ) return GRASS_ERR_DTYPE;
-    if (m < 0 || r < 0 || m >= (int64_t{1} << 31) || r >= (int64_t{1} << 31))
-        return GRASS_ERR_SHAPE;
+    if (!small(m) || !small(r)) return GRASS_ERR_SHAPE;
     const bool with_repl = method != GRASS_SEL_TOPR && replacement;
     if (!with_repl && r > m) return GRASS_ERR_SHAPE;
     if (r > 0 && m == 0) return GRASS_ERR_SHAPE;
@@ -98,7 +99,7 @@ grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_m
 size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt,
                              grass_dy_layout layout) {
     (void)m;
-    if (T < 0 || n < 0 || r < 0) return 0;
+    if (T < 0 || n < 0 || r < 0 || !small(T) || !small(n) || !small(r)) return 0;
     return gemm_workspace_bytes(T, r, n, dt, layout, true);
 }
 
@@ -130,7 +131,8 @@ grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout,
 
 size_t grass_cgrad_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
                                    grass_dtype dt, grass_dy_layout layout) {
-    if (T < 0 || n < 0 || count < 1 || count > GRASS_MAX_GROUP || !r) return 0;
+    if (T < 0 || n < 0 || !small(T) || !small(n) || count < 1 || count > GRASS_MAX_GROUP || !r)
+        return 0;
     for (int i = 0; i < count; ++i)
         if (r[i] < 0 || r[i] > kMaxGridRows) return 0;
     return gemm_group_workspace_bytes(T, r, count, n, dt, layout);
@@ -190,7 +192,8 @@ grass_status grass_scatter_update(void* W, grass_dtype wdt, int64_t m, int64_t n
 grass_status grass_scatter_update_cols(void* W, grass_dtype wdt, int64_t m, int64_t n, int64_t ldw,
                                        const int32_t* idx, const float* rho, float alpha,
                                        const float* U, int64_t r, void* stream) {
-    if (m < 0 || n < 0 || r < 0 || ldw < n || (r + 63) / 64 > kMaxGridRows || (r > 0 && n == 0))
+    if (m < 0 || n < 0 || r < 0 || ldw < n || !small(m) || !small(n) || !small(r) ||
+        (r + 63) / 64 > kMaxGridRows || (r > 0 && n == 0))
         return GRASS_ERR_SHAPE;
     if (!present(W, m * n) || !present(idx, r) || !present(rho, r) || !present(U, r * m))
         return GRASS_ERR_NULL;
@@ -225,7 +228,8 @@ static size_t scratch_gc_bytes(int64_t r, int64_t n) {
 
 size_t grass_step_group_workspace(int64_t T, int64_t n, int count, const int64_t* r,
                                   grass_dtype dt, grass_dy_layout layout) {
-    if (T < 0 || n < 0 || count < 1 || count > GRASS_MAX_GROUP || !r) return 0;
+    if (T < 0 || n < 0 || !small(T) || !small(n) || count < 1 || count > GRASS_MAX_GROUP || !r)
+        return 0;
     size_t extra = 256;  // a G_C for every layer that does not name one (the two-kernel route)
     for (int i = 0; i < count; ++i) {
         if (r[i] < 0 || r[i] > kMaxGridRows) return 0;
@@ -303,7 +307,7 @@ grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* 
 
 size_t grass_dense_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
                              grass_dy_layout layout) {
-    if (T < 0 || m < 0 || n < 0) return 0;
+    if (T < 0 || m < 0 || n < 0 || !small(T) || !small(m) || !small(n)) return 0;
     return gemm_workspace_bytes(T, m, n, dt, layout, false);
 }
 
@@ -324,7 +328,7 @@ grass_status grass_dense_grad(const void* dY, grass_dy_layout layout, int64_t ld
 
 size_t grass_grad_row_stats_workspace(int64_t T, int64_t m, int64_t n, grass_dtype dt,
                                       grass_dy_layout layout, int64_t ldy, int64_t ldx) {
-    if (T < 0 || m < 0 || n < 0) return 0;
+    if (T < 0 || m < 0 || n < 0 || !small(T) || !small(m) || !small(n)) return 0;
     return grad_row_stats_workspace_bytes(T, m, n, dt, layout, ldy, ldx);
 }
 
@@ -345,7 +349,8 @@ grass_status grass_grad_row_stats(const void* dY, grass_dy_layout layout, int64_
 grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,
                                const int32_t* idx, const float* rho, int64_t r, float* out,
                                int64_t ldo, void* stream) {
-    if (m < 0 || n < 0 || r < 0 || ldg < n || ldo < n || r > kMaxGridRows || (r > 0 && m == 0))
+    if (m < 0 || n < 0 || r < 0 || ldg < n || ldo < n || r > kMaxGridRows || !small(m) ||
+        !small(n) || (r > 0 && m == 0))
         return GRASS_ERR_SHAPE;
     if (!present(G, m * n) || !present(idx, r) || !present(rho, r) || !present(out, r * n))
         return GRASS_ERR_NULL;

@@ -134,6 +134,26 @@ def test_compressed_grad_group_validation():
     assert L.grass_cgrad_group_workspace(4096, 512, 0, i64(), grass.BF16, 0) == 0
 
 
+def test_sizes_of_2_to_the_31_and_more_are_refused_everywhere():
+    """Every size is below 2^31, so that no product of two of them can leave 64 bits."""
+    L = grass.lib()
+    big = 1 << 31
+    assert L.grass_row_stats(FAKE, grass.F32, 4, big, big, FAKE, None) == grass.ERR_SHAPE
+    assert L.grass_row_stats(FAKE, grass.F32, big, 4, 4, FAKE, None) == grass.ERR_SHAPE
+    assert L.grass_adam_rows(FAKE, big, FAKE, FAKE, 2, big, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE,
+                             None) == grass.ERR_SHAPE
+    assert L.grass_adam_rows(FAKE, 8, FAKE, FAKE, big, 8, 1e-3, 0.9, 0.999, 1e-8, 1, FAKE,
+                             None) == grass.ERR_SHAPE
+    assert L.grass_scatter_update(FAKE, 0, big, 8, 8, FAKE, FAKE, 1.0, FAKE, 2,
+                                  None) == grass.ERR_SHAPE
+    assert L.grass_scatter_update_cols(FAKE, 0, big, 8, 8, FAKE, FAKE, 1.0, FAKE, 2,
+                                       None) == grass.ERR_SHAPE
+    assert L.grass_gather_rows(FAKE, 0, 4, big, big, FAKE, FAKE, 2, FAKE, big,
+                               None) == grass.ERR_SHAPE
+    assert grass.cgrad_workspace(big, 256, 256, 16, grass.BF16) == 0
+    assert grass.dense_workspace(1024, big, 512, grass.BF16) == 0
+
+
 def test_adam_and_scatter_validation():
     L = grass.lib()
     a = L.grass_adam_rows
