@@ -314,6 +314,11 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
     uint16_t* panel = reinterpret_cast<uint16_t*>(base);
     float* partial = reinterpret_cast<float*>(base + p.pack_bytes);
+    // launch sizes are checked before the first launch: a refused call has done nothing
+    const int64_t items = static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.splits;
+    const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
+    const int x_chunks = static_cast<int>((nb / 2 + 1023) / 1024);
+    if (chunk * kNumXcd > 0x7FFFFFFF || (copy_x && T * x_chunks > 0x7FFFFFFF)) return GRASS_ERR_SHAPE;
 
     GemmArgs g;
     if (pack) {
@@ -334,14 +339,14 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                                                          width, p.rp, tpr_log2, panel + off);
                 } else if (aligned_to(seg[i].dY, 16) && seg[i].ldy % 8 == 0 && p.rp % 8 == 0 &&
                            width % 8 == 0) {
-                    const dim3 grid(static_cast<unsigned>((width + kPackWideJ - 1) / kPackWideJ),
-                                    static_cast<unsigned>((T + kPackWideT - 1) / kPackWideT));
+                    const dim3 grid(static_cast<unsigned>((T + kPackWideT - 1) / kPackWideT),
+                                    static_cast<unsigned>((width + kPackWideJ - 1) / kPackWideJ));
                     pack_mxt_wide_kernel<<<grid, 256, 0, s>>>(
                         static_cast<const uint16_t*>(seg[i].dY), seg[i].ldy, T, seg[i].idx,
                         seg[i].rows, width, p.rp, panel + off);
                 } else {
-                    const dim3 grid(static_cast<unsigned>((width + 63) / 64),
-                                    static_cast<unsigned>((T + 63) / 64));
+                    const dim3 grid(static_cast<unsigned>((T + 63) / 64),
+                                    static_cast<unsigned>((width + 63) / 64));
                     pack_mxt_kernel<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(seg[i].dY),
                                                          seg[i].ldy, T, seg[i].idx, seg[i].rows,
                                                          width, p.rp, panel + off);
@@ -362,10 +367,8 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     g.a_rows = a_rows_form ? seg[0].idx : nullptr;
     if (copy_x) {
         uint16_t* xa = reinterpret_cast<uint16_t*>(base + p.pack_bytes + round_up(p.partial_bytes, 256));
-        const int chunks = static_cast<int>((nb / 2 + 1023) / 1024);
-        if (T * chunks > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
-        align_rows_kernel<<<static_cast<unsigned>(T * chunks), 256, 0, s>>>(
-            static_cast<const uint16_t*>(X), ldx, n, nb, chunks, xa);
+        align_rows_kernel<<<static_cast<unsigned>(T * x_chunks), 256, 0, s>>>(
+            static_cast<const uint16_t*>(X), ldx, n, nb, x_chunks, xa);
         g.B = xa;
         g.ldb = nb;
         g.Ncols = nb;
@@ -385,9 +388,6 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     g.splits = p.splits;
     g.ktiles_per_split = p.ktiles_per_split;
 
-    const int64_t items = static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.splits;
-    const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
-    if (chunk * kNumXcd > 0x7FFFFFFF) return GRASS_ERR_SHAPE;
     if (ev_start) (void)hipEventRecord(ev_start, s);
     const unsigned grid = static_cast<unsigned>(chunk * kNumXcd);
     hipError_t le;

@@ -52,8 +52,9 @@ __global__ __launch_bounds__(256) void pack_mxt_kernel(const uint16_t* __restric
                                                        int64_t r, int64_t rp, int64_t ldo,
                                                        uint16_t* __restrict__ out) {
     __shared__ uint16_t tile[64][66];
-    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * 64;
+    // blockIdx.x runs over t (it can be large), blockIdx.y over the blocks of j
+    const int64_t j0 = static_cast<int64_t>(blockIdx.y) * 64;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * 64;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     for (int jj = w; jj < 64; jj += 4) {
         const int64_t j = j0 + jj, t = t0 + lane;
@@ -83,8 +84,8 @@ __global__ __launch_bounds__(256) void pack_mxt_wide_kernel(const uint16_t* __re
                                                             uint16_t* __restrict__ out) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[kPackWideJ * kPackWideLd];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * kPackWideJ;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * kPackWideT;
+    const int64_t j0 = static_cast<int64_t>(blockIdx.y) * kPackWideJ;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kPackWideT;
     const int chunk = threadIdx.x & 31;  // 8 values of t each
 #pragma unroll
     for (int pass = 0; pass < kPackWideJ / 8; ++pass) {

@@ -853,3 +853,18 @@ def test_compressed_grad_very_long_token_batch(layout):
     got = to_f64(gpu_cgrad(dY_dev, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), layout))
     want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
     assert rel_fro(got, want) <= 2e-5
+
+
+@pytest.mark.parametrize("layout,T", [(grass.DY_TxM, 4_200_003), (grass.DY_MxT, 4_200_003),
+                                      (grass.DY_MxT, 16_800_008)])
+def test_compressed_grad_millions_of_tokens(layout, T):
+    """More than 65535 blocks of t in every packing kernel (64 and 256 rows of t per block): the
+    block index over t is the x dimension of their grids."""
+    m, n, r = 16, 8, 4
+    dY = randn((T, m), torch.bfloat16, 181, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 182)
+    idx, rho = make_idx(m, r, 183, False)
+    dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
+    got = to_f64(gpu_cgrad(dY_dev, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), layout))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert rel_fro(got, want) <= 2e-5
