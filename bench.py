@@ -92,12 +92,15 @@ def cpu_baseline(cfg, layer, dY, X, state, W, seconds):
         t = t.cpu()
         return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
 
-    state.compressed_grad(dY, X)  # the timed steps do not store G_C; the oracle's Adam is fed one
     cores = len(os.sched_getaffinity(0))
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
     dYh, Xh = host(dY), host(X)
-    idx, rho = state.idx.cpu().numpy(), state.rho.cpu().numpy()
-    r = len(idx)
+    # the oracle's inputs are seeded draws of its own (nothing the GPU computed): r rows drawn
+    # with replacement, unit scales, a normal compressed gradient for the Adam + update leg
+    rng = np.random.default_rng(2406)
+    r = state.r
+    idx = np.sort(rng.integers(0, state.m, r)).astype(np.int32)
+    rho = np.ones(r, np.float32)
     rows = min(r, cores)
     t0 = time.perf_counter()
     ref.compressed_grad(dYh, Xh, idx[:rows], rho[:rows])
@@ -111,7 +114,7 @@ def cpu_baseline(cfg, layer, dY, X, state, W, seconds):
         ref.compressed_grad(dYh, Xh, idx[:rows], rho[:rows])
         t_probe = time.perf_counter() - t0
     t_cgrad_full = t_probe * r / rows
-    GC = state.GC.cpu().numpy().astype(np.float64)
+    GC = rng.standard_normal((r, state.n))
     M = np.zeros_like(GC)
     V = np.zeros_like(GC)
     Wd = W.cpu().to(torch.float64).numpy()

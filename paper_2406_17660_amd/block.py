@@ -91,11 +91,14 @@ class GrassBlock:
         self.t = 0
         self.graph = None
 
-    def refresh(self, dY, X):
-        """compute_P (+ update_state) for every layer.  dY: {name: tensor}, X: {group: tensor}."""
+    def refresh(self, dY, X, statistics=None):
+        """compute_P (+ update_state) for every layer.  dY: {name: tensor}, X: {group: tensor};
+        statistics: optional {name: fp32 device array} of row statistics to select from in
+        place of a layer's own (see GrassLayer.refresh)."""
         for g in self.groups:
             for name in g:
-                self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state)
+                self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state,
+                                          statistic=(statistics or {}).get(name))
 
     def _step_group(self, g, dY, X, W, lr, step_scalars=None):
         """One library call for the group: grouped G_C, Adam and the row updates."""
@@ -132,10 +135,10 @@ class GrassBlock:
                 joined.record(side)
             main.wait_event(joined)
 
-    def train_step(self, dY, X, W, schedule: RewarmSchedule):
+    def train_step(self, dY, X, W, schedule: RewarmSchedule, statistics=None):
         """Step t of Algorithm 1 under `schedule`: refresh when t = 0 mod K, then update."""
         if schedule.is_refresh(self.t):
-            self.refresh(dY, X)
+            self.refresh(dY, X, statistics)
         if self.graph is not None:
             self.replay(schedule.lr(self.t))
         else:

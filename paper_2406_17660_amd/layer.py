@@ -97,8 +97,15 @@ class GrassLayer:
                 self.T, self.m, self.n, self.dt, self.layout, ldy, ldx), X.device)
         return grass.grad_row_stats(dY, X, self.sumsq, self.ws_stats, self.layout)
 
-    def refresh(self, dY, X, reset_state=True):
-        self.row_statistic(dY, X)
+    def refresh(self, dY, X, reset_state=True, statistic=None):
+        """compute_P and update_state.  `statistic`: an fp32 device array of m squared row norms
+        to select from in place of this layer's own (one that was reduced elsewhere, say summed
+        over data-parallel workers); dY and X are then not read."""
+        if statistic is None:
+            self.row_statistic(dY, X)
+        else:
+            assert statistic.dtype == torch.float32 and tuple(statistic.shape) == (self.m,)
+            self.sumsq.copy_(statistic)
         grass.select_rows(self.sumsq, self.r, self.method, self.replacement, self.scale, self.seed,
                           self.refresh_id, self.idx, self.rho, self.ws_sel)
         self.refresh_id += 1

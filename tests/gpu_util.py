@@ -68,3 +68,19 @@ def gpu_dense(dY, X, gdtype, layout=grass.DY_TxM):
     ws = grass.workspace(grass.dense_workspace(T, m, n, dt, layout))
     grass.dense_grad(dY, X, G, ws, layout)
     return G
+
+
+def check_own_selection(idx, ref_ss, r, method, replacement):
+    """What must hold for rows the GPU selected from its OWN statistic, which equals the oracle's
+    `ref_ss` only up to fp32 rounding (so a near-tie may legitimately be decided differently):
+    r rows, ascending, in range, distinct unless drawn with replacement, and for Top-r no
+    unselected row clearly above a selected one."""
+    idx = np.asarray(idx)
+    m = len(ref_ss)
+    assert idx.shape == (r,) and (np.diff(idx) >= 0).all()
+    assert r == 0 or (idx.min() >= 0 and idx.max() < m)
+    if method == grass.SEL_TOPR or not replacement:
+        assert len(np.unique(idx)) == r
+    if method == grass.SEL_TOPR and 0 < r < m:
+        rest = np.setdiff1d(np.arange(m), idx)
+        assert ref_ss[idx].min() >= ref_ss[rest].max() * (1 - 1e-5)

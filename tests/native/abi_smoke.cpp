@@ -110,10 +110,20 @@ int main() {
     hipStream_t s;
     HIP_OK(hipStreamCreate(&s));
 
+    // The oracle's statistic first: nothing the GPU computes goes into the oracle, so the rows
+    // are selected, on both sides, from the oracle's statistic rounded once to fp32.
+    std::vector<double> G(m * n), ss_ref(m);
+    if (grass_ref_full_grad(dY.data(), 0, m, X.data(), n, 1, T, m, n, G.data()) != 0) return 4;
+    if (grass_ref_row_stats(G.data(), 2, m, n, n, ss_ref.data()) != 0) return 4;
+    std::vector<float> ss32(ss_ref.begin(), ss_ref.end());
+    float* d_ss32 = nullptr;
+    HIP_OK(hipMalloc(&d_ss32, m * 4));
+    HIP_OK(hipMemcpy(d_ss32, ss32.data(), m * 4, hipMemcpyHostToDevice));
+
     // refresh: row statistic of G (G itself is never stored), then selection without replacement
     GRASS_OK_OR_FAIL(grass_grad_row_stats(d_dY, GRASS_DY_TxM, m, d_X, n, GRASS_BF16, T, m, n, d_ss,
                                           d_ws_stat, b_stat, s));
-    GRASS_OK_OR_FAIL(grass_select_rows(d_ss, m, r, GRASS_SEL_MULTI_NORM, 0, GRASS_SCALE_PAPER, 77, 0,
+    GRASS_OK_OR_FAIL(grass_select_rows(d_ss32, m, r, GRASS_SEL_MULTI_NORM, 0, GRASS_SCALE_PAPER, 77, 0,
                                        d_idx, d_rho, d_ws_sel, b_sel, s));
     // regular step
     GRASS_OK_OR_FAIL(grass_compressed_grad(d_dY, GRASS_DY_TxM, m, d_X, n, GRASS_BF16, T, m, n, r,
@@ -141,34 +151,29 @@ int main() {
         if (!ok) ++failures;
     };
     check(sel_status == GRASS_OK, "selection status word", sel_status);
-    // oracle, fed with the same bits
-    std::vector<double> G(m * n), ss_ref(m);
-    if (grass_ref_full_grad(dY.data(), 0, m, X.data(), n, 1, T, m, n, G.data()) != 0) return 4;
-    if (grass_ref_row_stats(G.data(), 2, m, n, n, ss_ref.data()) != 0) return 4;
     check(rel_fro(std::vector<double>(ss.begin(), ss.end()), ss_ref) <= 1e-5, "row statistic", 0);
     std::vector<int32_t> idx_ref(r);
     std::vector<float> rho_ref(r);
-    if (grass_ref_select_rows(ss.data(), m, r, 2, 0, 0, 77, 0, idx_ref.data(), rho_ref.data(), nullptr) != 0)
+    if (grass_ref_select_rows(ss32.data(), m, r, 2, 0, 0, 77, 0, idx_ref.data(), rho_ref.data(), nullptr) != 0)
         return 4;
     check(idx == idx_ref && rho == rho_ref, "selected rows and scales, bit-exact", r);
     std::vector<double> GC_ref(r * n), Mr(r * n, 0.0), Vr(r * n, 0.0), U(r * n), Wr(m * n);
-    if (grass_ref_compressed_grad(dY.data(), 0, m, X.data(), n, 1, T, m, n, r, idx.data(), rho.data(),
-                                  GC_ref.data()) != 0)
+    if (grass_ref_compressed_grad(dY.data(), 0, m, X.data(), n, 1, T, m, n, r, idx_ref.data(),
+                                  rho_ref.data(), GC_ref.data()) != 0)
         return 4;
     const double e_gc = rel_fro(std::vector<double>(GC.begin(), GC.end()), GC_ref);
     check(e_gc <= 2e-5, "compressed gradient", e_gc);
-    std::vector<double> GCd(GC.begin(), GC.end());  // Adam is fed what the GPU produced
-    if (grass_ref_adam_rows(GCd.data(), n, Mr.data(), Vr.data(), r, n, lr, b1, b2, eps, 1, U.data()) != 0)
+    if (grass_ref_adam_rows(GC_ref.data(), n, Mr.data(), Vr.data(), r, n, lr, b1, b2, eps, 1, U.data()) != 0)
         return 4;
     for (int64_t i = 0; i < m * n; ++i) Wr[i] = from_bf16(W[i]);
-    if (grass_ref_scatter_update(Wr.data(), m, n, n, idx.data(), rho.data(), alpha, U.data(), r) != 0)
+    if (grass_ref_scatter_update(Wr.data(), m, n, n, idx_ref.data(), rho_ref.data(), alpha, U.data(), r) != 0)
         return 4;
     check(rel_fro(std::vector<double>(M.begin(), M.end()), Mr) <= 1e-5, "first moment", 0);
     check(rel_fro(std::vector<double>(V.begin(), V.end()), Vr) <= 1e-5, "second moment", 0);
     std::vector<double> Wsel_got, Wsel_want;
     bool untouched_same = true;
     std::vector<char> selected(m, 0);
-    for (int32_t k : idx) selected[k] = 1;
+    for (int32_t k : idx_ref) selected[k] = 1;
     for (int64_t k = 0; k < m; ++k)
         for (int64_t i = 0; i < n; ++i) {
             if (selected[k]) {

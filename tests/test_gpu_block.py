@@ -10,7 +10,7 @@ from oracle import ref
 from paper_2406_17660_amd import grass
 from paper_2406_17660_amd.block import GrassBlock, RewarmSchedule
 from paper_2406_17660_amd.layer import AdamHyper
-from gpu_util import DEV, TOL_BF16, rel_fro, to_f64, to_np
+from gpu_util import DEV, TOL_BF16, TOL_F32, check_own_selection, gpu_select, rel_fro, to_f64, to_np
 from test_gpu_steps import OracleLayer, REF_METHOD
 
 pytestmark = pytest.mark.gpu
@@ -49,14 +49,31 @@ def test_block_training_steps_match_layerwise_oracle(method, replacement, reset,
         dY = {name: draw((T, s[0]), 2000 + 10 * t + i, 0.1) for i, (name, s) in enumerate(shapes.items())}
         refreshed = sched.is_refresh(t)
         dY_dev = dY if layout == grass.DY_TxM else {k: v.t().contiguous() for k, v in dY.items()}
-        blk.train_step(dY_dev, X, W, sched)
+        stats = None
+        if refreshed:
+            # The GPU's own statistics are compared with the oracle's; the rows are then selected,
+            # on both sides, from the oracle's statistics rounded once to fp32.
+            stats, ref_ss = {}, {}
+            for g in blk.groups:
+                Xh = to_np(X[g])
+                for name in g:
+                    L = blk.layers[name]
+                    ref_ss[name] = ref.row_stats(ref.full_grad(to_np(dY[name]), Xh))
+                    L.row_statistic(dY_dev[name], X[g])
+                    assert rel_fro(L.sumsq.cpu().numpy(), ref_ss[name]) <= TOL_F32, (name, t)
+                    own, _, status = gpu_select(L.sumsq, L.r, L.method, L.replacement, L.scale,
+                                                L.seed, L.refresh_id)
+                    assert status == grass.OK
+                    check_own_selection(own.cpu().numpy(), ref_ss[name], L.r, L.method, L.replacement)
+                    stats[name] = torch.from_numpy(ref_ss[name].astype(np.float32)).to(DEV)
+        blk.train_step(dY_dev, X, W, sched, statistics=stats)
         lr = sched.lr(t)
         for g in blk.groups:
             Xh = to_np(X[g])
             for name in g:
                 L, o = blk.layers[name], orc[name]
-                if refreshed:  # the oracle's compute_P on the statistics the GPU produced
-                    o.refresh(L.sumsq.cpu().numpy(), reset=reset)
+                if refreshed:
+                    o.refresh(ref_ss[name].astype(np.float32), reset=reset)
                     assert grass.select_status(L.ws_sel) == grass.OK
                     assert np.array_equal(L.idx.cpu().numpy(), o.idx), (name, t)
                     assert np.array_equal(L.rho.cpu().numpy(), o.rho)
