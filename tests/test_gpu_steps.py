@@ -90,9 +90,9 @@ def run_config(cfg, layer, T, steps, refresh_every, method=None, replacement=Non
             gpu_ss = st.sumsq.cpu().numpy()
             if materialise_G:
                 assert rel_fro(to_f64(st.G), G) <= (TOL_BF16 if st.G.dtype == torch.bfloat16 else 2e-5)
-                assert rel_fro(gpu_ss, ref_ss) <= tol
-                # the statistic of the matrix the GPU actually stored: fp32-accumulation accuracy
-                assert rel_fro(gpu_ss, ref.row_stats(to_np(st.G))) <= TOL_F32
+                # of a G rounded to its stored type: the rounding errors (2^-9 relative, mean
+                # zero) average out over the n squares of a row
+                assert rel_fro(gpu_ss, ref_ss) <= min(tol, 1e-3)
             else:  # squares taken from the fp32 accumulators: G is never rounded to bf16
                 assert st.G is None
                 assert rel_fro(gpu_ss, ref_ss) <= TOL_F32
@@ -221,7 +221,6 @@ def test_config5_full_size_sampled(layer):
     if stored:
         assert rel_fro(to_f64(st.G[torch.from_numpy(rows).to(DEV)]), G_rows) <= TOL_BF16
         assert rel_fro(gpu_ss[rows], ref.row_stats(G_rows)) <= TOL_BF16
-        assert rel_fro(gpu_ss, ref.row_stats(to_np(st.G))) <= TOL_F32
     else:
         assert st.G is None
         assert rel_fro(gpu_ss[rows], ref.row_stats(G_rows)) <= TOL_F32
