@@ -37,7 +37,8 @@ def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=200)
-    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--warmup", type=int, default=50,
+                   help="untimed steps first: the chip needs some tens of launches after an idle period to settle at its sustained clock")
     p.add_argument("--config", type=int, default=5)
     p.add_argument("--layer", type=int, default=0, help="index into the config's layer list")
     p.add_argument("--tokens", type=int, default=None, help="override T (debug)")
