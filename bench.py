@@ -277,11 +277,25 @@ def main():
     }
 
     if not args.no_extras:
-        # context for the fraction above: what a kernel of nothing but this matrix instruction
-        # sustains on this very machine (its clock under that load varies from box to box)
-        probe = grass.probe_mfma_rate()
+        # Context for the fraction above: what kernels of nothing but this matrix instruction
+        # sustain on this very machine.  The clock under that load depends on the box and on what
+        # the instructions are fed: constants; values distributed like the GEMM's inputs (dY-like
+        # on the left, X-like on the right) held in registers; the same values read from LDS
+        # fragment by fragment as the GEMM reads its operands (no global memory traffic).
+        g = torch.Generator(device=dev)
+        g.manual_seed(workloads.BASE_SEED + 99)
+        vals = torch.randn(32768, generator=g, device=dev)
+        left = (torch.arange(32768, device=dev) // 2048) % 8 < 4
+        vals = torch.where(left, vals * 0.1, vals).to(torch.bfloat16)
+        probe = grass.probe_mfma_rate(source=grass.PROBE_CONSTANTS)
+        probe_regs = grass.probe_mfma_rate(source=grass.PROBE_REGISTERS, operands=vals)
+        probe_lds = grass.probe_mfma_rate(source=grass.PROBE_LDS, operands=vals)
         out["roofline"]["mfma_only_kernel_tflops_this_box"] = probe
+        out["roofline"]["mfma_only_kernel_normal_operands_tflops"] = probe_regs
+        out["roofline"]["mfma_plus_lds_reads_kernel_normal_operands_tflops"] = probe_lds
         out["roofline"]["frac_of_mfma_only_kernel"] = gemm_tflops / probe
+        out["roofline"]["frac_of_mfma_only_kernel_normal_operands"] = gemm_tflops / probe_regs
+        out["roofline"]["frac_of_mfma_plus_lds_reads_kernel"] = gemm_tflops / probe_lds
 
     if not args.no_extras and args.side == "rows" and args.layout == "txm":
         detail = {}

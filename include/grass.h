@@ -340,15 +340,31 @@ grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* 
 /* ---------------------------------------------------------------------------
  * Measurement aid (not a step of the method; for benchmarks that want to state what the
  * matrix cores of the machine at hand sustain).  Launches a kernel that does nothing but
- * issue the bf16 matrix instruction of the compressed-gradient GEMM on every compute unit
- * (non-zero operands in registers, no memory traffic): 256 workgroups x 4 wavefronts x
- * `iters` x 16 instructions.  `out` (device, at least 65536 floats, `out_floats` says how
- * many) receives one value per thread so that the work cannot be optimised away; `*flops`
- * (host) receives the number of floating-point operations the launch performs.  The caller
- * times the launch on `stream`.
- * Errors: NULL, SHAPE (iters < 1, out too small). */
-grass_status grass_probe_mfma_rate(float* out, size_t out_floats, int iters, double* flops,
-                                   void* stream);
+ * issue the bf16 matrix instruction of the compressed-gradient GEMM on every compute unit:
+ * 256 workgroups x 4 wavefronts x `iters` x 32 instructions, no global memory traffic inside
+ * the loop.  The clock the chip sustains under this load depends on what the instructions
+ * are fed, hence three operand sources:
+ *   GRASS_PROBE_CONSTANTS  small constants held in registers (`operands` is not read);
+ *   GRASS_PROBE_REGISTERS  the caller's values, two sets of eight fragments held in
+ *                          registers and used alternately;
+ *   GRASS_PROBE_LDS        the caller's values staged in LDS once; every group of 16
+ *                          instructions reads its eight fragments from there (16 bytes per
+ *                          lane and fragment: the LDS read traffic of the GEMM).
+ * `operands` (device, 16-byte aligned, at least 65536 bytes, `operand_bytes` says how many):
+ * bf16 values; thread t of a workgroup takes elements [(256 f + t) 8, +8) as fragment f = 0..15,
+ * fragments 0-3 and 8-11 on the left side of the products, 4-7 and 12-15 on the right.
+ * `out` (device, at least 65536 floats, `out_floats` says how many) receives one value per
+ * thread so that the work cannot be optimised away; `*flops` (host) receives the number of
+ * floating-point operations the launch performs.  The caller times the launch on `stream`.
+ * Errors: NULL, DTYPE (unknown source), SHAPE (iters < 1, a buffer too small or misaligned). */
+typedef enum {
+    GRASS_PROBE_CONSTANTS = 0,
+    GRASS_PROBE_REGISTERS = 1,
+    GRASS_PROBE_LDS = 2
+} grass_probe_source;
+grass_status grass_probe_mfma_rate(grass_probe_source source, const void* operands,
+                                   size_t operand_bytes, float* out, size_t out_floats, int iters,
+                                   double* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -358,13 +358,20 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
     return launch_gather_rows(G, gdt, n, ldg, idx, rho, r, out, ldo, as_stream(stream));
 }
 
-grass_status grass_probe_mfma_rate(float* out, size_t out_floats, int iters, double* flops,
-                                   void* stream) {
+grass_status grass_probe_mfma_rate(grass_probe_source source, const void* operands,
+                                   size_t operand_bytes, float* out, size_t out_floats, int iters,
+                                   double* flops, void* stream) {
     if (!out || !flops) return GRASS_ERR_NULL;
+    if (source < GRASS_PROBE_CONSTANTS || source > GRASS_PROBE_LDS) return GRASS_ERR_DTYPE;
+    if (source != GRASS_PROBE_CONSTANTS) {
+        if (!operands) return GRASS_ERR_NULL;
+        if (operand_bytes < static_cast<size_t>(kProbeOperandBytes) || !aligned_to(operands, 16))
+            return GRASS_ERR_SHAPE;
+    }
     if (iters < 1 || out_floats < static_cast<size_t>(kProbeWorkgroups) * 256) return GRASS_ERR_SHAPE;
-    // 4 wavefronts per workgroup, 16 instructions of 32 x 32 x 16 multiply-adds per iteration
-    *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
-    return launch_probe_mfma_rate(out, iters, as_stream(stream));
+    // 4 wavefronts per workgroup, 32 instructions of 32 x 32 x 16 multiply-adds per iteration
+    *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * iters * 32.0 * (2.0 * 32 * 32 * 16);
+    return launch_probe_mfma_rate(static_cast<int>(source), operands, out, iters, as_stream(stream));
 }
 
 }  // extern "C"

@@ -109,9 +109,12 @@ grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy,
                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // Measurement aid: kProbeWorkgroups workgroups of 256 threads, each wavefront issuing
-// 16 * iters matrix instructions; `out` takes kProbeWorkgroups * 256 floats.
+// 32 * iters matrix instructions; `out` takes kProbeWorkgroups * 256 floats; `operands` (sources
+// 1 and 2) holds kProbeOperandBytes of bf16 values.
 constexpr int kProbeWorkgroups = 256;
-grass_status launch_probe_mfma_rate(float* out, int iters, hipStream_t s);
+constexpr int kProbeOperandBytes = 65536;
+grass_status launch_probe_mfma_rate(int source, const void* operands, float* out, int iters,
+                                    hipStream_t s);
 
 // What follows the compressed gradient in a regular step (Adam on r x n, update of the rows of
 // W).  Given to the GEMM launcher, the split-K reduction, Adam and the update run as one kernel

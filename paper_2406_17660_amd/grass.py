@@ -94,7 +94,7 @@ def lib():
     L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
     L.grass_grad_row_stats_workspace.restype = sz
     L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
-    L.grass_probe_mfma_rate.argtypes = [vp, sz, i32, C.POINTER(C.c_double), vp]
+    L.grass_probe_mfma_rate.argtypes = [i32, vp, sz, vp, sz, i32, C.POINTER(C.c_double), vp]
     L.grass_cgrad_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
     L.grass_cgrad_group_workspace.restype = sz
     L.grass_compressed_grad_group.argtypes = [i32, vp, i32, vp, vp, i64, i32, i64, vp, i64, vp,
@@ -416,16 +416,25 @@ def workspace(nbytes: int, device="cuda"):
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
 
-def probe_mfma_rate(iters=20000):
+PROBE_CONSTANTS, PROBE_REGISTERS, PROBE_LDS = 0, 1, 2
+
+
+def probe_mfma_rate(iters=10000, source=PROBE_CONSTANTS, operands=None):
     """TFLOP/s of a kernel that only issues the GEMM's bf16 matrix instruction on every compute
-    unit (measurement aid: what the matrix cores of this machine sustain under that load)."""
+    unit (measurement aid: what the matrix cores of this machine sustain under that load).
+    `operands`: at least 32768 bf16 values on the device for the sources that take the caller's
+    values (held in registers, or read from LDS like the GEMM's operand fragments)."""
     out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
     flops = C.c_double(0.0)
+    ptr, nbytes = (None, 0) if operands is None else (C.c_void_p(operands.data_ptr()),
+                                                      operands.numel() * operands.element_size())
 
     def launch():
-        _check(lib().grass_probe_mfma_rate(C.c_void_p(out.data_ptr()), out.numel(), iters,
-                                           C.byref(flops), _stream()), "grass_probe_mfma_rate")
-    launch()
+        _check(lib().grass_probe_mfma_rate(source, ptr, nbytes, C.c_void_p(out.data_ptr()),
+                                           out.numel(), iters, C.byref(flops), _stream()),
+               "grass_probe_mfma_rate")
+    for _ in range(3):  # the clock settles over the first launches
+        launch()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     launch()

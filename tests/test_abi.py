@@ -265,10 +265,20 @@ def test_probe_validation():
     import ctypes as C
     f = grass.lib().grass_probe_mfma_rate
     flops = C.c_double(0.0)
-    assert f(None, 1 << 16, 10, C.byref(flops), None) == grass.ERR_NULL
-    assert f(FAKE, 1 << 16, 10, None, None) == grass.ERR_NULL
-    assert f(FAKE, 1 << 16, 0, C.byref(flops), None) == grass.ERR_SHAPE
-    assert f(FAKE, 1000, 10, C.byref(flops), None) == grass.ERR_SHAPE
+    ok = (0, None, 0, FAKE, 1 << 16, 10, C.byref(flops), None)
+
+    def call(**kw):
+        names = ("source", "operands", "operand_bytes", "out", "out_floats", "iters", "flops", "stream")
+        return f(*[kw.get(n, v) for n, v in zip(names, ok)])
+    assert call(out=None) == grass.ERR_NULL
+    assert call(flops=None) == grass.ERR_NULL
+    assert call(iters=0) == grass.ERR_SHAPE
+    assert call(out_floats=1000) == grass.ERR_SHAPE
+    assert call(source=3) == grass.ERR_DTYPE
+    for source in (grass.PROBE_REGISTERS, grass.PROBE_LDS):  # these read the caller's values
+        assert call(source=source) == grass.ERR_NULL
+        assert call(source=source, operands=FAKE, operand_bytes=65535) == grass.ERR_SHAPE
+        assert call(source=source, operands=C.c_void_p(FAKE.value + 2), operand_bytes=65536) == grass.ERR_SHAPE
 
 
 def test_grad_row_stats_validation():

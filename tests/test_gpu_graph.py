@@ -55,7 +55,13 @@ def test_step_replayed_from_a_graph_equals_eager_step(layout, T, m, n, r):
             assert torch.equal(a, b), f"replay {replay} differs from the eager step"
 
 
-def test_matrix_core_probe_reports_a_plausible_rate():
-    """The measurement aid runs and lands between a tenth of and just above the datasheet peak."""
-    rate = grass.probe_mfma_rate(iters=2000)
-    assert 250.0 < rate < 2600.0
+def test_matrix_core_probe_reports_plausible_rates():
+    """The measurement aid runs with each operand source and lands between a tenth of and just
+    above the datasheet peak; random operands cannot be faster than constants by much."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    operands = torch.randn(32768, generator=g, device="cuda").to(torch.bfloat16)
+    rates = [grass.probe_mfma_rate(2000, source, operands)
+             for source in (grass.PROBE_CONSTANTS, grass.PROBE_REGISTERS, grass.PROBE_LDS)]
+    assert all(250.0 < r < 2600.0 for r in rates), rates
+    assert rates[1] < 1.1 * rates[0] and rates[2] < 1.1 * rates[0], rates
