@@ -206,11 +206,16 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
 #pragma unroll
         for (int part = 0; part < 4; ++part) read_quarter(f, i, k16, part);
     };
-    // Row `a` of the 4 x 4 fragment products of a slice.
+    // Row `a` of the 4 x 4 fragment products of a slice.  Odd rows run through the columns
+    // backwards, so that only one operand changes from the last instruction of a row to the
+    // first of the next (fewer operand switches: measured 0.5 % faster; the kernel is bound
+    // by power).
     auto mfma_row = [&](const Frags& f, int a) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int bb = 0; bb < 4; ++bb) {
+            const int b = (a & 1) ? 3 - bb : bb;
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
+        }
     };
     auto mfma16 = [&](const Frags& f) {
 #pragma unroll
