@@ -278,6 +278,19 @@ def test_config5_full_size_sampled(layer):
     assert np.array_equal(to_np(W)[rest], W0_bits[rest])
     assert not np.array_equal(to_np(W)[sel], W0_bits[sel])
 
+    # bench.py's own launch configuration: the one-call step that never writes G_C.  Same
+    # kernels minus one store, so state and weights must equal the run above bit for bit.
+    st2 = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
+                     seed=workloads.BASE_SEED, store_GC=False)
+    W2 = workloads.make_W(cfg, layer, DEV)
+    st2.GC.fill_(float("nan"))
+    st2.refresh(dY, X, statistic=torch.from_numpy(ss).to(DEV))
+    st2.step(dY, X, W2)
+    assert torch.equal(st2.idx, st.idx) and torch.equal(st2.rho, st.rho)
+    assert torch.equal(st2.M, st.M) and torch.equal(st2.V, st.V) and torch.equal(W2, W)
+    assert bool(torch.isnan(st2.GC).all())  # and G_C was indeed not stored
+    del st2, W2
+
     # Adam and the row update in full at this size, on a seeded compressed gradient
     g = torch.Generator(device=DEV)
     g.manual_seed(workloads.BASE_SEED + 77 + layer)
