@@ -868,3 +868,23 @@ def test_compressed_grad_millions_of_tokens(layout, T):
     got = to_f64(gpu_cgrad(dY_dev, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV), layout))
     want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
     assert rel_fro(got, want) <= 2e-5
+
+
+@pytest.mark.parametrize("T,m,n,r,dup,pad,shift", [
+    (257, 2048, 64, 512, False, 0, 0),     # smallest shape that takes the staged gather; odd T
+    (130, 5464, 72, 600, True, 8, 0),      # row length not a power of two, padded rows, duplicates
+    (66, 16384, 64, 1500, True, 0, 0),     # the longest rows two of which fit the staging buffer
+    (65, 16392, 64, 700, False, 0, 0),     # one step longer: the plain gather
+    (96, 4096, 128, 1024, False, 8, 1),    # rows that are not 16-byte aligned: the plain gather
+    (1, 4096, 64, 512, False, 0, 0),       # a single row of t
+])
+def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
+    """Wide T x m gradients: the gather copies whole rows of dY into LDS first.  Shapes on both
+    sides of every condition of that route (width, row length, alignment), against the oracle."""
+    buf = randn((T, m + pad + shift), torch.bfloat16, 191, scale=0.1)
+    dY = buf[:, shift:shift + m]
+    X = randn((T, n), torch.bfloat16, 192)
+    idx, rho = make_idx(m, r, 193, dup)
+    got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
+    want = ref.compressed_grad(np.ascontiguousarray(to_np(dY)), to_np(X), idx, rho)
+    assert rel_fro(got, want) <= 2e-5
