@@ -328,15 +328,19 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             const int64_t width = i + 1 == count ? p.rp - off : (seg[i].rows + 7) / 8 * 8;
             if (width > 0) {
                 const int64_t m_src = seg[i].src_rows;  // row length of this set's dY
-                if (layout == GRASS_DY_TxM && m_src >= 2048 && width >= 512 && m_src % 8 == 0 &&
-                    seg[i].ldy % 8 == 0 && aligned_to(seg[i].dY, 16) &&
-                    m_src * 2 * kPackStageRows <= kPackStageMaxBytes &&
-                    (T + kPackStageRows - 1) / kPackStageRows <= 0x7FFFFFFF) {
+                if (layout == GRASS_DY_TxM && m_src >= 2048 && m_src <= kPackStageMaxM &&
+                    width >= 512 && m_src % 8 == 0 && seg[i].ldy % 8 == 0 &&
+                    aligned_to(seg[i].dY, 16)) {
                     // wide rows: staged through LDS (streaming loads of whole rows)
-                    pack_txm_staged_kernel<<<static_cast<unsigned>((T + kPackStageRows - 1) / kPackStageRows),
-                                             256, static_cast<size_t>(m_src) * 2 * kPackStageRows, s>>>(
-                        static_cast<const uint16_t*>(seg[i].dY), seg[i].ldy, T, m_src, seg[i].idx,
-                        seg[i].rows, width, p.rp, panel + off);
+                    const auto* src = static_cast<const uint16_t*>(seg[i].dY);
+                    if (m_src <= kPackStageTwoRowsMaxM)
+                        pack_txm_staged_kernel<2><<<static_cast<unsigned>((T + 1) / 2), 256,
+                                                    static_cast<size_t>(m_src) * 4, s>>>(
+                            src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
+                    else
+                        pack_txm_staged_kernel<1><<<static_cast<unsigned>(T), 256,
+                                                    static_cast<size_t>(m_src) * 2, s>>>(
+                            src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                 } else if (layout == GRASS_DY_TxM) {
                     int tpr_log2 = 8;  // threads per row of t: the power of two covering width / 4
                     while (tpr_log2 > 0 && (int64_t{4} << (tpr_log2 - 1)) >= width) --tpr_log2;

@@ -51,26 +51,28 @@ __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restric
 // from LDS and stores the panel rows with streaming 8-byte stores.  Measured at the 7B layer
 // against the kernel above: 0.21 instead of 0.24 ms (1.34 GB at 6.3 TB/s); one row per
 // workgroup is slower than the kernel above, two to eight rows differ little.
-// Needs m % 8 == 0, 16-byte aligned rows of dY, and kPackStageRows * m * 2 bytes of LDS.
-constexpr int kPackStageRows = 2;
-constexpr int64_t kPackStageMaxBytes = 65536;
+// Needs m % 8 == 0, 16-byte aligned rows of dY, and kRows * m * 2 bytes of LDS.  Two rows per
+// workgroup while three workgroups still fit a compute unit's LDS (m <= 12288), one row beyond
+// (at m = 13824 two rows, 55 KB, leave two workgroups per compute unit and lose to the kernel above).
+constexpr int64_t kPackStageTwoRowsMaxM = 12288, kPackStageMaxM = 32768;
+template <int kRows>
 __global__ __launch_bounds__(256) void pack_txm_staged_kernel(const uint16_t* __restrict__ dY,
                                                               int64_t ldy, int64_t T, int64_t m,
                                                               const int32_t* __restrict__ idx,
                                                               int64_t r, int64_t rp, int64_t ldo,
                                                               uint16_t* __restrict__ out) {
-    extern __shared__ __attribute__((aligned(16))) uint16_t stage[];  // kPackStageRows x m
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kPackStageRows;
+    extern __shared__ __attribute__((aligned(16))) uint16_t stage[];  // kRows x m
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kRows;
     const int vec_per_row = static_cast<int>(m / 8);
     for (int c = threadIdx.x; c < vec_per_row; c += 256) {
-        s16x8 x[kPackStageRows];
+        s16x8 x[kRows];
 #pragma unroll
-        for (int row = 0; row < kPackStageRows; ++row) {
+        for (int row = 0; row < kRows; ++row) {
             const int64_t t = t0 + row < T ? t0 + row : T - 1;  // a row past the end is not used
             x[row] = __builtin_nontemporal_load(reinterpret_cast<const s16x8*>(dY + t * ldy) + c);
         }
 #pragma unroll
-        for (int row = 0; row < kPackStageRows; ++row)
+        for (int row = 0; row < kRows; ++row)
             *reinterpret_cast<s16x8*>(stage + static_cast<int64_t>(row) * m + c * 8) = x[row];
     }
     __syncthreads();
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void pack_txm_staged_kernel(const uint16_t* __
         for (int e = 0; e < 4; ++e)
             col[e] = j0 + e < r ? (idx ? idx[j0 + e] : static_cast<int32_t>(j0 + e)) : -1;
 #pragma unroll
-        for (int row = 0; row < kPackStageRows; ++row) {
+        for (int row = 0; row < kRows; ++row) {
             if (t0 + row >= T) break;
             const uint16_t* src = stage + static_cast<int64_t>(row) * m;
             uint16_t v[4];

@@ -873,8 +873,10 @@ def test_compressed_grad_millions_of_tokens(layout, T):
 @pytest.mark.parametrize("T,m,n,r,dup,pad,shift", [
     (257, 2048, 64, 512, False, 0, 0),     # smallest shape that takes the staged gather; odd T
     (130, 5464, 72, 600, True, 8, 0),      # row length not a power of two, padded rows, duplicates
-    (66, 16384, 64, 1500, True, 0, 0),     # the longest rows two of which fit the staging buffer
-    (65, 16392, 64, 700, False, 0, 0),     # one step longer: the plain gather
+    (67, 12288, 64, 1500, True, 0, 0),     # the longest rows staged two at a time
+    (65, 12296, 64, 700, False, 0, 0),     # one step longer: one row per workgroup
+    (34, 32768, 64, 900, True, 0, 0),      # the longest rows that are staged at all
+    (33, 32776, 64, 600, False, 0, 0),     # one step longer: the plain gather
     (96, 4096, 128, 1024, False, 8, 1),    # rows that are not 16-byte aligned: the plain gather
     (1, 4096, 64, 512, False, 0, 0),       # a single row of t
 ])
