@@ -39,7 +39,8 @@ def parse():
     p.add_argument("--steps", type=int, default=200)
     p.add_argument("--warmup", type=int, default=50,
                    help="untimed steps first: the chip needs some tens of launches after an idle period to settle at its sustained clock")
-    p.add_argument("--config", type=int, default=5)
+    p.add_argument("--config", type=int, default=None,
+                   help="workload configuration 1-5 (default: 5, or the one a --block belongs to)")
     p.add_argument("--layer", type=int, default=0, help="index into the config's layer list")
     p.add_argument("--tokens", type=int, default=None, help="override T (debug)")
     p.add_argument("--side", choices=["rows", "cols"], default="rows",
@@ -200,6 +201,8 @@ def main():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
     grass.lib()
+    if args.config is None:  # a block brings its model's token batch, rank and selection rule
+        args.config = {"60m": 2, "350m": 3, "1b": 4}.get(args.block, 5)
     cfg = workloads.CONFIGS[args.config]
     if args.block:
         return bench_block(args, cfg)
