@@ -304,12 +304,19 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     if (tile == kTile256 && layout == GRASS_DY_MxT && count == 1 && T % kFastBK == 0 &&
         aligned_to(dY0, 16) && ldy0 % 8 == 0 && getenv("GRASS_GEMM_PACK_MXT") == nullptr) {
         const int64_t src_rows = seg[0].idx ? seg[0].src_rows : total;
-        a_rows_form = src_rows > 0 && src_rows * ldy0 * 2 + 64 < (int64_t{1} << 32);
+        a_rows_form = src_rows > 0 && src_rows * ldy0 * 2 + 128 < (int64_t{1} << 32);
     }
     if (a_rows_form) pack = false;
+    // whole cache lines per row (64 values of k per load) when the K tiles pair up
+    const bool a_pairs = a_rows_form && T % (2 * kFastBK) == 0 && getenv("GRASS_GEMM_NO_PAIRS") == nullptr;
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
     const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
-    const Plan p = plan_for(tile, T, total, n, pack);  // sized for all T rows; K tiling per tile kind
+    Plan p = plan_for(tile, T, total, n, pack);  // sized for all T rows; K tiling per tile kind
+    if (a_pairs && p.ktiles_per_split % 2 != 0) {  // every workgroup gets whole pairs of K tiles
+        ++p.ktiles_per_split;
+        const int64_t ktiles = T / kFastBK;
+        p.splits = static_cast<int>((ktiles + p.ktiles_per_split - 1) / p.ktiles_per_split);
+    }
     char* base = static_cast<char*>(ws);
     base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
     uint16_t* panel = reinterpret_cast<uint16_t*>(base);
@@ -406,7 +413,9 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     const unsigned grid = static_cast<unsigned>(chunk * kNumXcd);
     hipError_t le;
     if (tile == kTile256) {
-        if (a_rows_form)
+        if (a_pairs)
+            tn_gemm_bf16_direct_kernel<false, false, true, true><<<grid, 256, 0, s>>>(g);
+        else if (a_rows_form)
             tn_gemm_bf16_direct_kernel<false, false, true><<<grid, 256, 0, s>>>(g);
         else if (gathered)
             tn_gemm_bf16_direct_kernel<false><<<grid, 256, 0, s>>>(g);

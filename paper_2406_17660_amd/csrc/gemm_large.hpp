@@ -83,9 +83,18 @@ __device__ __forceinline__ void wait_vmcnt() {
 // wavefront, which read one slot of 16 consecutive rows, cover all 64 banks once) and an MFMA
 // operand is a single 16-byte read per lane: no transposition is needed, the 8 consecutive k
 // a lane feeds to the matrix core are contiguous in the row.
-template <bool kDense, bool kRowStats = false, bool kARows = false>
+//
+// kAPairs (with kARows): the rows of the left operand are fetched 64 values of k at a time, one
+// whole 128-byte cache line per row and request instead of half a line per K tile (half-line
+// requests make the loads of this operand twice as expensive as those of a packed panel).  The
+// four A blocks of the ring then form two blocks of [256 rows][64 k] (128 bytes per row, 16-byte
+// slot c of row j stored at slot c ^ ((j / 2) % 8)), each serving two consecutive K tiles: the
+// pair (i, i+1), i even, is loaded during K tile i-2, right after the pair (i-2, i-1) has been
+// used up.  B keeps its four single stages.  Needs an even number of K tiles per workgroup.
+template <bool kDense, bool kRowStats = false, bool kARows = false, bool kAPairs = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void tn_gemm_bf16_direct_kernel(GemmArgs g) {
+    static_assert(!kAPairs || kARows, "paired A stages are a form of the row-gathering kernel");
     __shared__ __attribute__((aligned(1024))) uint16_t ring[kFastStages * kFastStageElems];
 
     const int64_t items = static_cast<int64_t>(g.tiles_m) * g.tiles_n * g.splits;
@@ -135,6 +144,21 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
         }
         laneB[p] = static_cast<uint32_t>(((p * 8 + lrow) * g.ldb + colB) * 2);
     }
+    // kAPairs: load q (0..7) of this wavefront fills rows 8 (4 q + wave) .. +8 of a pair block,
+    // eight lanes per row; the lane that fills physical slot p of row j fetches logical slot
+    // p ^ ((j / 2) % 8) of the 64 values of k.
+    uint32_t lanePair[kAPairs ? 8 : 1];
+    if (kAPairs) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int trow = 8 * (4 * q + wave) + (lane >> 3);
+            int64_t j = m0 + trow;
+            if (j >= g.Mcols) j = 0;
+            const int64_t src = g.a_rows ? g.a_rows[j] : j;
+            const int lslot = (lane & 7) ^ ((trow >> 1) & 7);
+            lanePair[q] = static_cast<uint32_t>((src * g.lda + lslot * 8) * 2);
+        }
+    }
     const int64_t tileA = kARows ? kFastBK : kFastBK * g.lda, tileB = kFastBK * g.ldb;
     const int ldsrow = wave * 2;  // first LDS row this wavefront writes in a pass
 
@@ -144,6 +168,23 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     // wavefronts of a workgroup share one address unit, and eight back-to-back 1 KiB loads
     // from each of them right after a barrier stall the last wavefront's MFMAs.
     const uint32_t ring_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_void_t*)ring));
+    // Element offsets of the A and B blocks of K tile i inside the ring.  Paired form: A pair
+    // blocks at 0 and 32 KiB, the four B stages behind them.
+    auto a_base = [&](int i) -> int {
+        return kAPairs ? ((i >> 1) & 1) * 2 * kFastOperandElems : (i % kFastStages) * kFastStageElems;
+    };
+    auto b_base = [&](int i) -> int {
+        return kAPairs ? (4 + i % kFastStages) * kFastOperandElems
+                       : (i % kFastStages) * kFastStageElems + kFastOperandElems;
+    };
+    // paired form: load q of the pair that starts at K tile i (i even); B loads of K tile i
+    auto issue_pair_part = [&](int i, int q) {
+        load16_to_lds(gA, lanePair[kAPairs ? q : 0],
+                      ring_base + (a_base(i) + (4 * q + wave) * 8 * 64) * 2);
+    };
+    auto issue_b_part = [&](int i, int part) {
+        load16_to_lds(gB, laneB[part], ring_base + (b_base(i) + (ldsrow + part * 8) * 256) * 2);
+    };
     auto issue_part = [&](int i, int part) {
         const uint32_t d = ring_base + ((i % kFastStages) * kFastStageElems + ldsrow * 256) * 2;
         if (part < kFastBK / 8)  // both forms: pass `part` of this wavefront starts 4 KiB further
@@ -168,12 +209,13 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     int offA[4], offB[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if (kARows)  // row wr*128 + 32i + lane%32, slot (k16/8 + lane/32) ^ ((row/4)%4); k16 added later
+        if (kAPairs)  // row * 64 + (slot ^ ((row/2)%8)) * 8, slot = 4 (tile odd) + k16/8 + lane/32
+            offA[i] = (wr * 128 + i * 32 + (lane & 31)) * 64 + ((h ^ (((lane & 31) >> 1) & 7)) * 8);
+        else if (kARows)  // row wr*128 + 32i + lane%32, slot (k16/8 + lane/32) ^ ((row/4)%4); k16 added later
             offA[i] = (wr * 128 + i * 32 + (lane & 31)) * kFastBK + ((h ^ (((lane & 31) >> 2) & 3)) * 8);
         else
             offA[i] = rrow * 256 + ((((wr * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
-        offB[i] = kFastOperandElems + rrow * 256 +
-                  ((((wc * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
+        offB[i] = rrow * 256 + ((((wc * 128 + i * 32) >> 3) ^ swz) + lchunk) * 8 + half;
     }
 
     f32x16 acc[4][4];
@@ -189,14 +231,17 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     // Quarter `part` of the fragment reads of a slice, in the order the MFMAs consume them
     // (a0 b0 | b1 b2 | b3 a1 | a2 a3): two fragments = four transposing LDS reads.
     auto read_a = [&](int i, int k16, int a) -> bf16x8 {
-        if (kARows) {  // slots 2, 3 hold k16 = 16: flipping bit 1 of the slot = element offset ^ 16
-            const uint16_t* sa = ring + (i % kFastStages) * kFastStageElems + (offA[a] ^ k16);
+        if (kARows) {
+            // slots 2, 3 hold k16 = 16: flipping bit 1 of the slot = element offset ^ 16; in the
+            // paired form slots 4-7 hold the odd K tile of the pair: bit 2 of the slot, ^ 32
+            const int flip = kAPairs ? k16 + 32 * (i & 1) : k16;
+            const uint16_t* sa = ring + a_base(i) + (offA[a] ^ flip);
             return *reinterpret_cast<const lds_bf16x8*>((lds_void_t*)sa);
         }
-        return read_frag_swz(ring + (i % kFastStages) * kFastStageElems + k16 * 256 + offA[a]);
+        return read_frag_swz(ring + a_base(i) + k16 * 256 + offA[a]);
     };
     auto read_quarter = [&](Frags& f, int i, int k16, int part) {
-        const uint16_t* st = ring + (i % kFastStages) * kFastStageElems + k16 * 256;
+        const uint16_t* st = ring + b_base(i) + k16 * 256;
         if (part == 0) { f.a[0] = read_a(i, k16, 0); f.b[0] = read_frag_swz(st + offB[0]); }
         else if (part == 1) { f.b[1] = read_frag_swz(st + offB[1]); f.b[2] = read_frag_swz(st + offB[2]); }
         else if (part == 2) { f.b[3] = read_frag_swz(st + offB[3]); f.a[1] = read_a(i, k16, 1); }
@@ -257,7 +302,87 @@ void tn_gemm_bf16_direct_kernel(GemmArgs g) {
     constexpr int kAhead = kFastStages - 1;
     static_assert(kFastBK == 32 && kFastLoadsPerTile == 8, "two k16 slices, eight loads per tile");
     Frags F, G;
-    if (ntiles > 0) {
+    if constexpr (kAPairs) {
+        // Paired A stages (ntiles is even).  Loads in program order:
+        //   before the loop   A pair (0,1) x8, B(0) x4, B(1) x4, B(2) x4
+        //   K tile i even     A pair (i+2, i+3) x8 during its first slice, B(i+3) x4 during its second
+        //   K tile i odd      B(i+3) x4 during its second slice
+        // so before an even tile 8 younger loads may still be in flight (its own pair was issued
+        // two tiles earlier, followed by B x4 twice), before an odd tile 16 (B(i) was followed by
+        // B x4 and a whole even tile's 12).
+        auto slice_pair = [&](const Frags& cur, Frags& next, int next_tile, int next_k16, int kind,
+                              int load_tile) {
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                read_quarter(next, next_tile, next_k16, part);
+                mfma_row(cur, part);
+                interleave_hint4();
+                __builtin_amdgcn_sched_barrier(0);
+                if (kind == 1) {
+                    issue_pair_part(load_tile, 2 * part);
+                    issue_pair_part(load_tile, 2 * part + 1);
+                } else if (kind == 2) {
+                    issue_b_part(load_tile, part);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        auto issue_pair = [&](int i) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) issue_pair_part(i, q);
+            gA += 2 * kFastBK;
+        };
+        auto issue_b = [&](int i) {
+#pragma unroll
+            for (int part = 0; part < 4; ++part) issue_b_part(i, part);
+            gB += tileB;
+        };
+        if (ntiles > 0) {
+            issue_pair(0);
+            const int pre = ntiles < kAhead ? ntiles : kAhead;
+            for (int t = 0; t < pre; ++t) issue_b(t);
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            read_frags(F, 0, 0);
+            if (2 < ntiles) issue_pair(2);
+            if (3 < ntiles) issue_b(3);
+            read_frags(G, 0, 16);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma16(F);
+            __builtin_amdgcn_sched_barrier(0);
+            int i = 1;
+            for (; i + 4 < ntiles; i += 2) {
+                // odd K tile i: its half of the pair arrived with tile i-1
+                wait_vmcnt<16>();
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                slice_pair(G, F, i, 0, 0, 0);
+                slice_pair(F, G, i, 16, 2, i + 3);
+                gB += tileB;
+                // even K tile i+1: the pair (i+1, i+2) and B(i+1)
+                wait_vmcnt<8>();
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                slice_pair(G, F, i + 1, 0, 1, i + 3);
+                slice_pair(F, G, i + 1, 16, 2, i + 4);
+                gA += 2 * kFastBK;
+                gB += tileB;
+            }
+            // drain: everything has been issued (the last even tile of the loop issued the
+            // pair and the B tile that end the K range)
+            for (; i < ntiles; ++i) {
+                wait_vmcnt<0>();
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                slice_pair(G, F, i, 0, 0, 0);
+                slice_pair(F, G, i, 16, 0, 0);
+            }
+            mfma16(G);
+        }
+    } else if (ntiles > 0) {
         const int pre = ntiles < kAhead ? ntiles : kAhead;
         for (int i = 0; i < pre; ++i) issue(i);
         // tile 0: nothing to overlap with yet

@@ -561,11 +561,16 @@ def test_fused_adam_scatter_with_bf16_moments(wdtype, m, n, r, dup):
 
 
 # ------------------------------------------------------------------------------ dY stored m x T
-@pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 224, 1056])
-def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T):
+@pytest.mark.parametrize("pairs", [True, False])
+@pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 192, 224, 256, 320, 384, 448, 1056, 1088])
+def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T, pairs):
     """dY stored m x T with T a whole number of K tiles: the large-tile kernel gathers the
-    selected rows itself (no packing pass); prologue, steady loop and drain at every length."""
+    selected rows itself (no packing pass); prologue, steady loop and drain at every length.
+    An even number of K tiles takes the form that loads 64 values of k per row and request
+    (unless switched off), an odd one the form with one load per K tile."""
     monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    if not pairs:
+        monkeypatch.setenv("GRASS_GEMM_NO_PAIRS", "1")
     m, n, r = 300, 264, 260
     dY = randn((T, m), torch.bfloat16, 71, scale=0.1)
     X = randn((T, n), torch.bfloat16, 72)
@@ -584,6 +589,7 @@ def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T):
     (1024, 5000, 520, 700, 0),     # rows spread over a tall matrix, 700 = 2 tiles + 188
     (512, 640, 1376, 257, 64),     # one row past a tile boundary, padded leading dimension
     (8192, 600, 264, 8, 0),        # a handful of rows, several K slices
+    (16384 + 64, 520, 264, 300, 0),  # K slices of an odd number of K tiles, rounded up to pairs
 ])
 def test_row_gathering_gemm_shapes_and_agreement_with_packing(monkeypatch, T, m, n, r, pad):
     monkeypatch.setenv("GRASS_GEMM_TILE", "256")
