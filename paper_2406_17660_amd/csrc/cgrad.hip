@@ -329,15 +329,48 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
 
     GemmArgs g;
     if (pack) {
+        // T x m storage, wide rows: staged through LDS (streaming loads of whole rows)
+        auto staged = [&](int i, int64_t width) {
+            const int64_t m_src = seg[i].src_rows;
+            return layout == GRASS_DY_TxM && m_src >= 2048 && m_src <= kPackStageMaxM &&
+                   width >= 512 && m_src % 8 == 0 && seg[i].ldy % 8 == 0 && aligned_to(seg[i].dY, 16);
+        };
+        auto threads_per_row_log2 = [](int64_t width) {
+            int tpr_log2 = 8;  // the power of two covering width / 4
+            while (tpr_log2 > 0 && (int64_t{4} << (tpr_log2 - 1)) >= width) --tpr_log2;
+            return tpr_log2;
+        };
+        // several sets, none of them wide: one launch gathers them all
+        bool one_launch = count > 1 && layout == GRASS_DY_TxM && T > 0;
+        {
+            PackSets sets;
+            int64_t off = 0, gx = 1, gy = 1;
+            for (int i = 0; i < count && one_launch; ++i) {
+                const int64_t width = i + 1 == count ? p.rp - off : (seg[i].rows + 7) / 8 * 8;
+                if (staged(i, width)) one_launch = false;
+                const int tpr_log2 = threads_per_row_log2(width > 0 ? width : 1);
+                sets.set[i] = PackSet{static_cast<const uint16_t*>(seg[i].dY), seg[i].ldy, seg[i].idx,
+                                      seg[i].rows, width, off, tpr_log2};
+                const int64_t rows_per_wg = static_cast<int64_t>(kPackRows) * (256 >> tpr_log2);
+                const int64_t bx = (T + rows_per_wg - 1) / rows_per_wg;
+                const int64_t by = (width + (int64_t{4} << tpr_log2) - 1) / (int64_t{4} << tpr_log2);
+                gx = bx > gx ? bx : gx;
+                gy = by > gy ? by : gy;
+                off += width;
+            }
+            if (one_launch) {
+                const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy),
+                                static_cast<unsigned>(count));
+                pack_txm_group_kernel<<<grid, 256, 0, s>>>(sets, T, p.rp, panel);
+            }
+        }
         int64_t off = 0;
-        for (int i = 0; i < count && T > 0; ++i) {
+        for (int i = 0; i < count && T > 0 && !one_launch; ++i) {
             // the last set also zero-fills the panel's padding columns
             const int64_t width = i + 1 == count ? p.rp - off : (seg[i].rows + 7) / 8 * 8;
             if (width > 0) {
                 const int64_t m_src = seg[i].src_rows;  // row length of this set's dY
-                if (layout == GRASS_DY_TxM && m_src >= 2048 && m_src <= kPackStageMaxM &&
-                    width >= 512 && m_src % 8 == 0 && seg[i].ldy % 8 == 0 &&
-                    aligned_to(seg[i].dY, 16)) {
+                if (staged(i, width)) {
                     // wide rows: staged through LDS (streaming loads of whole rows)
                     const auto* src = static_cast<const uint16_t*>(seg[i].dY);
                     if (m_src <= kPackStageTwoRowsMaxM)
@@ -349,8 +382,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                                                     static_cast<size_t>(m_src) * 2, s>>>(
                             src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                 } else if (layout == GRASS_DY_TxM) {
-                    int tpr_log2 = 8;  // threads per row of t: the power of two covering width / 4
-                    while (tpr_log2 > 0 && (int64_t{4} << (tpr_log2 - 1)) >= width) --tpr_log2;
+                    const int tpr_log2 = threads_per_row_log2(width);
                     const int64_t gx = (width + (int64_t{4} << tpr_log2) - 1) / (int64_t{4} << tpr_log2);
                     const int64_t rows_per_wg = static_cast<int64_t>(kPackRows) * (256 >> tpr_log2);
                     const dim3 grid(static_cast<unsigned>((T + rows_per_wg - 1) / rows_per_wg),

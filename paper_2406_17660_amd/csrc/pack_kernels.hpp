@@ -45,6 +45,49 @@ __global__ __launch_bounds__(256) void pack_txm_kernel(const uint16_t* __restric
     }
 }
 
+// The gather above for several matrices in one launch (layers that share X: their selected
+// rows go side by side into one panel): blockIdx.z picks the set.  Short gathers (tens of
+// microseconds each) otherwise pay a launch and a ramp-up apiece.
+struct PackSet {
+    const uint16_t* dY;
+    int64_t ldy;
+    const int32_t* idx;
+    int64_t r, rp;       // selected rows, panel columns of this set (padding included)
+    int64_t off;         // first panel column of this set
+    int tpr_log2;        // threads per row of t
+};
+struct PackSets {
+    PackSet set[GRASS_MAX_GROUP];
+};
+__global__ __launch_bounds__(256) void pack_txm_group_kernel(PackSets sets, int64_t T, int64_t ldo,
+                                                             uint16_t* __restrict__ panel) {
+    const PackSet& q = sets.set[blockIdx.z];
+    const int tpr_log2 = q.tpr_log2;
+    const int tpr = 1 << tpr_log2, rows_per_pass = 256 >> tpr_log2;
+    const int64_t j0 = (static_cast<int64_t>(blockIdx.y) * tpr + (threadIdx.x & (tpr - 1))) * 4;
+    if (j0 >= q.rp) return;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kPackRows * rows_per_pass +
+                       (threadIdx.x >> tpr_log2);
+    if (t0 >= T) return;  // the grid covers the set with the fewest rows of t per workgroup
+    int64_t col[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) col[e] = j0 + e < q.r ? (q.idx ? q.idx[j0 + e] : j0 + e) : -1;
+    uint16_t* out = panel + q.off;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int tt = 0; tt < kPackRows; ++tt) {
+        const int64_t t = t0 + static_cast<int64_t>(tt) * rows_per_pass;
+        if (t >= T) break;
+        const uint16_t* row = q.dY + t * q.ldy;
+        uint16_t v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? row[col[e]] : static_cast<uint16_t>(0);
+        const u32x2 w = {v[0] | (static_cast<uint32_t>(v[1]) << 16),
+                         v[2] | (static_cast<uint32_t>(v[3]) << 16)};
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x2*>(out + t * ldo + j0));
+    }
+}
+
 // The same gather for wide matrices, with the rows of dY staged through LDS: a workgroup copies
 // kPackStageRows whole rows of t into LDS with streaming 16-byte loads (every byte of dY is
 // fetched exactly once, by a full-width request, and is not kept in the caches), then gathers
