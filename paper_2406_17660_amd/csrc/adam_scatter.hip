@@ -259,14 +259,21 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
 // idx are walked by their first member, as in adam_scatter_kernel.  Fixed order: deterministic.
 template <typename WT, typename ST>
 __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
-    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
-    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
-    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
-    float* __restrict__ GC, int64_t ldgc) {
+    TailSets sets, int slices, int64_t Mp, int64_t Np, int64_t n, AdamParams p_in, float alpha) {
     __shared__ float4 quarter[4][64];
+    const TailSet& q = sets.set[blockIdx.z];  // the row set of this workgroup
+    const int64_t j = blockIdx.y, r = q.r;
+    if (j >= r) return;  // the grid spans the largest set
+    const float* __restrict__ part = q.part;
+    ST* __restrict__ M = static_cast<ST*>(q.M);
+    ST* __restrict__ V = static_cast<ST*>(q.V);
+    WT* __restrict__ W = static_cast<WT*>(q.W);
+    const int64_t ldw = q.ldw, ldgc = q.ldgc;
+    const int32_t* __restrict__ idx = q.idx;
+    const float* __restrict__ rho = q.rho;
+    float* __restrict__ GC = q.GC;
     const AdamParams p = resolve(p_in);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t j = blockIdx.y;
     const int32_t row = idx[j];
     if (j > 0 && idx[j - 1] == row) return;  // whole workgroup: no barrier is skipped by part of it
     const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + lane * 4;
@@ -324,12 +331,19 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
 // kernel keeps as many bytes in flight as adam_scatter_kernel does.
 template <typename WT, typename ST>
 __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
-    const float* __restrict__ part, int slices, int64_t Mp, int64_t Np, int64_t n, int64_t r,
-    AdamParams p_in, ST* __restrict__ M, ST* __restrict__ V, WT* __restrict__ W, int64_t ldw,
-    const int32_t* __restrict__ idx, const float* __restrict__ rho, float alpha,
-    float* __restrict__ GC, int64_t ldgc) {
+    TailSets sets, int slices, int64_t Mp, int64_t Np, int64_t n, AdamParams p_in, float alpha) {
+    const TailSet& q = sets.set[blockIdx.z];
+    const int64_t j = blockIdx.y, r = q.r;
+    if (j >= r) return;
+    const float* __restrict__ part = q.part;
+    ST* __restrict__ M = static_cast<ST*>(q.M);
+    ST* __restrict__ V = static_cast<ST*>(q.V);
+    WT* __restrict__ W = static_cast<WT*>(q.W);
+    const int64_t ldw = q.ldw, ldgc = q.ldgc;
+    const int32_t* __restrict__ idx = q.idx;
+    const float* __restrict__ rho = q.rho;
+    float* __restrict__ GC = q.GC;
     const AdamParams p = resolve(p_in);
-    const int64_t j = blockIdx.y;
     const int32_t row = idx[j];
     if (j > 0 && idx[j - 1] == row) return;
     const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
@@ -599,34 +613,32 @@ bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64
 }
 
 template <typename WT, typename ST>
-static void reduce_adam_scatter_typed(const float* part, int slices, int64_t Mp, int64_t Np,
-                                      int64_t r, int64_t n, const AdamParams& p, const StepTail& t,
-                                      const int32_t* idx, const float* rho, float* GC,
-                                      int64_t ldgc, hipStream_t s) {
+static void reduce_adam_scatter_typed(const TailSets& sets, int count, int64_t rmax, int slices,
+                                      int64_t Mp, int64_t Np, int64_t n, const AdamParams& p,
+                                      float alpha, hipStream_t s) {
     if (slices <= 8) {
-        reduce_adam_scatter_few_kernel<WT, ST><<<grid_for(n, r, 4), kThreads, 0, s>>>(
-            part, slices, Mp, Np, n, r, p, static_cast<ST*>(t.M), static_cast<ST*>(t.V),
-            static_cast<WT*>(t.W), t.ldw, idx, rho, t.alpha, GC, ldgc);
+        dim3 grid = grid_for(n, rmax, 4);
+        grid.z = static_cast<unsigned>(count);
+        reduce_adam_scatter_few_kernel<WT, ST><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
         return;
     }
-    const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(r));
-    reduce_adam_scatter_kernel<WT, ST><<<grid, kThreads, 0, s>>>(
-        part, slices, Mp, Np, n, r, p, static_cast<ST*>(t.M), static_cast<ST*>(t.V),
-        static_cast<WT*>(t.W), t.ldw, idx, rho, t.alpha, GC, ldgc);
+    const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(rmax),
+                    static_cast<unsigned>(count));
+    reduce_adam_scatter_kernel<WT, ST><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
 }
 
-grass_status launch_reduce_adam_scatter(const float* part, int slices, int64_t Mp, int64_t Np,
-                                        int64_t r, int64_t n, const StepTail& t,
-                                        const int32_t* idx, const float* rho, float* GC,
-                                        int64_t ldgc, hipStream_t s) {
-    if (r == 0 || n == 0) return GRASS_OK;
-    if (r > kMaxGridY) return GRASS_ERR_SHAPE;
+grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
+                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s) {
+    int64_t rmax = 0;
+    for (int i = 0; i < count; ++i) rmax = sets.set[i].r > rmax ? sets.set[i].r : rmax;
+    if (count < 1 || rmax == 0 || n == 0) return GRASS_OK;
+    if (rmax > kMaxGridY || count > GRASS_MAX_GROUP) return GRASS_ERR_SHAPE;
     const AdamParams p = make_params(t.lr, t.beta1, t.beta2, t.eps, t.t, t.step_scalars);
     const bool wf = t.wdt == GRASS_F32, sf = t.sdt == GRASS_F32;
-    if (wf && sf) reduce_adam_scatter_typed<float, float>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
-    else if (wf) reduce_adam_scatter_typed<float, uint16_t>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
-    else if (sf) reduce_adam_scatter_typed<uint16_t, float>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
-    else reduce_adam_scatter_typed<uint16_t, uint16_t>(part, slices, Mp, Np, r, n, p, t, idx, rho, GC, ldgc, s);
+    if (wf && sf) reduce_adam_scatter_typed<float, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+    else if (wf) reduce_adam_scatter_typed<float, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+    else if (sf) reduce_adam_scatter_typed<uint16_t, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+    else reduce_adam_scatter_typed<uint16_t, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
     return launch_status();
 }
 

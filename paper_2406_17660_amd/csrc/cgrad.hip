@@ -480,15 +480,18 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     }
 
     int64_t off = 0;
+    TailSets tails;  // sets whose reduction, Adam and row update run as one kernel (one launch)
+    int ntails = 0;
+    const StepTail* tail_common = nullptr;
     for (int i = 0; i < count; ++i) {
         const GemmSegment& q = seg[i];
         if (q.rows > 0 && q.tail && odt == GRASS_F32 &&
             reduce_adam_scatter_ok(*q.tail, n, q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc)) {
-            // reduction, Adam and the row update in one kernel, straight from the partial tiles
-            const grass_status st = launch_reduce_adam_scatter(
-                partial + off * p.Np, slices, p.Mp, p.Np, q.rows, n, *q.tail, q.idx, q.rho,
-                q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc, s);
-            if (st != GRASS_OK) return st;
+            // straight from the partial tiles; launched after the loop, together
+            tails.set[ntails++] = TailSet{partial + off * p.Np, q.rows, q.tail->M, q.tail->V, q.tail->W,
+                                          q.tail->ldw, q.idx, q.rho,
+                                          q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc};
+            tail_common = q.tail;
         } else if (q.rows > 0) {
             const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
             const float* part = partial + off * p.Np;
@@ -509,6 +512,11 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             if (st != GRASS_OK) return st;
         }
         off += (q.rows + 7) / 8 * 8;
+    }
+    if (ntails > 0) {
+        const grass_status st = launch_reduce_adam_scatter(tails, ntails, slices, p.Mp, p.Np, n,
+                                                           *tail_common, s);
+        if (st != GRASS_OK) return st;
     }
     return launch_status();
 }

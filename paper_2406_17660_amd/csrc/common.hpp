@@ -134,11 +134,27 @@ struct StepTail {
 };
 // True when M, V, W (and GC, if given) allow the 16-byte accesses of the fused kernel.
 bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc);
-// part: partial tiles [slices][Mp][Np] (already offset to this segment's first row).
-grass_status launch_reduce_adam_scatter(const float* part, int slices, int64_t Mp, int64_t Np,
-                                        int64_t r, int64_t n, const StepTail& t,
-                                        const int32_t* idx, const float* rho, float* GC,
-                                        int64_t ldgc, hipStream_t s);
+// One row set of the fused tail.  part: partial tiles [slices][Mp][Np], already offset to this
+// set's first row; GC: where to store the compressed gradient, or nullptr.
+struct TailSet {
+    const float* part;
+    int64_t r;
+    void* M;
+    void* V;
+    void* W;
+    int64_t ldw;
+    const int32_t* idx;
+    const float* rho;
+    float* GC;
+    int64_t ldgc;
+};
+struct TailSets {
+    TailSet set[GRASS_MAX_GROUP];
+};
+// The fused tail for `count` row sets in one launch.  The sets share the partial-tile geometry,
+// n, the dtypes and Adam's scalars, which are taken from `t` (its M, V, W are not read).
+grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
+                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s);
 
 // The same product for several row sets that share X (one packed panel, one GEMM).
 struct GemmSegment {
