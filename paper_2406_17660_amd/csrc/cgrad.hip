@@ -115,13 +115,16 @@ template <typename Cfg, bool kDense>
 hipError_t launch_gemm_kernel(const GemmArgs& g, unsigned grid, hipStream_t s) {
     auto kernel = tn_gemm_bf16_kernel<Cfg, kDense>;
     if (Cfg::kLdsBytes > 64 * 1024) {
-        static bool raised = false;  // per instantiation; the attribute is sticky per process
-        if (!raised) {
+        // per instantiation and device; the attribute sticks for the life of the process
+        static bool raised[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+        if (dev < 0 || dev >= 64 || !raised[dev]) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      static_cast<int>(Cfg::kLdsBytes));
             if (e != hipSuccess) return e;
-            raised = true;
+            if (dev >= 0 && dev < 64) raised[dev] = true;
         }
     }
     kernel<<<grid, Cfg::kThreads, Cfg::kLdsBytes, s>>>(g);
