@@ -435,6 +435,9 @@ def test_large_tile_kernel_every_pipeline_length(monkeypatch, T):
     (1056, 264, (300, 520, 64), (130, 129, 0), "256"),  # large tile, an empty set in last place
     (777, 333, (130, 40, 50), (0, 40, 9), None),        # an empty set first, odd n
     (2048, 512, (384,), (260,), "256"),                 # a group of one
+    (130, 64, (2048, 2056, 4096), (512, 600, 700), None),  # wide sets: each gathered through LDS
+    (130, 64, (2048, 300), (512, 40), None),            # a wide set next to a narrow one: separate gathers
+    (257, 72, (520, 264, 1376), (128, 40, 200), None),  # narrow sets: one gather launch for all
 ])
 def test_compressed_grad_group_matches_per_matrix_oracle(monkeypatch, dtype, layout, T, n, ms, rs, tile):
     """Several matrices sharing X (q, k, v): every output equals the single-matrix definition."""
