@@ -9,6 +9,9 @@
 //              GEMM main loop would pull m/r times more cache lines through each CU's L1
 //              than the tile uses; doing it once in an HBM-bound pass keeps the GEMM's
 //              inner loop on full 16-byte loads.  (The dense gradient needs no pack.)
+//              Wide matrices stage whole rows of dY through LDS (streaming loads, gather
+//              from LDS); narrow sets of a group share one launch.  With dY stored m x T
+//              there is no pack: the GEMM's tile loads fetch the selected rows themselves.
 //   2. GEMM:   v_mfma_f32_32x32x16_bf16 tiles.  Global tiles [BK x BM] / [BK x BN] are staged
 //              through LDS in their memory order (t-major) with 16-byte loads; the MFMA
 //              operand layout (8 consecutive t per lane) is produced by the gfx950
@@ -16,7 +19,8 @@
 //              materialised.  Split-K over T fills the 256 CUs; work items are numbered
 //              so that the workgroups an XCD receives share one K slice (L2 reuse).
 //   3. reduce: sums the split-K partials in a fixed order (deterministic), applies rho and
-//              converts to the output dtype.
+//              converts to the output dtype; in a regular step this, Adam and the update of
+//              the rows of W are one kernel that reads the partial tiles directly.
 // fp32 path: a plain LDS-tiled FMA kernel (small reference-precision configurations).
 #include "common.hpp"
 
