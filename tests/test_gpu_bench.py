@@ -1,0 +1,46 @@
+"""bench.py's one-line JSON contract, on a shortened token batch (runs in seconds)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def run_bench(*args):
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], cwd=ROOT,
+                       capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1, "exactly one JSON line"
+    return json.loads(lines[0])
+
+
+def test_layer_bench_line_has_every_field_of_the_contract():
+    d = run_bench("--tokens", "4096", "--steps", "5", "--warmup", "2", "--cpu-seconds", "1")
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
+                "higher_is_better", "scaling", "vs_baseline", "dtype", "data", "config", "roofline",
+                "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["warmup"] == 2
+    assert d["higher_is_better"] is True and d["vs_baseline"] is None
+    assert d["unit"] == "layer-steps/s" and d["dtype"] == "bf16" and d["data"] == "synthetic"
+    assert abs(d["value"] * d["ms_per_step"] * 1e-3 - 1.0) < 1e-6
+    assert "workload" in d["config"] and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
+    assert abs(r["achieved"] - r["flops_per_launch"] / (r["avg_launch_ms"] * 1e-3) / 1e12) < 1e-6 * r["achieved"]
+    assert "traffic" in r  # measured bytes exist for the full-size workload only
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["unit"] == d["unit"] and c["cores"] >= 1 and c["value"] > 0
+    assert isinstance(c["sample"], str) and c["sample"]
+
+
+def test_block_bench_line():
+    d = run_bench("--block", "60m", "--tokens", "2048", "--steps", "4", "--warmup", "1")
+    assert d["unit"] == "block-steps/s" and d["n_gpus"] == 1 and d["value"] > 0
+    assert "workload" in d["config"]
