@@ -318,6 +318,28 @@ grass_status grass_step_group(int count, const grass_step_layer* layers, grass_d
                               void* ws, size_t ws_bytes, void* stream, void* ev_gemm_start,
                               void* ev_gemm_stop);
 
+/* The regular step in column form, in one call (Section 4.1 projects the smaller dimension of
+ * G; for a layer with m > n that is the input dimension, so r of the n COLUMNS of W are
+ * trained): with dY (T x m) and X (T x n), both stored with t as the row index,
+ *   G_C = rho ((B X^T) dY)            r x m   (= (G P)^T, P the n x r projection),
+ *   Adam on r x m moments M, V        (U = its output, r x m fp32),
+ *   W[:, idx[j]] += alpha * rho[j] * U[j, :]^T.
+ * Exactly what grass_compressed_grad (X in the place of dY and dY in the place of X),
+ * grass_adam_rows_state and grass_scatter_update_cols compute one after the other; the
+ * split-K reduction of the product and Adam run as one kernel that reads the product's
+ * partial tiles.  idx: r column indices in [0, n), ascending; GC: NULL, or r x m fp32 (leading
+ * dimension ldgc) to receive G_C; U: r x m fp32, contiguous, 16-byte aligned (scratch the
+ * caller owns; holds Adam's output afterwards); W: m x n of dtype wdt, leading dimension ldw;
+ * ws: grass_step_cols_workspace(...) bytes.  Errors: NULL, SHAPE, DTYPE, WORKSPACE. */
+size_t grass_step_cols_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt);
+grass_status grass_step_cols(const void* dY, int64_t ldy, const void* X, int64_t ldx,
+                             grass_dtype dt, int64_t T, int64_t m, int64_t n, int64_t r,
+                             const int32_t* idx, const float* rho, float* GC, int64_t ldgc,
+                             void* M, void* V, grass_dtype sdt, float* U, void* W,
+                             grass_dtype wdt, int64_t ldw, float lr, float beta1, float beta2,
+                             float eps, int64_t t, float alpha, void* ws, size_t ws_bytes,
+                             void* stream, void* ev_gemm_start, void* ev_gemm_stop);
+
 /* ---------------------------------------------------------------------------
  * The fused Adam + update for callers that capture a step into a HIP graph and replay it.
  * Adam's step count t and the learning rate change every step, and a captured launch keeps

@@ -257,7 +257,9 @@ __global__ __launch_bounds__(kThreads) void adam_scatter_kernel(
 // the quarters meet in LDS and the first wavefront scales the sum by rho (that is G_C, written
 // out only if the caller wants it), runs Adam on it and accumulates the update.  Runs of equal
 // idx are walked by their first member, as in adam_scatter_kernel.  Fixed order: deterministic.
-template <typename WT, typename ST>
+// kToU (column form): every compressed row stands for itself (no runs, W is not touched) and
+// Adam's output is stored to U.
+template <typename WT, typename ST, bool kToU>
 __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
     TailSets sets, int slices, int64_t Mp, int64_t Np, int64_t n, AdamParams p_in, float alpha) {
     __shared__ float4 quarter[4][64];
@@ -272,19 +274,20 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
     const int32_t* __restrict__ idx = q.idx;
     const float* __restrict__ rho = q.rho;
     float* __restrict__ GC = q.GC;
+    float* __restrict__ U = q.U;
     const AdamParams p = resolve(p_in);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int32_t row = idx[j];
-    if (j > 0 && idx[j - 1] == row) return;  // whole workgroup: no barrier is skipped by part of it
+    const int32_t row = kToU ? 0 : idx[j];
+    if (!kToU && j > 0 && idx[j - 1] == row) return;  // whole workgroup: no barrier is skipped by part of it
     const int64_t c = static_cast<int64_t>(blockIdx.x) * 256 + lane * 4;
     const bool live = c < n;  // n % 4 == 0: a live lane owns four whole columns
     const int per = (slices + 3) / 4;
     const int k0 = w * per, k1 = k0 + per < slices ? k0 + per : slices;
     const int64_t slice_stride = Mp * Np;
     WVec<WT, 4> wv;
-    if (w == 0 && live) wv.load(W + static_cast<int64_t>(row) * ldw + c);
+    if (!kToU && w == 0 && live) wv.load(W + static_cast<int64_t>(row) * ldw + c);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+    for (int64_t jj = j; kToU ? jj == j : (jj < r && idx[jj] == row); ++jj) {
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
         if (live) {
             const float* src = part + (static_cast<int64_t>(k0) * Mp + jj) * Np + c;
@@ -312,14 +315,21 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
             WVec<ST, 4> mv, vv;
             mv.load(M + jj * n + c);
             vv.load(V + jj * n + c);
+            if (kToU) {
+                F32Vec<4> u;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+                for (int e = 0; e < 4; ++e) u.x[e] = adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+                u.store(U + jj * n + c);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+            }
             mv.store(M + jj * n + c);
             vv.store(V + jj * n + c);
         }
         __syncthreads();  // the quarters are rewritten for the next member of the run
     }
-    if (w == 0 && live) {
+    if (!kToU && w == 0 && live) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
         wv.store(W + static_cast<int64_t>(row) * ldw + c);
@@ -329,7 +339,7 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_kernel(
 // The same for a handful of slices: every thread adds all slices of its own four columns (the
 // loads are independent, nothing goes through LDS) and all four wavefronts run Adam, so the
 // kernel keeps as many bytes in flight as adam_scatter_kernel does.
-template <typename WT, typename ST>
+template <typename WT, typename ST, bool kToU>
 __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
     TailSets sets, int slices, int64_t Mp, int64_t Np, int64_t n, AdamParams p_in, float alpha) {
     const TailSet& q = sets.set[blockIdx.z];
@@ -343,16 +353,17 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
     const int32_t* __restrict__ idx = q.idx;
     const float* __restrict__ rho = q.rho;
     float* __restrict__ GC = q.GC;
+    float* __restrict__ U = q.U;
     const AdamParams p = resolve(p_in);
-    const int32_t row = idx[j];
-    if (j > 0 && idx[j - 1] == row) return;
+    const int32_t row = kToU ? 0 : idx[j];
+    if (!kToU && j > 0 && idx[j - 1] == row) return;
     const int64_t c = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
     if (c >= n) return;  // n % 4 == 0: four whole columns or none
     const int64_t slice_stride = Mp * Np;
     WVec<WT, 4> wv;
-    wv.load(W + static_cast<int64_t>(row) * ldw + c);
+    if (!kToU) wv.load(W + static_cast<int64_t>(row) * ldw + c);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t jj = j; jj < r && idx[jj] == row; ++jj) {
+    for (int64_t jj = j; kToU ? jj == j : (jj < r && idx[jj] == row); ++jj) {
         WVec<ST, 4> mv, vv;
         mv.load(M + jj * n + c);
         vv.load(V + jj * n + c);
@@ -369,11 +380,19 @@ __global__ __launch_bounds__(kThreads) void reduce_adam_scatter_few_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) g.x[e] *= sc;
         if (GC) g.store(GC + jj * ldgc + c);
+        if (kToU) {
+            F32Vec<4> u;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+            for (int e = 0; e < 4; ++e) u.x[e] = adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+            u.store(U + jj * n + c);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += sc * adam_elem<ST>(g.x[e], mv.x[e], vv.x[e], p);
+        }
         mv.store(M + jj * n + c);
         vv.store(V + jj * n + c);
     }
+    if (kToU) return;
 #pragma unroll
     for (int e = 0; e < 4; ++e) wv.x[e] += alpha * acc[e];
     wv.store(W + static_cast<int64_t>(row) * ldw + c);
@@ -609,22 +628,23 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
 
 bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc) {
     return n % 4 == 0 && w_rows_vectorisable(t.M, t.sdt, n) && w_rows_vectorisable(t.V, t.sdt, n) &&
-           w_rows_vectorisable(t.W, t.wdt, t.ldw) && (!GC || f32_rows_vectorisable(GC, ldgc));
+           (t.U ? f32_rows_vectorisable(t.U, n) : w_rows_vectorisable(t.W, t.wdt, t.ldw)) &&
+           (!GC || f32_rows_vectorisable(GC, ldgc));
 }
 
-template <typename WT, typename ST>
+template <typename WT, typename ST, bool kToU = false>
 static void reduce_adam_scatter_typed(const TailSets& sets, int count, int64_t rmax, int slices,
                                       int64_t Mp, int64_t Np, int64_t n, const AdamParams& p,
                                       float alpha, hipStream_t s) {
     if (slices <= 8) {
         dim3 grid = grid_for(n, rmax, 4);
         grid.z = static_cast<unsigned>(count);
-        reduce_adam_scatter_few_kernel<WT, ST><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+        reduce_adam_scatter_few_kernel<WT, ST, kToU><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
         return;
     }
     const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(rmax),
                     static_cast<unsigned>(count));
-    reduce_adam_scatter_kernel<WT, ST><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+    reduce_adam_scatter_kernel<WT, ST, kToU><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
 }
 
 grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
@@ -635,6 +655,13 @@ grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int sli
     if (rmax > kMaxGridY || count > GRASS_MAX_GROUP) return GRASS_ERR_SHAPE;
     const AdamParams p = make_params(t.lr, t.beta1, t.beta2, t.eps, t.t, t.step_scalars);
     const bool wf = t.wdt == GRASS_F32, sf = t.sdt == GRASS_F32;
+    if (sets.set[0].U) {  // column form: W is not touched here
+        for (int i = 0; i < count; ++i)
+            if (!sets.set[i].U) return GRASS_ERR_SHAPE;  // one form per launch
+        if (sf) reduce_adam_scatter_typed<uint16_t, float, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+        else reduce_adam_scatter_typed<uint16_t, uint16_t, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+        return launch_status();
+    }
     if (wf && sf) reduce_adam_scatter_typed<float, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
     else if (wf) reduce_adam_scatter_typed<float, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
     else if (sf) reduce_adam_scatter_typed<uint16_t, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);

@@ -281,6 +281,47 @@ grass_status grass_step_group(int count, const grass_step_layer* layers, grass_d
                                    static_cast<hipEvent_t>(ev_gemm_stop));
 }
 
+size_t grass_step_cols_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt) {
+    if (T < 0 || m < 0 || n < 0 || r < 0 || !small(T) || !small(m) || !small(n) || r > kMaxGridRows)
+        return 0;
+    // the transposed problem: r selected rows of an n x m gradient, plus room for an unnamed G_C
+    return gemm_workspace_bytes(T, r, m, dt, GRASS_DY_TxM, true) + 256 + scratch_gc_bytes(r, m);
+}
+
+grass_status grass_step_cols(const void* dY, int64_t ldy, const void* X, int64_t ldx,
+                             grass_dtype dt, int64_t T, int64_t m, int64_t n, int64_t r,
+                             const int32_t* idx, const float* rho, float* GC, int64_t ldgc,
+                             void* M, void* V, grass_dtype sdt, float* U, void* W,
+                             grass_dtype wdt, int64_t ldw, float lr, float beta1, float beta2,
+                             float eps, int64_t t, float alpha, void* ws, size_t ws_bytes,
+                             void* stream, void* ev_gemm_start, void* ev_gemm_stop) {
+    grass_status st = check_products(dY, GRASS_DY_TxM, ldy, X, ldx, dt, T, m, n);
+    if (st != GRASS_OK) return st;
+    if (r < 0 || r > kMaxGridRows || (GC && ldgc < m) || (r > 0 && n == 0)) return GRASS_ERR_SHAPE;
+    st = check_adam(GC ? GC : reinterpret_cast<const float*>(M), GC ? ldgc : m, M, V, sdt, r, m,
+                    beta1, beta2, t);
+    if (st != GRASS_OK) return st;
+    if (ldw < n) return GRASS_ERR_SHAPE;
+    if (!present(W, m * n) || !present(idx, r) || !present(rho, r) || !present(U, r * m))
+        return GRASS_ERR_NULL;
+    if (!dtype_ok(wdt)) return GRASS_ERR_DTYPE;
+    if (!aligned_to(U, 16)) return GRASS_ERR_SHAPE;
+    const size_t gemm_bytes = gemm_workspace_bytes(T, r, m, dt, GRASS_DY_TxM, true);
+    if (!ws || ws_bytes < gemm_bytes + 256 + scratch_gc_bytes(r, m)) return GRASS_ERR_WORKSPACE;
+    char* scratch = static_cast<char*>(ws) + gemm_bytes;
+    scratch += (256 - reinterpret_cast<uintptr_t>(scratch) % 256) % 256;
+    StepTail tail{M, V, sdt, lr, beta1, beta2, eps, t, nullptr, W, wdt, ldw, alpha};
+    tail.U = U;
+    tail.w_rows = m;
+    // rows of the transposed problem: the r selected columns of X are gathered, dY is the
+    // dense operand
+    const GemmSegment seg{X, ldx, idx, rho, GC ? static_cast<void*>(GC) : scratch, GC ? ldgc : m,
+                          r, n, &tail, GC != nullptr};
+    return launch_tn_gemm_segments(&seg, 1, GRASS_DY_TxM, dY, ldy, dt, T, m, GRASS_F32, ws,
+                                   as_stream(stream), static_cast<hipEvent_t>(ev_gemm_start),
+                                   static_cast<hipEvent_t>(ev_gemm_stop));
+}
+
 grass_status grass_adam_step_scalars(float lr, float beta1, float beta2, int64_t t,
                                      float* scalars) {
     if (!scalars) return GRASS_ERR_NULL;

@@ -231,6 +231,12 @@ size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int
 grass_status run_tail_unfused(const GemmSegment& q, int64_t n, hipStream_t s) {
     if (!q.tail || q.rows == 0) return GRASS_OK;
     const StepTail& t = *q.tail;
+    if (t.U) {  // column form: Adam into U, then the update of the columns of W
+        const grass_status st = launch_adam_rows(static_cast<const float*>(q.C), q.ldc, t.M, t.V, t.sdt,
+                                                 q.rows, n, t.lr, t.beta1, t.beta2, t.eps, t.t, t.U, s);
+        if (st != GRASS_OK) return st;
+        return launch_scatter_cols(t.W, t.wdt, t.w_rows, t.ldw, q.idx, q.rho, t.alpha, t.U, q.rows, s);
+    }
     return launch_adam_scatter(static_cast<const float*>(q.C), q.ldc, t.M, t.V, t.sdt, q.rows, n,
                                t.lr, t.beta1, t.beta2, t.eps, t.t, t.W, t.wdt, t.ldw, q.idx, q.rho,
                                t.alpha, s, t.step_scalars);
@@ -495,10 +501,21 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         if (q.rows > 0 && q.tail && odt == GRASS_F32 &&
             reduce_adam_scatter_ok(*q.tail, n, q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc)) {
             // straight from the partial tiles; launched after the loop, together
-            tails.set[ntails++] = TailSet{partial + off * p.Np, q.rows, q.tail->M, q.tail->V, q.tail->W,
-                                          q.tail->ldw, q.idx, q.rho,
-                                          q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc};
-            tail_common = q.tail;
+            const TailSet one{partial + off * p.Np, q.rows, q.tail->M, q.tail->V, q.tail->W,
+                              q.tail->ldw, q.idx, q.rho,
+                              q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc, q.tail->U};
+            if (q.tail->U) {  // column form: its own launch, followed by the column update
+                TailSets single;
+                single.set[0] = one;
+                grass_status st = launch_reduce_adam_scatter(single, 1, slices, p.Mp, p.Np, n, *q.tail, s);
+                if (st != GRASS_OK) return st;
+                st = launch_scatter_cols(q.tail->W, q.tail->wdt, q.tail->w_rows, q.tail->ldw, q.idx,
+                                         q.rho, q.tail->alpha, q.tail->U, q.rows, s);
+                if (st != GRASS_OK) return st;
+            } else {
+                tails.set[ntails++] = one;
+                tail_common = q.tail;
+            }
         } else if (q.rows > 0) {
             const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
             const float* part = partial + off * p.Np;

@@ -131,8 +131,13 @@ struct StepTail {
     grass_dtype wdt;
     int64_t ldw;
     float alpha;
+    // Column form (U != nullptr): the set's rows are columns of W.  Adam's output goes to U
+    // (rows x n fp32, contiguous) and W (w_rows = n rows) gets W[:, idx[j]] += alpha rho_j U[j, :].
+    // step_scalars is not supported in this form.
+    float* U = nullptr;
+    int64_t w_rows = 0;
 };
-// True when M, V, W (and GC, if given) allow the 16-byte accesses of the fused kernel.
+// True when M, V, W or U (and GC, if given) allow the 16-byte accesses of the fused kernel.
 bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64_t ldgc);
 // One row set of the fused tail.  part: partial tiles [slices][Mp][Np], already offset to this
 // set's first row; GC: where to store the compressed gradient, or nullptr.
@@ -147,12 +152,14 @@ struct TailSet {
     const float* rho;
     float* GC;
     int64_t ldgc;
+    float* U;  // column form: Adam's output (r x n, contiguous) instead of the update of W
 };
 struct TailSets {
     TailSet set[GRASS_MAX_GROUP];
 };
 // The fused tail for `count` row sets in one launch.  The sets share the partial-tile geometry,
-// n, the dtypes and Adam's scalars, which are taken from `t` (its M, V, W are not read).
+// n, the dtypes, the form (row or column) and Adam's scalars, which are taken from `t` (its M, V,
+// W, U are not read).  In column form the caller launches the column update afterwards.
 grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
                                         int64_t Np, int64_t n, const StepTail& t, hipStream_t s);
 

@@ -30,6 +30,7 @@ EXPORTS = [
     "grass_adam_rows_state", "grass_adam_scatter_state", "grass_probe_mfma_rate",
     "grass_adam_step_scalars", "grass_adam_scatter_replayable",
     "grass_step_group_workspace", "grass_step_group",
+    "grass_step_cols_workspace", "grass_step_cols",
 ]
 
 _lib = None
@@ -86,6 +87,11 @@ def lib():
     L.grass_step_group_workspace.restype = sz
     L.grass_step_group.argtypes = [i32, vp, i32, vp, i64, i32, i64, i64, i32, i32, f32, f32, f32,
                                    f32, i64, vp, f32, vp, sz, vp, vp, vp]
+    L.grass_step_cols_workspace.argtypes = [i64, i64, i64, i64, i32]
+    L.grass_step_cols_workspace.restype = sz
+    L.grass_step_cols.argtypes = [vp, i64, vp, i64, i32, i64, i64, i64, i64, vp, vp, vp, i64, vp, vp,
+                                  i32, vp, vp, i32, i64, f32, f32, f32, f32, i64, f32, vp, sz, vp,
+                                  vp, vp]
     L.grass_dense_workspace.argtypes = [i64, i64, i64, i32, i32]
     L.grass_dense_workspace.restype = sz
     L.grass_dense_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, i32, i64, vp,
@@ -102,7 +108,8 @@ def lib():
     for name in EXPORTS:
         if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
                         "grass_dense_workspace", "grass_grad_row_stats_workspace",
-                        "grass_cgrad_group_workspace", "grass_step_group_workspace"):
+                        "grass_cgrad_group_workspace", "grass_step_group_workspace",
+                        "grass_step_cols_workspace"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -291,6 +298,35 @@ def step_group(dYs, X, idxs, rhos, Ms, Vs, Ws, lr, beta1, beta2, eps, t, alpha, 
     _check(lib().grass_step_group(count, arr, layout, pX, ldx, _dtype(X), T, n, sdt, wdt, lr, beta1,
                                   beta2, eps, t, sc, alpha, wp, wb, _stream(), e0, e1),
            "grass_step_group")
+
+
+def step_cols_workspace(T, m, n, r, dtype) -> int:
+    return int(lib().grass_step_cols_workspace(T, m, n, r, dtype))
+
+
+def step_cols(dY, X, idx, rho, M, V, U, W, lr, beta1, beta2, eps, t, alpha, ws, GC=None,
+              gemm_events=None):
+    """The regular step with r of the n COLUMNS of W selected (dY T x m, X T x n, state r x m)
+    in one call; GC: optional r x m tensor that receives the compressed gradient."""
+    pY, T, m, ldy = _mat(dY)
+    pX, Tx, n, ldx = _mat(X)
+    assert Tx == T and dY.dtype == X.dtype
+    r = idx.shape[0]
+    pW, mw, nw, ldw = _mat(W)
+    assert (mw, nw) == (m, n)
+    pM, pV, sdt = _moments(M, V, r, m)
+    assert U.shape == (r, m) and U.is_contiguous() and U.dtype == torch.float32 and U.is_cuda
+    pG, ldgc = None, 0
+    if GC is not None:
+        pG, gr, gcols, ldgc = _mat(GC)
+        assert (gr, gcols) == (r, m) and GC.dtype == torch.float32
+    wp, wb = _ws(ws)
+    e0, e1 = ((C.c_void_p(e.cuda_event) for e in gemm_events) if gemm_events is not None
+              else (None, None))
+    _check(lib().grass_step_cols(pY, ldy, pX, ldx, _dtype(X), T, m, n, r, _vec(idx, torch.int32),
+                                 _vec(rho, torch.float32), pG, ldgc, pM, pV, sdt,
+                                 C.c_void_p(U.data_ptr()), pW, _dtype(W), ldw, lr, beta1, beta2, eps,
+                                 t, alpha, wp, wb, _stream(), e0, e1), "grass_step_cols")
 
 
 def adam_rows(GC, M, V, lr, beta1, beta2, eps, t, U):

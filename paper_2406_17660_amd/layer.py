@@ -60,9 +60,12 @@ class GrassLayer:
         self.sumsq = torch.empty(m, dtype=torch.float32, device=dev)
         self.ws_sel = grass.workspace(grass.select_workspace(m, r, self.method, replacement), dev)
         # one workspace serves both the separate calls and the one-call step
-        self.ws_gemm = grass.workspace(max(grass.cgrad_workspace(T, m, n, r, self.dt, layout),
-                                           grass.step_group_workspace(T, n, [r], self.dt, layout)),
-                                       dev)
+        ws_bytes = max(grass.cgrad_workspace(T, m, n, r, self.dt, layout),
+                       grass.step_group_workspace(T, n, [r], self.dt, layout))
+        if side == "cols":  # (m, n are those of the transposed problem here)
+            ws_bytes = max(ws_bytes, grass.step_cols_workspace(T, n, m, r, self.dt))
+            self.U = torch.empty((r, n), dtype=torch.float32, device=dev)  # Adam's output
+        self.ws_gemm = grass.workspace(ws_bytes, dev)
         self.store_GC = store_GC  # False: the one-call step does not write G_C at all
         self.ws_dense = None  # allocated on first refresh: only refresh steps need it
         self.G = None
@@ -132,8 +135,6 @@ class GrassLayer:
             return grass.adam_scatter_replayable(self.GC, self.M, self.V, a.beta1, a.beta2, a.eps,
                                                  step_scalars, W, self.idx, self.rho, self.alpha)
         if self.side == "cols":  # Adam on r x m, then the update of r columns of W
-            if not hasattr(self, "U"):
-                self.U = torch.empty_like(self.GC)
             grass.adam_rows(self.GC, self.M, self.V, a.lr, a.beta1, a.beta2, a.eps, self.adam_t,
                             self.U)
             return grass.scatter_update_cols(W, self.idx, self.rho, self.alpha, self.U)
@@ -141,16 +142,16 @@ class GrassLayer:
                                   self.adam_t, W, self.idx, self.rho, self.alpha)
 
     def step(self, dY, X, W, gemm_events=None):
-        """The regular step.  Row selection: one library call (grass_step_group) in which the
-        reduction of the product, Adam and the row update are one kernel.  Column selection:
-        the three separate calls."""
-        if self.side == "cols":
-            self.compressed_grad(dY, X, gemm_events)
-            self.adam_scatter(W)
-            return
+        """The regular step in one library call (grass_step_group, or grass_step_cols when
+        columns are selected): the reduction of the product and Adam are one kernel, which
+        for selected rows also updates W."""
         self.adam_t += 1
         a = self.adam
         assert tuple(W.shape) == self.w_shape
+        if self.side == "cols":
+            return grass.step_cols(dY, X, self.idx, self.rho, self.M, self.V, self.U, W, a.lr, a.beta1,
+                                   a.beta2, a.eps, self.adam_t, self.alpha, self.ws_gemm,
+                                   GC=self.GC if self.store_GC else None, gemm_events=gemm_events)
         grass.step_group([dY], X, [self.idx], [self.rho], [self.M], [self.V], [W], a.lr, a.beta1,
                          a.beta2, a.eps, self.adam_t, self.alpha, self.ws_gemm, self.layout,
                          GCs=[self.GC] if self.store_GC else None, gemm_events=gemm_events)

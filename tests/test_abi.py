@@ -261,6 +261,36 @@ def test_step_group_validation():
     assert a >= b + 2 * 256 * 512 * 4  # room for a G_C per layer that does not name one
 
 
+def test_step_cols_validation():
+    L = grass.lib()
+    f = L.grass_step_cols
+    T, m, n, r = 128, 64, 32, 8
+    big_ws = 1 << 30
+    ok = dict(dY=FAKE, ldy=m, X=FAKE, ldx=n, dt=grass.BF16, T=T, m=m, n=n, r=r, idx=FAKE, rho=FAKE,
+              GC=None, ldgc=0, M=FAKE, V=FAKE, sdt=grass.F32, U=FAKE, W=FAKE, wdt=grass.BF16, ldw=n,
+              lr=1e-3, b1=0.9, b2=0.999, eps=1e-8, t=1, alpha=0.25, ws=FAKE, ws_bytes=big_ws,
+              stream=None, e0=None, e1=None)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(*a.values())
+    assert grass.step_cols_workspace(T, m, n, r, grass.BF16) >= r * m * 4
+    assert grass.step_cols_workspace(T, m, n, 70000, grass.BF16) == 0
+    assert call(dY=None) == grass.ERR_NULL
+    assert call(U=None) == grass.ERR_NULL
+    assert call(W=None) == grass.ERR_NULL
+    assert call(ldw=n - 1) == grass.ERR_SHAPE
+    assert call(ldy=m - 1) == grass.ERR_SHAPE
+    assert call(GC=FAKE, ldgc=m - 1) == grass.ERR_SHAPE
+    assert call(r=70000) == grass.ERR_SHAPE
+    assert call(t=0) == grass.ERR_SHAPE
+    assert call(U=C.c_void_p(FAKE.value + 4)) == grass.ERR_SHAPE  # 16-byte aligned scratch
+    assert call(wdt=5) == grass.ERR_DTYPE
+    assert call(sdt=5) == grass.ERR_DTYPE
+    assert call(ws=None) == grass.ERR_WORKSPACE
+    assert call(ws_bytes=16) == grass.ERR_WORKSPACE
+
+
 def test_probe_validation():
     import ctypes as C
     f = grass.lib().grass_probe_mfma_rate

@@ -899,3 +899,45 @@ def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
     got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
     want = ref.compressed_grad(np.ascontiguousarray(to_np(dY)), to_np(X), idx, rho)
     assert rel_fro(got, want) <= 2e-5
+
+
+@pytest.mark.parametrize("sdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,m,n,r,dup,want_gc,tile", [
+    (512, 688, 256, 64, True, True, None),      # gate/up-shaped, duplicates
+    (300, 130, 50, 17, False, False, None),     # nothing divides anything (m % 4 != 0: separate kernels)
+    (1056, 520, 264, 260, True, False, "256"),  # large tile
+    (4096, 64, 32, 8, False, True, None),       # many K slices for a small output
+])
+def test_step_cols_equals_the_separate_calls_and_the_oracle(monkeypatch, sdtype, T, m, n, r, dup, want_gc, tile):
+    """The column-form step in one call against the oracle (compressed gradient of the exchanged
+    operands, Adam on r x m, update of r columns of W)."""
+    if tile:
+        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    dY = randn((T, m), torch.bfloat16, 201, scale=0.1)
+    X = randn((T, n), torch.bfloat16, 202)
+    idx, rho = make_idx(n, r, 203, dup)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    _, M, V = adam_inputs(r, m, 204, m)
+    M, V = M.to(sdtype).contiguous(), V.to(sdtype).contiguous()
+    M0, V0 = to_f64(M).copy(), to_f64(V).copy()
+    W = randn((m, n), torch.bfloat16, 207, scale=0.02)
+    W0, W0_bits = to_f64(W).copy(), to_np(W).copy()
+    U = torch.full((r, m), float("nan"), device=DEV)
+    GC = torch.full((r, m), float("nan"), device=DEV) if want_gc else None
+    ws = grass.workspace(grass.step_cols_workspace(T, m, n, r, grass.BF16))
+    grass.step_cols(dY, X, d_idx, d_rho, M, V, U, W, LR, B1, B2, EPS, 3, 0.25, ws, GC=GC)
+    f = np.float32
+    want_gc_ref = ref.compressed_grad(to_np(X), to_np(dY), idx, rho)  # r x m
+    if want_gc:
+        assert rel_fro(to_f64(GC), want_gc_ref) <= 2e-5
+    Uo = ref.adam_rows(want_gc_ref, M0, V0, float(f(LR)), float(f(B1)), float(f(B2)), float(f(EPS)), 3,
+                       state_bf16=sdtype == torch.bfloat16)
+    Wo = W0.copy()
+    ref.scatter_update_cols(Wo, idx, rho, 0.25, Uo)
+    state_tol = 1e-2 if sdtype == torch.bfloat16 else 2e-5
+    assert rel_fro(to_f64(M), M0) <= state_tol and rel_fro(to_f64(V), V0) <= state_tol
+    assert rel_fro(to_f64(U), Uo) <= (5e-2 if sdtype == torch.bfloat16 else 1e-3)
+    sel = np.unique(idx)
+    assert rel_fro(to_f64(W)[:, sel], Wo[:, sel]) <= TOL_BF16
+    rest = np.setdiff1d(np.arange(n), sel)
+    assert np.array_equal(to_np(W)[:, rest], W0_bits[:, rest])
