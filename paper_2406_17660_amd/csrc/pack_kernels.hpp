@@ -89,11 +89,11 @@ __global__ __launch_bounds__(256) void pack_txm_group_kernel(PackSets sets, int6
 }
 
 // The same gather for wide matrices, with the rows of dY staged through LDS: a workgroup copies
-// kPackStageRows whole rows of t into LDS with streaming 16-byte loads (every byte of dY is
+// kRows whole rows of t into LDS with streaming 16-byte loads (every byte of dY is
 // fetched exactly once, by a full-width request, and is not kept in the caches), then gathers
 // from LDS and stores the panel rows with streaming 8-byte stores.  Measured at the 7B layer
 // against the kernel above: 0.21 instead of 0.24 ms (1.34 GB at 6.3 TB/s); one row per
-// workgroup is slower than the kernel above, two to eight rows differ little.
+// workgroup is slower than the kernel above at m = 4096, two to eight rows differ little.
 // Needs m % 8 == 0, 16-byte aligned rows of dY, and kRows * m * 2 bytes of LDS.  Two rows per
 // workgroup while three workgroups still fit a compute unit's LDS (m <= 12288), one row beyond
 // (at m = 13824 two rows, 55 KB, leave two workgroups per compute unit and lose to the kernel above).
