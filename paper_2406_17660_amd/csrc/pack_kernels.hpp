@@ -212,35 +212,36 @@ __global__ __launch_bounds__(256) void pack_mxt_wide_kernel(const uint16_t* __re
     }
 }
 
-// out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np even, rows of `out` np apart): a copy
-// of a matrix whose rows start at odd element offsets (n not a multiple of 8, as in the
-// 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM can take.  `in` itself
-// is 4-byte aligned.  A thread moves one 32-bit pair at a time; a row that starts in the upper
-// half of an aligned word is read as two words and shifted.
+// out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np a multiple of 8, rows of `out` np
+// apart and 16-byte aligned): a copy of a matrix whose rows start at odd element offsets (n not a
+// multiple of 8, as in the 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM
+// can take.  `in` itself is 4-byte aligned.  A thread produces four consecutive 32-bit pairs
+// (one streaming 16-byte store) from aligned 32-bit loads; a row that starts in the upper half of
+// an aligned word is read one word further and shifted.
 __global__ __launch_bounds__(256) void align_rows_kernel(const uint16_t* __restrict__ in, int64_t ld,
                                                          int64_t n, int64_t np, int chunks,
                                                          uint16_t* __restrict__ out) {
     const int64_t t = blockIdx.x / chunks;
     const int chunk = blockIdx.x % chunks;
+    const int64_t d0 = static_cast<int64_t>(chunk) * 1024 + threadIdx.x * 4;  // first pair of this thread
+    if (2 * d0 >= np) return;  // np % 8 == 0: four whole pairs or none
     const uint16_t* row = in + t * ld;
     const uintptr_t a = reinterpret_cast<uintptr_t>(row);
     const bool upper = (a & 2) != 0;
     const uint32_t* w = reinterpret_cast<const uint32_t*>(a - (upper ? 2 : 0));
-    uint32_t* o = reinterpret_cast<uint32_t*>(out + t * np);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 v;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int64_t d = static_cast<int64_t>(chunk) * 1024 + i * 256 + threadIdx.x;
-        const int64_t c = 2 * d;
-        if (c >= np) break;
-        uint32_t v;
+        const int64_t d = d0 + i, c = 2 * d;
         if (upper ? c + 2 < n : c + 1 < n) {  // every word touched lies inside the row
-            v = upper ? (w[d] >> 16) | (w[d + 1] << 16) : w[d];
+            v[i] = upper ? (w[d] >> 16) | (w[d + 1] << 16) : w[d];
         } else {
             const uint32_t lo = c < n ? row[c] : 0u, hi = c + 1 < n ? row[c + 1] : 0u;
-            v = lo | (hi << 16);
+            v[i] = lo | (hi << 16);
         }
-        o[d] = v;
     }
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + t * np) + d0 / 4);
 }
 
 
