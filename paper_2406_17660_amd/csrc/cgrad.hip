@@ -337,7 +337,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     // launch sizes are checked before the first launch: a refused call has done nothing
     const int64_t items = static_cast<int64_t>(p.tiles_m) * p.tiles_n * p.splits;
     const int64_t chunk = (items + kNumXcd - 1) / kNumXcd;
-    const int x_chunks = static_cast<int>((nb / 2 + 1023) / 1024);
+    const int x_chunks = static_cast<int>((nb / 8 + 255) / 256);  // workgroups per row of the aligning copy
     if (chunk * kNumXcd > 0x7FFFFFFF || (copy_x && T * x_chunks > 0x7FFFFFFF)) return GRASS_ERR_SHAPE;
 
     GemmArgs g;
@@ -434,7 +434,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     if (copy_x) {
         uint16_t* xa = reinterpret_cast<uint16_t*>(base + p.pack_bytes + round_up(p.partial_bytes, 256));
         align_rows_kernel<<<static_cast<unsigned>(T * x_chunks), 256, 0, s>>>(
-            static_cast<const uint16_t*>(X), ldx, n, nb, x_chunks, xa);
+            static_cast<const uint16_t*>(X), ldx, T, n, nb, x_chunks, xa);
         g.B = xa;
         g.ldb = nb;
         g.Ncols = nb;

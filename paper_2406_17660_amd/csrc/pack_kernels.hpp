@@ -215,33 +215,51 @@ __global__ __launch_bounds__(256) void pack_mxt_wide_kernel(const uint16_t* __re
 // out[t, c] = in[t, c] for c < n and 0 for n <= c < np (np a multiple of 8, rows of `out` np
 // apart and 16-byte aligned): a copy of a matrix whose rows start at odd element offsets (n not a
 // multiple of 8, as in the 5461-wide MLP of the 1B model) into rows the 16-byte loads of the GEMM
-// can take.  `in` itself is 4-byte aligned.  A thread produces four consecutive 32-bit pairs
-// (one streaming 16-byte store) from aligned 32-bit loads; a row that starts in the upper half of
-// an aligned word is read one word further and shifted.
+// can take.  `in` itself is 4-byte aligned, so a row starts e = 0, 2, ..., 14 bytes after a
+// 16-byte boundary.  A thread produces 8 output elements (one streaming 16-byte store) from the
+// two aligned 16-byte vectors that contain them: with e = 4 k + b, output word i is input word
+// k + i of that 32-byte window, or the upper half of it joined to the lower half of the next
+// (b = 2).  k and b are the same for a whole row, i.e. for the whole workgroup.  Vectors that
+// would reach outside [lo, hi) (the bytes of the matrix: the start of the first row, the end of
+// the last) or past column n are put together element by element.
 __global__ __launch_bounds__(256) void align_rows_kernel(const uint16_t* __restrict__ in, int64_t ld,
-                                                         int64_t n, int64_t np, int chunks,
+                                                         int64_t T, int64_t n, int64_t np, int chunks,
                                                          uint16_t* __restrict__ out) {
-    const int64_t t = blockIdx.x / chunks;
-    const int chunk = blockIdx.x % chunks;
-    const int64_t d0 = static_cast<int64_t>(chunk) * 1024 + threadIdx.x * 4;  // first pair of this thread
-    if (2 * d0 >= np) return;  // np % 8 == 0: four whole pairs or none
-    const uint16_t* row = in + t * ld;
-    const uintptr_t a = reinterpret_cast<uintptr_t>(row);
-    const bool upper = (a & 2) != 0;
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(a - (upper ? 2 : 0));
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int64_t t = blockIdx.x / chunks;
+    const int64_t q = static_cast<int64_t>(blockIdx.x % chunks) * 256 + threadIdx.x;  // 8 elements each
+    if (8 * q >= np) return;
+    const uint16_t* row = in + t * ld;
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(in);
+    const uintptr_t hi = lo + static_cast<uintptr_t>(((T - 1) * ld + n) * 2);
+    const uintptr_t start = reinterpret_cast<uintptr_t>(row), e = start & 15;
+    const uintptr_t window = (start - e) + 16 * static_cast<uintptr_t>(q);
     u32x4 v;
+    if (8 * q + 8 <= n && window >= lo && window + 32 <= hi) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(window);
+        const u32x4 a = src[0], b = src[1];
+        const uint32_t w[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+        const bool half = (e & 2) != 0;
+        auto take = [&](int k) {  // k is a constant at every call site
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t d = d0 + i, c = 2 * d;
-        if (upper ? c + 2 < n : c + 1 < n) {  // every word touched lies inside the row
-            v[i] = upper ? (w[d] >> 16) | (w[d + 1] << 16) : w[d];
-        } else {
-            const uint32_t lo = c < n ? row[c] : 0u, hi = c + 1 < n ? row[c + 1] : 0u;
-            v[i] = lo | (hi << 16);
+            for (int i = 0; i < 4; ++i)
+                v[i] = half ? (w[k + i] >> 16) | (w[k + i + 1] << 16) : w[k + i];
+        };
+        switch (e >> 2) {  // uniform over the workgroup
+            case 0: take(0); break;
+            case 1: take(1); break;
+            case 2: take(2); break;
+            default: take(3); break;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t c = 8 * q + 2 * i;
+            const uint32_t l = c < n ? row[c] : 0u, h = c + 1 < n ? row[c + 1] : 0u;
+            v[i] = l | (h << 16);
         }
     }
-    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + t * np) + d0 / 4);
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + t * np) + q);
 }
 
 
