@@ -343,10 +343,14 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     GemmArgs g;
     if (pack) {
         // T x m storage, wide rows: staged through LDS (streaming loads of whole rows)
+        // measured on the 60M to 1B layer shapes: from 1024 elements per row on the staged form
+        // wins (3 - 15 %), at 512 it loses 20 %; the number of selected rows matters little
+        const int64_t min_width = getenv("GRASS_PACK_STAGE_MIN_WIDTH") ? atoll(getenv("GRASS_PACK_STAGE_MIN_WIDTH")) : 64;
+        const int64_t min_m = getenv("GRASS_PACK_STAGE_MIN_M") ? atoll(getenv("GRASS_PACK_STAGE_MIN_M")) : 1024;
         auto staged = [&](int i, int64_t width) {
             const int64_t m_src = seg[i].src_rows;
-            return layout == GRASS_DY_TxM && m_src >= 2048 && m_src <= kPackStageMaxM &&
-                   width >= 512 && m_src % 8 == 0 && seg[i].ldy % 8 == 0 && aligned_to(seg[i].dY, 16);
+            return layout == GRASS_DY_TxM && m_src >= min_m && width >= min_width &&
+                   pack_stage_row_elems(m_src) * 2 <= kPackStageMaxBytes;
         };
         auto threads_per_row_log2 = [](int64_t width) {
             int tpr_log2 = 8;  // the power of two covering width / 4
@@ -386,13 +390,12 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                 if (staged(i, width)) {
                     // wide rows: staged through LDS (streaming loads of whole rows)
                     const auto* src = static_cast<const uint16_t*>(seg[i].dY);
+                    const size_t row_bytes = static_cast<size_t>(pack_stage_row_elems(m_src)) * 2;
                     if (m_src <= kPackStageTwoRowsMaxM)
-                        pack_txm_staged_kernel<2><<<static_cast<unsigned>((T + 1) / 2), 256,
-                                                    static_cast<size_t>(m_src) * 4, s>>>(
+                        pack_txm_staged_kernel<2><<<static_cast<unsigned>((T + 1) / 2), 256, 2 * row_bytes, s>>>(
                             src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                     else
-                        pack_txm_staged_kernel<1><<<static_cast<unsigned>(T), 256,
-                                                    static_cast<size_t>(m_src) * 2, s>>>(
+                        pack_txm_staged_kernel<1><<<static_cast<unsigned>(T), 256, row_bytes, s>>>(
                             src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                 } else if (layout == GRASS_DY_TxM) {
                     const int tpr_log2 = threads_per_row_log2(width);

@@ -89,34 +89,63 @@ __global__ __launch_bounds__(256) void pack_txm_group_kernel(PackSets sets, int6
 }
 
 // The same gather for wide matrices, with the rows of dY staged through LDS: a workgroup copies
-// kRows whole rows of t into LDS with streaming 16-byte loads (every byte of dY is
-// fetched exactly once, by a full-width request, and is not kept in the caches), then gathers
-// from LDS and stores the panel rows with streaming 8-byte stores.  Measured at the 7B layer
-// against the kernel above: 0.21 instead of 0.24 ms (1.34 GB at 6.3 TB/s); one row per
-// workgroup is slower than the kernel above at m = 4096, two to eight rows differ little.
-// Needs m % 8 == 0, 16-byte aligned rows of dY, and kRows * m * 2 bytes of LDS.  Two rows per
-// workgroup while three workgroups still fit a compute unit's LDS (m <= 12288), one row beyond
-// (at m = 13824 two rows, 55 KB, leave two workgroups per compute unit and lose to the kernel above).
-constexpr int64_t kPackStageTwoRowsMaxM = 12288, kPackStageMaxM = 32768;
+// kRows whole rows of t into LDS with streaming 16-byte loads (every byte of dY is fetched
+// exactly once, by a full-width request, and is not kept in the caches), then gathers from LDS
+// and stores the panel rows with streaming 8-byte stores.  Measured at the 7B layer against
+// the kernel above: 0.21 instead of 0.24 ms (1.34 GB at 6.3 TB/s); one row per workgroup is
+// slower than the kernel above at m = 4096, two to eight rows differ little.
+// Rows need no alignment: a row that starts e bytes after a 16-byte boundary is copied as the
+// aligned vectors that cover it and lands in LDS with the same e, which the gather adds to its
+// indices.  Vectors that would reach outside [lo, hi), the bytes of the matrix (the first of the
+// first row, the last of the last), are put together element by element.
+// LDS: kRows * pack_stage_row_elems(m) * 2 bytes.  Two rows per workgroup while three workgroups
+// still fit a compute unit's LDS (m <= 12288), one row beyond (at m = 13824 two rows, 55 KB,
+// leave two workgroups per compute unit and lose to the kernel above).
+constexpr int64_t kPackStageTwoRowsMaxM = 12288, kPackStageMaxBytes = 65536;
+__host__ __device__ constexpr int64_t pack_stage_row_elems(int64_t m) {
+    return ((2 * m + 14 + 15) / 16) * 8;  // the most 16-byte vectors a row of m elements can touch
+}
 template <int kRows>
 __global__ __launch_bounds__(256) void pack_txm_staged_kernel(const uint16_t* __restrict__ dY,
                                                               int64_t ldy, int64_t T, int64_t m,
                                                               const int32_t* __restrict__ idx,
                                                               int64_t r, int64_t rp, int64_t ldo,
                                                               uint16_t* __restrict__ out) {
-    extern __shared__ __attribute__((aligned(16))) uint16_t stage[];  // kRows x m
+    extern __shared__ __attribute__((aligned(16))) uint16_t stage[];  // kRows x pack_stage_row_elems(m)
     const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kRows;
-    const int vec_per_row = static_cast<int>(m / 8);
-    for (int c = threadIdx.x; c < vec_per_row; c += 256) {
+    const int64_t stride = pack_stage_row_elems(m);
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(dY);
+    const uintptr_t hi = lo + static_cast<uintptr_t>(((T - 1) * ldy + m) * 2);
+    uintptr_t window[kRows];  // 16-byte aligned start of the vectors covering each row
+    int shift[kRows];         // elements between it and the row's first element
+    int nvec = 0;
+#pragma unroll
+    for (int row = 0; row < kRows; ++row) {
+        const int64_t t = t0 + row < T ? t0 + row : T - 1;  // a row past the end is not used
+        const uintptr_t start = reinterpret_cast<uintptr_t>(dY + t * ldy), e = start & 15;
+        window[row] = start - e;
+        shift[row] = static_cast<int>(e >> 1);
+        const int v = static_cast<int>((e + 2 * static_cast<uintptr_t>(m) + 15) >> 4);
+        nvec = v > nvec ? v : nvec;
+    }
+    for (int c = threadIdx.x; c < nvec; c += 256) {
         s16x8 x[kRows];
 #pragma unroll
         for (int row = 0; row < kRows; ++row) {
-            const int64_t t = t0 + row < T ? t0 + row : T - 1;  // a row past the end is not used
-            x[row] = __builtin_nontemporal_load(reinterpret_cast<const s16x8*>(dY + t * ldy) + c);
+            const uintptr_t addr = window[row] + 16 * static_cast<uintptr_t>(c);
+            if (addr >= lo && addr + 16 <= hi) {
+                x[row] = __builtin_nontemporal_load(reinterpret_cast<const s16x8*>(addr));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uintptr_t a = addr + 2 * i;
+                    x[row][i] = a >= lo && a + 2 <= hi ? *reinterpret_cast<const short*>(a) : short{0};
+                }
+            }
         }
 #pragma unroll
         for (int row = 0; row < kRows; ++row)
-            *reinterpret_cast<s16x8*>(stage + static_cast<int64_t>(row) * m + c * 8) = x[row];
+            *reinterpret_cast<s16x8*>(stage + row * stride + c * 8) = x[row];
     }
     __syncthreads();
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -128,7 +157,7 @@ __global__ __launch_bounds__(256) void pack_txm_staged_kernel(const uint16_t* __
 #pragma unroll
         for (int row = 0; row < kRows; ++row) {
             if (t0 + row >= T) break;
-            const uint16_t* src = stage + static_cast<int64_t>(row) * m;
+            const uint16_t* src = stage + row * stride + shift[row];
             uint16_t v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = col[e] >= 0 ? src[col[e]] : static_cast<uint16_t>(0);

@@ -880,14 +880,19 @@ def test_compressed_grad_millions_of_tokens(layout, T):
 
 
 @pytest.mark.parametrize("T,m,n,r,dup,pad,shift", [
-    (257, 2048, 64, 512, False, 0, 0),     # smallest shape that takes the staged gather; odd T
+    (257, 1024, 64, 64, False, 0, 0),      # smallest shape that takes the staged gather; odd T
+    (257, 1016, 64, 64, False, 0, 0),      # one step narrower / (next) one selected row fewer: plain
+    (257, 1024, 64, 56, False, 0, 0),
     (130, 5464, 72, 600, True, 8, 0),      # row length not a power of two, padded rows, duplicates
+    (131, 5461, 72, 600, True, 0, 0),      # odd row length: every row starts at another byte offset
     (67, 12288, 64, 1500, True, 0, 0),     # the longest rows staged two at a time
     (65, 12296, 64, 700, False, 0, 0),     # one step longer: one row per workgroup
-    (34, 32768, 64, 900, True, 0, 0),      # the longest rows that are staged at all
-    (33, 32776, 64, 600, False, 0, 0),     # one step longer: the plain gather
-    (96, 4096, 128, 1024, False, 8, 1),    # rows that are not 16-byte aligned: the plain gather
+    (34, 32760, 64, 900, True, 0, 0),      # the longest rows that are staged at all (64 KB of LDS)
+    (33, 32768, 64, 600, False, 3, 0),     # one step longer: the plain gather
+    (96, 4096, 128, 1024, False, 8, 1),    # rows that start 2 bytes after a 16-byte boundary
+    (96, 4099, 128, 1024, True, 2, 5),     # odd everything
     (1, 4096, 64, 512, False, 0, 0),       # a single row of t
+    (2, 2051, 64, 300, False, 0, 3),       # the first and the last vector of the matrix are partial
 ])
 def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
     """Wide T x m gradients: the gather copies whole rows of dY into LDS first.  Shapes on both
