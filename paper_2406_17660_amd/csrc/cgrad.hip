@@ -391,11 +391,14 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                     // wide rows: staged through LDS (streaming loads of whole rows)
                     const auto* src = static_cast<const uint16_t*>(seg[i].dY);
                     const size_t row_bytes = static_cast<size_t>(pack_stage_row_elems(m_src)) * 2;
-                    if (m_src <= kPackStageTwoRowsMaxM)
-                        pack_txm_staged_kernel<2><<<static_cast<unsigned>((T + 1) / 2), 256, 2 * row_bytes, s>>>(
+                    if (m_src < kPackStageDeepMinM)
+                        pack_txm_staged_kernel<2, 1><<<static_cast<unsigned>((T + 1) / 2), 256, 2 * row_bytes, s>>>(
+                            src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
+                    else if (m_src <= kPackStageTwoRowsMaxM)
+                        pack_txm_staged_kernel<2, 4><<<static_cast<unsigned>((T + 1) / 2), 256, 2 * row_bytes, s>>>(
                             src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                     else
-                        pack_txm_staged_kernel<1><<<static_cast<unsigned>(T), 256, row_bytes, s>>>(
+                        pack_txm_staged_kernel<1, 4><<<static_cast<unsigned>(T), 256, row_bytes, s>>>(
                             src, seg[i].ldy, T, m_src, seg[i].idx, seg[i].rows, width, p.rp, panel + off);
                 } else if (layout == GRASS_DY_TxM) {
                     const int tpr_log2 = threads_per_row_log2(width);
