@@ -270,8 +270,8 @@ def main():
                                f"refresh every {REFRESH_EVERY} steps",
                    "m": m, "n": n, "T": T, "r": r},
         "roofline": {"bound": "mfma",
-                     "kernel": ("tn_gemm_bf16_direct_kernel<false, false, true>" if args.layout == "mxt"
-                                else "tn_gemm_bf16_direct_kernel<false, false, false>") + " (compressed-gradient GEMM)",
+                     "kernel": ("tn_gemm_bf16_direct_kernel<false, false, true, true>" if args.layout == "mxt"
+                                else "tn_gemm_bf16_direct_kernel<false, false, false, false>") + " (compressed-gradient GEMM)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS,
                      "traffic": measured_traffic(L.name, T) if args.layout == "txm" else None,
