@@ -32,6 +32,10 @@
  *   - r = 0, n = 0 or T = 0 are legal where they make sense (see each call) and
  *     produce the empty / zero result.  Every size (T, m, n, r) is below 2^31;
  *     GRASS_ERR_SHAPE (0 from a workspace query) beyond that.
+ *   - Index arrays (idx) live in device memory, so their VALUES cannot be validated
+ *     before the launch: every entry must lie inside the dimension it indexes
+ *     (grass_select_rows writes such arrays).  Entries outside it make the kernels
+ *     read or write outside the caller's buffers.
  *   - No call records a memset or an event (the _timed call excepted) or allocates, so
  *     calls can be captured into a HIP graph.
  */
