@@ -28,6 +28,21 @@ def test_header_and_library_agree():
         assert hasattr(L, name), name
 
 
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """include/grass.h stands on its own as C99 and as C++11 (no torch or HIP types in it)."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for compiler, std, ext in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "cpp")):
+        if shutil.which(compiler) is None:
+            pytest.skip(f"{compiler} not installed")
+        src = tmp_path / f"use_header.{ext}"
+        src.write_text('#include "include/grass.h"\nint main(void) { return (int)GRASS_OK; }\n')
+        r = subprocess.run([compiler, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                            "-I", root, str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
 def test_status_strings():
     seen = {grass.status_string(c) for c in range(7)}
     assert len(seen) == 7 and "ok" in seen
