@@ -916,10 +916,18 @@ def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
 def test_step_cols_equals_the_separate_calls_and_the_oracle(monkeypatch, sdtype, T, m, n, r, dup, want_gc, tile):
     """The column-form step in one call against the oracle (compressed gradient of the exchanged
     operands, Adam on r x m, update of r columns of W)."""
+    run_step_cols(monkeypatch, torch.bfloat16, sdtype, T, m, n, r, dup, want_gc, tile)
+
+
+def test_step_cols_fp32_inputs(monkeypatch):
+    run_step_cols(monkeypatch, torch.float32, torch.float32, 300, 130, 50, 17, True, True, None)
+
+
+def run_step_cols(monkeypatch, dtype, sdtype, T, m, n, r, dup, want_gc, tile):
     if tile:
         monkeypatch.setenv("GRASS_GEMM_TILE", tile)
-    dY = randn((T, m), torch.bfloat16, 201, scale=0.1)
-    X = randn((T, n), torch.bfloat16, 202)
+    dY = randn((T, m), dtype, 201, scale=0.1)
+    X = randn((T, n), dtype, 202)
     idx, rho = make_idx(n, r, 203, dup)
     d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
     _, M, V = adam_inputs(r, m, 204, m)
@@ -929,7 +937,8 @@ def test_step_cols_equals_the_separate_calls_and_the_oracle(monkeypatch, sdtype,
     W0, W0_bits = to_f64(W).copy(), to_np(W).copy()
     U = torch.full((r, m), float("nan"), device=DEV)
     GC = torch.full((r, m), float("nan"), device=DEV) if want_gc else None
-    ws = grass.workspace(grass.step_cols_workspace(T, m, n, r, grass.BF16))
+    dt = grass.F32 if dtype == torch.float32 else grass.BF16
+    ws = grass.workspace(max(grass.step_cols_workspace(T, m, n, r, dt), 16))
     grass.step_cols(dY, X, d_idx, d_rho, M, V, U, W, LR, B1, B2, EPS, 3, 0.25, ws, GC=GC)
     f = np.float32
     want_gc_ref = ref.compressed_grad(to_np(X), to_np(dY), idx, rho)  # r x m
