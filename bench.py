@@ -290,9 +290,10 @@ def main():
         vals = torch.randn(32768, generator=g, device=dev)
         left = (torch.arange(32768, device=dev) // 2048) % 8 < 4
         vals = torch.where(left, vals * 0.1, vals).to(torch.bfloat16)
-        probe = grass.probe_mfma_rate(source=grass.PROBE_CONSTANTS)
-        probe_regs = grass.probe_mfma_rate(source=grass.PROBE_REGISTERS, operands=vals)
-        probe_lds = grass.probe_mfma_rate(source=grass.PROBE_LDS, operands=vals)
+        from paper_2406_17660_amd import probe as mfma_probe  # measurement aid, a library of its own
+        probe = mfma_probe.mfma_rate(source=mfma_probe.CONSTANTS)
+        probe_regs = mfma_probe.mfma_rate(source=mfma_probe.REGISTERS, operands=vals)
+        probe_lds = mfma_probe.mfma_rate(source=mfma_probe.LDS, operands=vals)
         out["roofline"]["mfma_only_kernel_tflops_this_box"] = probe
         out["roofline"]["mfma_only_kernel_normal_operands_tflops"] = probe_regs
         out["roofline"]["mfma_plus_lds_reads_kernel_normal_operands_tflops"] = probe_lds

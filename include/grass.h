@@ -16,16 +16,22 @@
  *
  * Conventions that hold for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller, unless the
- *     argument is documented as a host value.  The library allocates no memory and
- *     keeps no state between calls; scratch memory is sized by the *_workspace
- *     queries and passed in by the caller.
+ *     argument is documented as a host value.  The library allocates no memory;
+ *     scratch memory is sized by the *_workspace queries and passed in by the caller.
+ *     It keeps no state that a result depends on.  What it does keep, per process: one
+ *     flag per device and kernel recording that the kernel's LDS limit has been raised
+ *     (set once, atomically), and the test hooks of grass_set_test_option (initially
+ *     off).
  *   - Matrices are row-major with an explicit leading dimension counted in
  *     ELEMENTS (ld >= number of columns).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     work is enqueued on it; no call synchronises with the host.
  *   - Arguments are validated on the host before anything is launched.  A call
- *     that returns anything but GRASS_OK has launched nothing and written nothing.
- *     A pointer may be NULL only when the array it names has no elements.
+ *     that returns an argument error (NULL, SHAPE, DTYPE, WORKSPACE) has launched
+ *     nothing and written nothing.  GRASS_ERR_DEVICE reports a launch the HIP runtime
+ *     refused; kernels the call enqueued before it still run, and the outputs are
+ *     then unspecified.  A pointer may be NULL only when the array it names has no
+ *     elements.
  *   - Calls that walk the compressed rows in the grid (compressed_grad,
  *     scatter_update, adam_scatter, gather_rows, dense_grad's m) accept at most
  *     65535 rows and return GRASS_ERR_SHAPE beyond that.
@@ -142,6 +148,18 @@ grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64
                                    int64_t m, int64_t n, int64_t r, const int32_t* idx,
                                    const float* rho, float* GC, int64_t ldgc, void* ws,
                                    size_t ws_bytes, void* stream);
+
+/* How the product above is planned for a panel of `rows` gathered rows (r for one matrix; for
+ * a group call the sum of its r[i], each rounded up to a multiple of 8): `*tile` receives the
+ * edge of the output tile (256, 128, or 64 for fp32 inputs) and `*k_slices` the number of
+ * slices the token dimension is split into (their partial products are what the split-K
+ * reduction, or the fused tail of grass_step_group / grass_step_cols, adds up; above 8 slices
+ * those kernels spread the slices over the wavefronts of a workgroup).  A pure host function,
+ * for callers that want to know what a shape costs and for tests that must reach every kernel.
+ * Operands whose base or leading dimension is not 16-byte aligned fall back to the 128 tile at
+ * launch whatever this reports.  Errors: NULL, SHAPE, DTYPE. */
+grass_status grass_cgrad_plan(int64_t T, int64_t n, int64_t rows, grass_dtype dt,
+                              grass_dy_layout layout, int* tile, int* k_slices);
 
 /* grass_compressed_grad with a timing hook: the two hipEvent_t handles (passed as
  * void*, either may be NULL) are recorded on `stream` immediately before and after
@@ -364,33 +382,26 @@ grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* 
                                            void* stream);
 
 /* ---------------------------------------------------------------------------
- * Measurement aid (not a step of the method; for benchmarks that want to state what the
- * matrix cores of the machine at hand sustain).  Launches a kernel that does nothing but
- * issue the bf16 matrix instruction of the compressed-gradient GEMM on every compute unit:
- * 256 workgroups x 4 wavefronts x `iters` x 32 instructions, no global memory traffic inside
- * the loop.  The clock the chip sustains under this load depends on what the instructions
- * are fed, hence three operand sources:
- *   GRASS_PROBE_CONSTANTS  small constants held in registers (`operands` is not read);
- *   GRASS_PROBE_REGISTERS  the caller's values, two sets of eight fragments held in
- *                          registers and used alternately;
- *   GRASS_PROBE_LDS        the caller's values staged in LDS once; every group of 16
- *                          instructions reads its eight fragments from there (16 bytes per
- *                          lane and fragment: the LDS read traffic of the GEMM).
- * `operands` (device, 16-byte aligned, at least 65536 bytes, `operand_bytes` says how many):
- * bf16 values; thread t of a workgroup takes elements [(256 f + t) 8, +8) as fragment f = 0..15,
- * fragments 0-3 and 8-11 on the left side of the products, 4-7 and 12-15 on the right.
- * `out` (device, at least 65536 floats, `out_floats` says how many) receives one value per
- * thread so that the work cannot be optimised away; `*flops` (host) receives the number of
- * floating-point operations the launch performs.  The caller times the launch on `stream`.
- * Errors: NULL, DTYPE (unknown source), SHAPE (iters < 1, a buffer too small or misaligned). */
+ * Test hooks.  The launchers choose their kernels from the shapes and alignments of a call;
+ * tests need to reach every kernel with small inputs, so a process-wide override exists for
+ * each such choice.  value 0 (the initial state) leaves the choice to the library.  The
+ * overrides are read when a call or a workspace query plans its launches: change them only
+ * while no other thread is inside the library, and query workspaces after setting them.
+ *   GRASS_TEST_GEMM_TILE     128 or 256: the matrix-multiply tile (the large tile still falls
+ *                            back to the small one where alignment rules it out)
+ *   GRASS_TEST_FUSED_STATS   1: grass_grad_row_stats takes the squares in the GEMM epilogue
+ *                            whenever the shape allows, not only when the tiles fill the machine
+ *   GRASS_TEST_PACK_MXT      1: dY stored m x T goes through the packing pass instead of the
+ *                            row-gathering GEMM
+ *   GRASS_TEST_NO_PAIRS      1: the row-gathering GEMM loads one K tile per request
+ * Errors: DTYPE for an unknown option. */
 typedef enum {
-    GRASS_PROBE_CONSTANTS = 0,
-    GRASS_PROBE_REGISTERS = 1,
-    GRASS_PROBE_LDS = 2
-} grass_probe_source;
-grass_status grass_probe_mfma_rate(grass_probe_source source, const void* operands,
-                                   size_t operand_bytes, float* out, size_t out_floats, int iters,
-                                   double* flops, void* stream);
+    GRASS_TEST_GEMM_TILE = 0,
+    GRASS_TEST_FUSED_STATS = 1,
+    GRASS_TEST_PACK_MXT = 2,
+    GRASS_TEST_NO_PAIRS = 3
+} grass_test_option;
+grass_status grass_set_test_option(grass_test_option option, int value);
 
 #ifdef __cplusplus
 }

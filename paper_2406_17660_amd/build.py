@@ -1,7 +1,8 @@
-"""Build paper_2406_17660_amd/libgrass.so from csrc/*.hip with hipcc for gfx950.
+"""Build paper_2406_17660_amd/libgrass.so from csrc/*.hip with hipcc for gfx950, and the
+benchmark's measurement aid probe/libgrass_probe.so from probe/*.hip.
 
-The library is built in-tree so that it travels with the source tree; tests, the smoke
-check and the benchmark only load it.
+The libraries are built in-tree so that they travel with the source tree; tests, the smoke
+check and the benchmark only load them.
 """
 import os
 import subprocess
@@ -12,6 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgrass.so")
+PROBE_DIR = os.path.join(HERE, "probe")
+PROBE_LIB = os.path.join(PROBE_DIR, "libgrass_probe.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
@@ -19,8 +22,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-ffp-contract=on"]
 
 
-def sources():
-    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+def sources(folder=CSRC):
+    return sorted(os.path.join(folder, f) for f in os.listdir(folder) if f.endswith(".hip"))
 
 
 def _compile(src: str) -> str:
@@ -35,17 +38,25 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every .hip file (always: this is also the 'does it build' check) and link."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as pool:
-        objs = list(pool.map(_compile, sources()))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    res = subprocess.run(cmd, capture_output=True, text=True)
+def _link(lib: str, objs) -> None:
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs],
+                         capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every .hip file (always: this is also the 'does it build' check) and link the
+    two libraries."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    lib_src, probe_src = sources(CSRC), sources(PROBE_DIR)
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        objs = list(pool.map(_compile, lib_src + probe_src))
+    _link(LIB, objs[:len(lib_src)])
+    _link(PROBE_LIB, objs[len(lib_src):])
     if verbose:
         print(LIB)
+        print(PROBE_LIB)
     return LIB
 
 

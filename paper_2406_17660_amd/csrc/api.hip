@@ -2,11 +2,16 @@
 // kernel launchers.  Validation touches no device memory and makes no HIP call, so a call
 // that fails validation has no side effect (and can be exercised on a machine without a
 // GPU).
+#include <atomic>
+
 #include "common.hpp"
 
 using namespace grass;
 
 namespace {
+
+constexpr int kNumTestOptions = 4;
+std::atomic<int> g_test_options[kNumTestOptions];  // zero-initialised: the library decides
 
 constexpr int64_t kMaxGridRows = 65535;  // rows are carried in blockIdx.y
 
@@ -49,6 +54,12 @@ grass_status check_rows_of_w(const void* W, grass_dtype wdt, int64_t m, int64_t 
 }
 
 }  // namespace
+
+namespace grass {
+int test_option(grass_test_option which) {
+    return g_test_options[which].load(std::memory_order_relaxed);
+}
+}  // namespace grass
 
 extern "C" {
 
@@ -101,6 +112,16 @@ size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_d
     (void)m;
     if (T < 0 || n < 0 || r < 0 || !small(T) || !small(n) || !small(r)) return 0;
     return gemm_workspace_bytes(T, r, n, dt, layout, true);
+}
+
+grass_status grass_cgrad_plan(int64_t T, int64_t n, int64_t rows, grass_dtype dt,
+                              grass_dy_layout layout, int* tile, int* k_slices) {
+    if (!tile || !k_slices) return GRASS_ERR_NULL;
+    if (T < 0 || n < 0 || rows < 0 || !small(T) || !small(n) || rows > kMaxGridRows)
+        return GRASS_ERR_SHAPE;
+    if (!dtype_ok(dt) || !layout_ok(layout)) return GRASS_ERR_DTYPE;
+    gemm_plan_summary(T, rows, n, dt, layout, tile, k_slices);
+    return GRASS_OK;
 }
 
 grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64_t ldy,
@@ -399,20 +420,11 @@ grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_
     return launch_gather_rows(G, gdt, n, ldg, idx, rho, r, out, ldo, as_stream(stream));
 }
 
-grass_status grass_probe_mfma_rate(grass_probe_source source, const void* operands,
-                                   size_t operand_bytes, float* out, size_t out_floats, int iters,
-                                   double* flops, void* stream) {
-    if (!out || !flops) return GRASS_ERR_NULL;
-    if (source < GRASS_PROBE_CONSTANTS || source > GRASS_PROBE_LDS) return GRASS_ERR_DTYPE;
-    if (source != GRASS_PROBE_CONSTANTS) {
-        if (!operands) return GRASS_ERR_NULL;
-        if (operand_bytes < static_cast<size_t>(kProbeOperandBytes) || !aligned_to(operands, 16))
-            return GRASS_ERR_SHAPE;
-    }
-    if (iters < 1 || out_floats < static_cast<size_t>(kProbeWorkgroups) * 256) return GRASS_ERR_SHAPE;
-    // 4 wavefronts per workgroup, 32 instructions of 32 x 32 x 16 multiply-adds per iteration
-    *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * iters * 32.0 * (2.0 * 32 * 32 * 16);
-    return launch_probe_mfma_rate(static_cast<int>(source), operands, out, iters, as_stream(stream));
+grass_status grass_set_test_option(grass_test_option option, int value) {
+    const int which = static_cast<int>(option);
+    if (which < 0 || which >= kNumTestOptions) return GRASS_ERR_DTYPE;
+    g_test_options[which].store(value, std::memory_order_relaxed);
+    return GRASS_OK;
 }
 
 }  // extern "C"

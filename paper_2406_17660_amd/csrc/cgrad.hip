@@ -22,6 +22,8 @@
 //              converts to the output dtype; in a regular step this, Adam and the update of
 //              the rows of W are one kernel that reads the partial tiles directly.
 // fp32 path: a plain LDS-tiled FMA kernel (small reference-precision configurations).
+#include <atomic>
+
 #include "common.hpp"
 
 #include "gemm_common.hpp"
@@ -104,7 +106,7 @@ size_t aligned_x_bytes(int64_t T, int64_t n) {
 // The 256 x 256 tile halves the LDS traffic per flop and is the faster kernel whenever it
 // does not waste much of itself on padding; narrow problems (r = 128, say) keep 128 x 128.
 TileId choose_tile(int64_t T, int64_t rows, int64_t n) {
-    if (const char* e = getenv("GRASS_GEMM_TILE")) return atoi(e) == 256 ? kTile256 : kTile128;
+    if (const int forced = test_option(GRASS_TEST_GEMM_TILE)) return forced == 256 ? kTile256 : kTile128;
     (void)T;
     if (rows < 1 || n < 1) return kTile128;
     const double padded = static_cast<double>((rows + 255) / 256 * 256) * ((n + 255) / 256 * 256);
@@ -119,16 +121,18 @@ template <typename Cfg, bool kDense>
 hipError_t launch_gemm_kernel(const GemmArgs& g, unsigned grid, hipStream_t s) {
     auto kernel = tn_gemm_bf16_kernel<Cfg, kDense>;
     if (Cfg::kLdsBytes > 64 * 1024) {
-        // per instantiation and device; the attribute sticks for the life of the process
-        static bool raised[64] = {};
+        // per instantiation and device; the attribute sticks for the life of the process, so it
+        // is set once (the only state the library keeps: a flag per device, set with release
+        // order after the attribute call has returned; two first callers both make the call)
+        static std::atomic<bool> raised[64];
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
-        if (dev < 0 || dev >= 64 || !raised[dev]) {
+        if (dev < 0 || dev >= 64 || !raised[dev].load(std::memory_order_acquire)) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      static_cast<int>(Cfg::kLdsBytes));
             if (e != hipSuccess) return e;
-            if (dev >= 0 && dev < 64) raised[dev] = true;
+            if (dev >= 0 && dev < 64) raised[dev].store(true, std::memory_order_release);
         }
     }
     kernel<<<grid, Cfg::kThreads, Cfg::kLdsBytes, s>>>(g);
@@ -140,8 +144,8 @@ bool fused_stats_shape_ok(int64_t T, int64_t m, int64_t n, grass_dtype dt, grass
     // the squares need complete sums, so the fused form cannot split K: it only pays when the
     // output tiles alone fill most of the 256 compute units
     const int64_t tiles = ((m + kFastBM - 1) / kFastBM) * ((n + kFastBN - 1) / kFastBN);
-    const char* force = getenv("GRASS_FUSED_STATS");  // "1": whenever the shape allows (tests)
-    return (tiles >= 192 || (force && force[0] == '1')) && dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kFastBK &&
+    const bool force = test_option(GRASS_TEST_FUSED_STATS) == 1;  // whenever the shape allows
+    return (tiles >= 192 || force) && dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kFastBK &&
            T % kFastBK == 0 &&
            m >= 8 && n >= 8 && m % 8 == 0 && n % 8 == 0 && ldy % 8 == 0 && ldx % 8 == 0 &&
            (kFastBK + 1) * ldy * 2 < (int64_t{1} << 32) && (kFastBK + 1) * ldx * 2 < (int64_t{1} << 32);
@@ -212,6 +216,26 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
     const Plan a = plan_for(kTile128, T, mrows, n, pack), b = plan_for(kTile256, T, mrows, n, pack);
     const size_t wa = a.pack_bytes + a.partial_bytes, wb = b.pack_bytes + b.partial_bytes;
     return (wa > wb ? wa : wb) + aligned_x_bytes(T, n) + 256;
+}
+
+void gemm_plan_summary(int64_t T, int64_t rows, int64_t n, grass_dtype dt, grass_dy_layout layout,
+                       int* tile, int* k_slices) {
+    if (dt == GRASS_F32) {  // the fp32 kernel: 64 x 64 tiles, K not split
+        *tile = 64;
+        *k_slices = 1;
+        return;
+    }
+    const TileId id = T >= kFastBK && rows >= 8 && n >= 8 ? choose_tile(T, rows, n) : kTile128;
+    Plan p = plan_for(id, T, rows, n, needs_pack(layout, true, rows));
+    if (id == kTile256 && layout == GRASS_DY_MxT && T % (2 * kFastBK) == 0 &&
+        test_option(GRASS_TEST_PACK_MXT) == 0 && test_option(GRASS_TEST_NO_PAIRS) == 0 &&
+        p.ktiles_per_split % 2 != 0) {  // the row-gathering kernel takes K tiles in pairs
+        ++p.ktiles_per_split;
+        p.splits = static_cast<int>((T / kFastBK + p.ktiles_per_split - 1) / p.ktiles_per_split);
+    }
+    *tile = id == kTile256 ? 256 : 128;
+    // the large tile takes whole K tiles; a ragged tail of T is one more slice
+    *k_slices = p.splits + (id == kTile256 && T % kFastBK != 0 ? 1 : 0);
 }
 
 size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
@@ -315,13 +339,13 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     // itself (no packing pass) when K is whole tiles and its 32-bit row offsets reach every row
     bool a_rows_form = false;
     if (tile == kTile256 && layout == GRASS_DY_MxT && count == 1 && T % kFastBK == 0 &&
-        aligned_to(dY0, 16) && ldy0 % 8 == 0 && getenv("GRASS_GEMM_PACK_MXT") == nullptr) {
+        aligned_to(dY0, 16) && ldy0 % 8 == 0 && test_option(GRASS_TEST_PACK_MXT) == 0) {
         const int64_t src_rows = seg[0].idx ? seg[0].src_rows : total;
         a_rows_form = src_rows > 0 && src_rows * ldy0 * 2 + 128 < (int64_t{1} << 32);
     }
     if (a_rows_form) pack = false;
     // whole cache lines per row (64 values of k per load) when the K tiles pair up
-    const bool a_pairs = a_rows_form && T % (2 * kFastBK) == 0 && getenv("GRASS_GEMM_NO_PAIRS") == nullptr;
+    const bool a_pairs = a_rows_form && T % (2 * kFastBK) == 0 && test_option(GRASS_TEST_NO_PAIRS) == 0;
     // the large-tile kernel takes whole K tiles; a ragged tail goes to the small-tile kernel
     const int64_t T_main = tile == kTile256 ? T / kFastBK * kFastBK : T;
     Plan p = plan_for(tile, T, total, n, pack);  // sized for all T rows; K tiling per tile kind
@@ -345,8 +369,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         // T x m storage, wide rows: staged through LDS (streaming loads of whole rows)
         // measured on the 60M to 1B layer shapes: from 1024 elements per row on the staged form
         // wins (3 - 15 %), at 512 it loses 20 %; the number of selected rows matters little
-        const int64_t min_width = getenv("GRASS_PACK_STAGE_MIN_WIDTH") ? atoll(getenv("GRASS_PACK_STAGE_MIN_WIDTH")) : 64;
-        const int64_t min_m = getenv("GRASS_PACK_STAGE_MIN_M") ? atoll(getenv("GRASS_PACK_STAGE_MIN_M")) : 1024;
+        constexpr int64_t min_width = 64, min_m = 1024;
         auto staged = [&](int i, int64_t width) {
             const int64_t m_src = seg[i].src_rows;
             return layout == GRASS_DY_TxM && m_src >= min_m && width >= min_width &&

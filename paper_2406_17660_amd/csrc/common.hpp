@@ -69,6 +69,9 @@ inline grass_status launch_status() {
 
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// Value of a test hook (grass_set_test_option): 0 unless a test has forced a code path.
+int test_option(grass_test_option which);
+
 // Kernel launchers, one per translation unit.  All pointers are device pointers; shapes
 // have been validated by the C entry points in api.hip before these are called.
 grass_status launch_row_stats(const void* G, grass_dtype dt, int64_t m, int64_t n, int64_t ldg,
@@ -102,19 +105,14 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
 // dense: idx = rho = nullptr).  Output dtype odt, leading dimension ldc.
 size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
                             grass_dy_layout layout, bool gathered);
+// Tile edge and number of K slices the launcher plans for a gathered panel of `rows` rows.
+void gemm_plan_summary(int64_t T, int64_t rows, int64_t n, grass_dtype dt, grass_dy_layout layout,
+                       int* tile, int* k_slices);
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
                             const int32_t* idx, const float* rho, void* C, grass_dtype odt,
                             int64_t ldc, void* ws, hipStream_t s, int64_t src_rows,
                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
-
-// Measurement aid: kProbeWorkgroups workgroups of 256 threads, each wavefront issuing
-// 32 * iters matrix instructions; `out` takes kProbeWorkgroups * 256 floats; `operands` (sources
-// 1 and 2) holds kProbeOperandBytes of bf16 values.
-constexpr int kProbeWorkgroups = 256;
-constexpr int kProbeOperandBytes = 65536;
-grass_status launch_probe_mfma_rate(int source, const void* operands, float* out, int iters,
-                                    hipStream_t s);
 
 // What follows the compressed gradient in a regular step (Adam on r x n, update of the rows of
 // W).  Given to the GEMM launcher, the split-K reduction, Adam and the update run as one kernel

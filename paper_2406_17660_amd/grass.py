@@ -19,6 +19,7 @@ F32, BF16 = 0, 1
 SEL_TOPR, SEL_UNIFORM, SEL_MULTI_NORM, SEL_MULTI_NORM2 = 0, 1, 2, 3
 SCALE_PAPER, SCALE_ONE, SCALE_INV_SQRT_RQ = 0, 1, 2
 DY_TxM, DY_MxT = 0, 1
+TEST_GEMM_TILE, TEST_FUSED_STATS, TEST_PACK_MXT, TEST_NO_PAIRS = 0, 1, 2, 3
 
 EXPORTS = [
     "grass_status_string", "grass_row_stats", "grass_select_workspace", "grass_select_rows",
@@ -27,7 +28,8 @@ EXPORTS = [
     "grass_adam_scatter", "grass_dense_workspace", "grass_dense_grad", "grass_gather_rows",
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
-    "grass_adam_rows_state", "grass_adam_scatter_state", "grass_probe_mfma_rate",
+    "grass_adam_rows_state", "grass_adam_scatter_state", "grass_cgrad_plan",
+    "grass_set_test_option",
     "grass_adam_step_scalars", "grass_adam_scatter_replayable",
     "grass_step_group_workspace", "grass_step_group",
     "grass_step_cols_workspace", "grass_step_cols",
@@ -100,7 +102,8 @@ def lib():
     L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
     L.grass_grad_row_stats_workspace.restype = sz
     L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
-    L.grass_probe_mfma_rate.argtypes = [i32, vp, sz, vp, sz, i32, C.POINTER(C.c_double), vp]
+    L.grass_cgrad_plan.argtypes = [i64, i64, i64, i32, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    L.grass_set_test_option.argtypes = [i32, i32]
     L.grass_cgrad_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
     L.grass_cgrad_group_workspace.restype = sz
     L.grass_compressed_grad_group.argtypes = [i32, vp, i32, vp, vp, i64, i32, i64, vp, i64, vp,
@@ -196,6 +199,19 @@ def select_status(ws) -> int:
 
 def cgrad_workspace(T, m, n, r, dtype, layout=DY_TxM) -> int:
     return int(lib().grass_cgrad_workspace(T, m, n, r, dtype, layout))
+
+
+def cgrad_plan(T, n, rows, dtype, layout=DY_TxM):
+    """(tile edge, number of K slices) the library plans for a gathered panel of `rows` rows."""
+    tile, slices = C.c_int(0), C.c_int(0)
+    _check(lib().grass_cgrad_plan(T, n, rows, dtype, layout, C.byref(tile), C.byref(slices)),
+           "grass_cgrad_plan")
+    return tile.value, slices.value
+
+
+def set_test_option(option: int, value: int):
+    """Test hook: force one of the launcher's choices (0 gives it back to the library)."""
+    _check(lib().grass_set_test_option(option, value), "grass_set_test_option")
 
 
 def compressed_grad(dY, X, idx, rho, GC, ws, layout=DY_TxM, gemm_events=None):
@@ -450,30 +466,3 @@ def gather_rows(G, idx, rho, out):
 def workspace(nbytes: int, device="cuda"):
     """A device byte buffer of at least `nbytes` (torch owns the memory)."""
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
-
-
-PROBE_CONSTANTS, PROBE_REGISTERS, PROBE_LDS = 0, 1, 2
-
-
-def probe_mfma_rate(iters=10000, source=PROBE_CONSTANTS, operands=None):
-    """TFLOP/s of a kernel that only issues the GEMM's bf16 matrix instruction on every compute
-    unit (measurement aid: what the matrix cores of this machine sustain under that load).
-    `operands`: at least 32768 bf16 values on the device for the sources that take the caller's
-    values (held in registers, or read from LDS like the GEMM's operand fragments)."""
-    out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-    flops = C.c_double(0.0)
-    ptr, nbytes = (None, 0) if operands is None else (C.c_void_p(operands.data_ptr()),
-                                                      operands.numel() * operands.element_size())
-
-    def launch():
-        _check(lib().grass_probe_mfma_rate(source, ptr, nbytes, C.c_void_p(out.data_ptr()),
-                                           out.numel(), iters, C.byref(flops), _stream()),
-               "grass_probe_mfma_rate")
-    for _ in range(3):  # the clock settles over the first launches
-        launch()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    launch()
-    b.record()
-    torch.cuda.synchronize()
-    return flops.value / (a.elapsed_time(b) * 1e-3) / 1e12

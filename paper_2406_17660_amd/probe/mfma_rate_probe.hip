@@ -1,4 +1,5 @@
-// grass_probe_mfma_rate: a measurement aid, not a step of the method.
+// mfma_rate_probe: a measurement aid for the benchmark, not a step of the method and not part
+// of the GRASS library (it is built into a library of its own, libgrass_probe.so).
 //
 // What the matrix cores of THIS machine sustain when a kernel does nothing but issue
 // v_mfma_f32_32x32x16_bf16 (the instruction of the compressed-gradient GEMM) on every compute
@@ -13,15 +14,19 @@
 //                  its eight fragments from there, 16 bytes per lane and fragment, which is the
 //                  LDS read traffic of the GEMM (no global memory traffic in the loop)
 // The benchmark reports these next to the GEMM's own rate.
-#include "common.hpp"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace grass {
+#include "mfma_rate_probe.h"
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+constexpr int kProbeWorkgroups = 256;
+constexpr int kProbeOperandBytes = 65536;
 constexpr int kPoolElems = kProbeOperandBytes / 2;
 
 // One wavefront per SIMD (4 per workgroup, one workgroup per compute unit), 16 independent
@@ -109,13 +114,23 @@ void mfma_rate_kernel(const uint16_t* __restrict__ pool, float* __restrict__ out
 
 }  // namespace
 
-grass_status launch_probe_mfma_rate(int source, const void* operands, float* out, int iters,
-                                    hipStream_t s) {
+extern "C" int mfma_rate_probe(int source, const void* operands, size_t operand_bytes, float* out,
+                               size_t out_floats, int iters, double* flops, void* stream) {
+    if (!out || !flops) return MFMA_PROBE_ERR_NULL;
+    if (source < MFMA_PROBE_CONSTANTS || source > MFMA_PROBE_LDS) return MFMA_PROBE_ERR_SOURCE;
+    if (source != MFMA_PROBE_CONSTANTS) {
+        if (!operands) return MFMA_PROBE_ERR_NULL;
+        if (operand_bytes < static_cast<size_t>(kProbeOperandBytes) ||
+            reinterpret_cast<uintptr_t>(operands) % 16 != 0)
+            return MFMA_PROBE_ERR_SIZE;
+    }
+    if (iters < 1 || out_floats < static_cast<size_t>(kProbeWorkgroups) * 256) return MFMA_PROBE_ERR_SIZE;
+    // 4 wavefronts per workgroup, 32 instructions of 32 x 32 x 16 multiply-adds per iteration
+    *flops = static_cast<double>(kProbeWorkgroups) * 4.0 * iters * 32.0 * (2.0 * 32 * 32 * 16);
     const uint16_t* pool = static_cast<const uint16_t*>(operands);
+    hipStream_t s = static_cast<hipStream_t>(stream);
     if (source == 0) mfma_rate_kernel<0><<<kProbeWorkgroups, 256, 0, s>>>(pool, out, iters);
     else if (source == 1) mfma_rate_kernel<1><<<kProbeWorkgroups, 256, 0, s>>>(pool, out, iters);
     else mfma_rate_kernel<2><<<kProbeWorkgroups, 256, 0, s>>>(pool, out, iters);
-    return launch_status();
+    return hipGetLastError() == hipSuccess ? MFMA_PROBE_OK : MFMA_PROBE_ERR_DEVICE;
 }
-
-}  // namespace grass

@@ -22,3 +22,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _library_decides_again_after_each_test():
+    """Tests force code paths through grass_set_test_option; whatever a test set is cleared
+    when it ends, so that no test depends on the one before it."""
+    yield
+    from paper_2406_17660_amd import grass
+    if grass._lib is not None:
+        for option in (grass.TEST_GEMM_TILE, grass.TEST_FUSED_STATS, grass.TEST_PACK_MXT,
+                       grass.TEST_NO_PAIRS):
+            grass.set_test_option(option, 0)

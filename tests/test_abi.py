@@ -306,24 +306,47 @@ def test_step_cols_validation():
     assert call(ws_bytes=16) == grass.ERR_WORKSPACE
 
 
-def test_probe_validation():
-    import ctypes as C
-    f = grass.lib().grass_probe_mfma_rate
+def test_probe_library_validation():
+    """The benchmark's measurement aid lives in a library and header of its own."""
+    from paper_2406_17660_amd import probe
+    f = probe.lib().mfma_rate_probe
     flops = C.c_double(0.0)
     ok = (0, None, 0, FAKE, 1 << 16, 10, C.byref(flops), None)
 
     def call(**kw):
         names = ("source", "operands", "operand_bytes", "out", "out_floats", "iters", "flops", "stream")
         return f(*[kw.get(n, v) for n, v in zip(names, ok)])
-    assert call(out=None) == grass.ERR_NULL
-    assert call(flops=None) == grass.ERR_NULL
-    assert call(iters=0) == grass.ERR_SHAPE
-    assert call(out_floats=1000) == grass.ERR_SHAPE
-    assert call(source=3) == grass.ERR_DTYPE
-    for source in (grass.PROBE_REGISTERS, grass.PROBE_LDS):  # these read the caller's values
-        assert call(source=source) == grass.ERR_NULL
-        assert call(source=source, operands=FAKE, operand_bytes=65535) == grass.ERR_SHAPE
-        assert call(source=source, operands=C.c_void_p(FAKE.value + 2), operand_bytes=65536) == grass.ERR_SHAPE
+    assert call(out=None) == probe.ERR_NULL
+    assert call(flops=None) == probe.ERR_NULL
+    assert call(iters=0) == probe.ERR_SIZE
+    assert call(out_floats=1000) == probe.ERR_SIZE
+    assert call(source=3) == probe.ERR_SOURCE
+    for source in (probe.REGISTERS, probe.LDS):  # these read the caller's values
+        assert call(source=source) == probe.ERR_NULL
+        assert call(source=source, operands=FAKE, operand_bytes=65535) == probe.ERR_SIZE
+        assert call(source=source, operands=C.c_void_p(FAKE.value + 2), operand_bytes=65536) == probe.ERR_SIZE
+    assert not hasattr(grass.lib(), "grass_probe_mfma_rate") and not hasattr(grass.lib(), "mfma_rate_probe")
+
+
+def test_plan_query_and_test_options():
+    """grass_cgrad_plan is a pure host function; the test hooks change what it reports."""
+    assert grass.cgrad_plan(131072, 4096, 1024, grass.BF16) == (256, 4)
+    tile, slices = grass.cgrad_plan(65536, 512, 128, grass.BF16)
+    assert tile == 128 and slices > 8  # the short, wide problems of the small models
+    assert grass.cgrad_plan(512, 256, 16, grass.F32) == (64, 1)
+    assert grass.cgrad_plan(1056, 264, 260, grass.BF16)[0] == 128
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
+    try:
+        assert grass.cgrad_plan(1056, 264, 260, grass.BF16)[0] == 256
+    finally:
+        grass.set_test_option(grass.TEST_GEMM_TILE, 0)
+    assert grass.cgrad_plan(1056, 264, 260, grass.BF16)[0] == 128
+    L = grass.lib()
+    assert L.grass_set_test_option(17, 1) == grass.ERR_DTYPE
+    t, k = C.c_int(0), C.c_int(0)
+    assert L.grass_cgrad_plan(64, 64, 8, grass.BF16, 0, None, C.byref(k)) == grass.ERR_NULL
+    assert L.grass_cgrad_plan(-1, 64, 8, grass.BF16, 0, C.byref(t), C.byref(k)) == grass.ERR_SHAPE
+    assert L.grass_cgrad_plan(64, 64, 8, 7, 0, C.byref(t), C.byref(k)) == grass.ERR_DTYPE
 
 
 def test_grad_row_stats_validation():

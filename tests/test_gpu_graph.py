@@ -61,7 +61,8 @@ def test_matrix_core_probe_reports_plausible_rates():
     g = torch.Generator(device="cuda")
     g.manual_seed(5)
     operands = torch.randn(32768, generator=g, device="cuda").to(torch.bfloat16)
-    rates = [grass.probe_mfma_rate(2000, source, operands)
-             for source in (grass.PROBE_CONSTANTS, grass.PROBE_REGISTERS, grass.PROBE_LDS)]
+    from paper_2406_17660_amd import probe
+    rates = [probe.mfma_rate(2000, source, operands)
+             for source in (probe.CONSTANTS, probe.REGISTERS, probe.LDS)]
     assert all(250.0 < r < 2600.0 for r in rates), rates
     assert rates[1] < 1.1 * rates[0] and rates[2] < 1.1 * rates[0], rates

@@ -307,9 +307,9 @@ def test_adam_scatter_empty():
     (4100, 600, 264, 257, False),    # one row past a tile boundary, narrow n, T tail of 4 rows
     (96, 300, 512, 256, False),      # fewer K tiles than ring stages
 ])
-def test_compressed_grad_large_tile_kernel(monkeypatch, layout, T, m, n, r, dup):
+def test_compressed_grad_large_tile_kernel(layout, T, m, n, r, dup):
     """The 256 x 256 load-to-LDS kernel, forced for shapes small enough for a full oracle."""
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     dY = randn((T, m), torch.bfloat16, 11, scale=0.1)
     X = randn((T, n), torch.bfloat16, 12)
     idx, rho = make_idx(m, r, 13, dup)
@@ -323,8 +323,8 @@ def test_compressed_grad_large_tile_kernel(monkeypatch, layout, T, m, n, r, dup)
 
 
 @pytest.mark.parametrize("T,m,n", [(1000, 520, 264), (2048, 512, 768)])
-def test_dense_grad_large_tile_kernel(monkeypatch, T, m, n):
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+def test_dense_grad_large_tile_kernel(T, m, n):
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     dY = randn((T, m), torch.bfloat16, 15, scale=0.1)
     X = randn((T, n), torch.bfloat16, 16)
     G = gpu_dense(dY, X, torch.float32)
@@ -358,12 +358,12 @@ def test_compressed_grad_large_tile_chosen_by_shape():
     (torch.float32, grass.DY_TxM, 512, 256, 256, 0),       # fp32 inputs: via fp32 G
 ])
 @pytest.mark.parametrize("force_fused", [True, False])
-def test_grad_row_stats_without_storing_G(monkeypatch, force_fused, dtype, layout, T, m, n, pad):
+def test_grad_row_stats_without_storing_G(force_fused, dtype, layout, T, m, n, pad):
     """The fused form is chosen by itself only for layers with enough output tiles to fill
     the machine; here it is forced so that small shapes exercise it, and the same shapes also
     run the way the launcher would choose (fp32 G inside the workspace, then the statistic)."""
     if force_fused:
-        monkeypatch.setenv("GRASS_FUSED_STATS", "1")
+        grass.set_test_option(grass.TEST_FUSED_STATS, 1)
     dY = randn((T, m), dtype, 31, scale=0.1, ld=m + pad)
     X = randn((T, n), dtype, 32, ld=n + pad)
     dY_dev = dY if layout == grass.DY_TxM else dY.t().contiguous()
@@ -414,9 +414,9 @@ def test_scatter_update_cols(wdtype, m, n, r, dup, ldw):
 
 
 @pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 192, 224, 256, 288, 1056])
-def test_large_tile_kernel_every_pipeline_length(monkeypatch, T):
+def test_large_tile_kernel_every_pipeline_length(T):
     """1 to 9 and 33 K tiles per workgroup: prologue, steady state and drain of the LDS ring."""
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     m, n, r = 300, 264, 260
     dY = randn((T, m), torch.bfloat16, 71, scale=0.1)
     X = randn((T, n), torch.bfloat16, 72)
@@ -439,10 +439,10 @@ def test_large_tile_kernel_every_pipeline_length(monkeypatch, T):
     (130, 64, (2048, 300), (512, 40), None),            # a wide set next to a narrow one: separate gathers
     (257, 72, (520, 264, 1376), (128, 40, 200), None),  # narrow sets: one gather launch for all
 ])
-def test_compressed_grad_group_matches_per_matrix_oracle(monkeypatch, dtype, layout, T, n, ms, rs, tile):
+def test_compressed_grad_group_matches_per_matrix_oracle(dtype, layout, T, n, ms, rs, tile):
     """Several matrices sharing X (q, k, v): every output equals the single-matrix definition."""
     if tile:
-        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     X = randn((T, n), dtype, 20)
     dYs, idxs, rhos, host = [], [], [], []
     for i, (m, r) in enumerate(zip(ms, rs)):
@@ -473,9 +473,9 @@ def test_compressed_grad_group_matches_per_matrix_oracle(monkeypatch, dtype, lay
     (777, 130, 334, 129, 340, 0),     # even n that is not a multiple of 8
     (64, 40, 9, 40, 9, 0),            # fewer columns than one 16-byte chunk and a half
 ])
-def test_compressed_grad_with_activations_that_break_16_byte_rows(monkeypatch, tile, T, m, n, r, ldx, xoff):
+def test_compressed_grad_with_activations_that_break_16_byte_rows(tile, T, m, n, r, ldx, xoff):
     """X whose rows cannot be read in aligned 16-byte chunks is first copied into padded rows."""
-    monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+    grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     dY = randn((T, m), torch.bfloat16, 51, scale=0.1)
     flat = randn((1, T * ldx + xoff), torch.bfloat16, 52)[0]
     X = flat[xoff:xoff + T * ldx].view(T, ldx)[:, :n]
@@ -489,10 +489,10 @@ def test_compressed_grad_with_activations_that_break_16_byte_rows(monkeypatch, t
 
 
 @pytest.mark.parametrize("T,m,n", [(1056, 301, 531), (520, 1365, 264), (96, 13, 9)])
-def test_dense_grad_with_unaligned_widths_on_the_large_tile(monkeypatch, T, m, n):
+def test_dense_grad_with_unaligned_widths_on_the_large_tile(T, m, n):
     """Full gradient when neither m nor n is a multiple of 8: dY goes through the packing
     pass with the identity selection, X through the aligning copy."""
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     dY = randn((T, m), torch.bfloat16, 55, scale=0.1)
     X = randn((T, n), torch.bfloat16, 56)
     G = gpu_dense(dY, X, torch.float32)
@@ -566,14 +566,14 @@ def test_fused_adam_scatter_with_bf16_moments(wdtype, m, n, r, dup):
 # ------------------------------------------------------------------------------ dY stored m x T
 @pytest.mark.parametrize("pairs", [True, False])
 @pytest.mark.parametrize("T", [32, 64, 96, 128, 160, 192, 224, 256, 320, 384, 448, 1056, 1088])
-def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T, pairs):
+def test_row_gathering_gemm_every_pipeline_length(T, pairs):
     """dY stored m x T with T a whole number of K tiles: the large-tile kernel gathers the
     selected rows itself (no packing pass); prologue, steady loop and drain at every length.
     An even number of K tiles takes the form that loads 64 values of k per row and request
     (unless switched off), an odd one the form with one load per K tile."""
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     if not pairs:
-        monkeypatch.setenv("GRASS_GEMM_NO_PAIRS", "1")
+        grass.set_test_option(grass.TEST_NO_PAIRS, 1)
     m, n, r = 300, 264, 260
     dY = randn((T, m), torch.bfloat16, 71, scale=0.1)
     X = randn((T, n), torch.bfloat16, 72)
@@ -594,8 +594,8 @@ def test_row_gathering_gemm_every_pipeline_length(monkeypatch, T, pairs):
     (8192, 600, 264, 8, 0),        # a handful of rows, several K slices
     (16384 + 64, 520, 264, 300, 0),  # K slices of an odd number of K tiles, rounded up to pairs
 ])
-def test_row_gathering_gemm_shapes_and_agreement_with_packing(monkeypatch, T, m, n, r, pad):
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+def test_row_gathering_gemm_shapes_and_agreement_with_packing(T, m, n, r, pad):
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     dYt = randn((m, T), torch.bfloat16, 75, scale=0.1, ld=T + pad)
     X = randn((T, n), torch.bfloat16, 76)
     idx, rho = make_idx(m, r, 77, False)
@@ -605,14 +605,14 @@ def test_row_gathering_gemm_shapes_and_agreement_with_packing(monkeypatch, T, m,
     assert rel_fro(to_f64(got), want) <= 2e-5
     assert np.abs(to_f64(got) - want).max() <= 1e-4 * np.abs(want).max()
     # the packing path multiplies the same values in the same order inside a tile
-    monkeypatch.setenv("GRASS_GEMM_PACK_MXT", "1")
+    grass.set_test_option(grass.TEST_PACK_MXT, 1)
     packed = gpu_cgrad(dYt, X, d_idx, d_rho, grass.DY_MxT)
     assert rel_fro(to_f64(packed), want) <= 2e-5
     assert (got - packed).abs().max().item() <= 1e-5 * float(np.abs(want).max())
 
 
-def test_dense_gradient_from_m_by_T_storage_without_packing(monkeypatch):
-    monkeypatch.setenv("GRASS_GEMM_TILE", "256")
+def test_dense_gradient_from_m_by_T_storage_without_packing():
+    grass.set_test_option(grass.TEST_GEMM_TILE, 256)
     T, m, n = 1024, 520, 264
     dY = randn((T, m), torch.bfloat16, 78, scale=0.1)
     X = randn((T, n), torch.bfloat16, 79)
@@ -713,11 +713,11 @@ def _sweep_cases(count, seed):
 
 
 @pytest.mark.parametrize("k,T,m,n,r,pad_y,pad_x,layout,tile", _sweep_cases(48, 2406))
-def test_compressed_grad_and_dense_grad_shape_sweep(monkeypatch, k, T, m, n, r, pad_y, pad_x, layout, tile):
+def test_compressed_grad_and_dense_grad_shape_sweep(k, T, m, n, r, pad_y, pad_x, layout, tile):
     """Seeded random shapes, paddings, layouts and forced tiles: every combination of packing,
     aligning copy, K tail and tile kind the launcher can take."""
     if tile:
-        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     X = randn((T, n), torch.bfloat16, 9000 + k, ld=n + pad_x)
     if layout == grass.DY_TxM:
         dY_dev = randn((T, m), torch.bfloat16, 9100 + k, scale=0.1, ld=m + pad_y)
@@ -811,10 +811,10 @@ def test_select_rows_random_sizes_bit_exact(case):
     (777, 334, (130, 90), (40, 9), False, None),             # n % 4 != 0: the two-kernel route
     (640, 1024, (400,), (256,), False, "256"),               # duplicates walk runs across the tile
 ])
-def test_step_group_equals_the_separate_calls_and_the_oracle(monkeypatch, dtype, wdtype, sdtype, T, n,
+def test_step_group_equals_the_separate_calls_and_the_oracle(dtype, wdtype, sdtype, T, n,
                                                              ms, rs, want_gc, tile):
     if tile:
-        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     X = randn((T, n), dtype, 120)
     dYs, idxs, rhos, Ms, Vs, Ws, host = [], [], [], [], [], [], []
     for i, (m, r) in enumerate(zip(ms, rs)):
@@ -913,19 +913,19 @@ def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
     (1056, 520, 264, 260, True, False, "256"),  # large tile
     (4096, 64, 32, 8, False, True, None),       # many K slices for a small output
 ])
-def test_step_cols_equals_the_separate_calls_and_the_oracle(monkeypatch, sdtype, T, m, n, r, dup, want_gc, tile):
+def test_step_cols_equals_the_separate_calls_and_the_oracle(sdtype, T, m, n, r, dup, want_gc, tile):
     """The column-form step in one call against the oracle (compressed gradient of the exchanged
     operands, Adam on r x m, update of r columns of W)."""
-    run_step_cols(monkeypatch, torch.bfloat16, sdtype, T, m, n, r, dup, want_gc, tile)
+    run_step_cols(torch.bfloat16, sdtype, T, m, n, r, dup, want_gc, tile)
 
 
-def test_step_cols_fp32_inputs(monkeypatch):
-    run_step_cols(monkeypatch, torch.float32, torch.float32, 300, 130, 50, 17, True, True, None)
+def test_step_cols_fp32_inputs():
+    run_step_cols(torch.float32, torch.float32, 300, 130, 50, 17, True, True, None)
 
 
-def run_step_cols(monkeypatch, dtype, sdtype, T, m, n, r, dup, want_gc, tile):
+def run_step_cols(dtype, sdtype, T, m, n, r, dup, want_gc, tile):
     if tile:
-        monkeypatch.setenv("GRASS_GEMM_TILE", tile)
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     dY = randn((T, m), dtype, 201, scale=0.1)
     X = randn((T, n), dtype, 202)
     idx, rho = make_idx(n, r, 203, dup)
