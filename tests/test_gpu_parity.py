@@ -806,13 +806,41 @@ def test_select_rows_random_sizes_bit_exact(case):
                                                  (torch.float32, torch.float32, torch.float32)])
 @pytest.mark.parametrize("T,n,ms,rs,want_gc,tile", [
     (512, 256, (256,), (16,), True, None),                   # one layer, G_C requested
-    (4096, 512, (300, 520, 64), (130, 129, 0), False, None), # group, many K slices, an empty set
+    (4096, 512, (300, 520, 64), (130, 129, 0), False, None), # group, several K slices, an empty set
     (1056, 264, (300, 520), (130, 129), True, "256"),        # large tile, K tail
     (777, 334, (130, 90), (40, 9), False, None),             # n % 4 != 0: the two-kernel route
     (640, 1024, (400,), (256,), False, "256"),               # duplicates walk runs across the tile
 ])
 def test_step_group_equals_the_separate_calls_and_the_oracle(dtype, wdtype, sdtype, T, n,
                                                              ms, rs, want_gc, tile):
+    run_step_group(dtype, wdtype, sdtype, T, n, ms, rs, want_gc, tile)
+
+
+@pytest.mark.parametrize("wdtype,sdtype", [(torch.bfloat16, torch.float32), (torch.float32, torch.bfloat16),
+                                           (torch.bfloat16, torch.bfloat16), (torch.float32, torch.float32)])
+@pytest.mark.parametrize("T,n,ms,rs,want_gc,tile", [
+    (8192, 256, (300,), (40,), True, None),                  # one layer, 16 slices
+    (8192, 256, (300, 520, 64), (40, 33, 8), False, None),   # a group of three in one launch
+    (8192, 1280, (24,), (40,), False, None),                 # every row drawn repeatedly; five column blocks
+    (8192, 264, (300, 90), (40, 9), True, None),             # the last column block is mostly empty
+    (8192, 1024, (400,), (256,), True, "256"),               # large tile: 32 slices
+    (8200, 512, (300,), (200,), False, "256"),               # ... with a ragged tail of T as one more slice
+    (4608, 256, (64,), (9,), False, None),                   # the fewest slices that take this kernel (9)
+    (6656, 128, (64,), (5,), True, None),                    # 13 slices: quarters of 4, 4, 4 and 1
+    (5120, 128, (40,), (8,), False, None),                   # 10 slices: quarters of 3, 3, 3 and 1
+])
+def test_step_group_with_more_than_eight_k_slices(wdtype, sdtype, T, n, ms, rs, want_gc, tile):
+    """Short, wide products (the layers of the small models at their token batch) split K into
+    dozens of slices; the step's tail is then the kernel whose four wavefronts each add a quarter
+    of the slices and meet in LDS.  The plan query confirms that these shapes take it."""
+    if tile:
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
+    total = sum((r + 7) // 8 * 8 for r in rs) if len(rs) > 1 else rs[0]
+    assert grass.cgrad_plan(T, n, total, grass.BF16)[1] > 8
+    run_step_group(torch.bfloat16, wdtype, sdtype, T, n, ms, rs, want_gc, tile)
+
+
+def run_step_group(dtype, wdtype, sdtype, T, n, ms, rs, want_gc, tile):
     if tile:
         grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
     X = randn((T, n), dtype, 120)
@@ -908,10 +936,26 @@ def test_compressed_grad_gather_staged_through_lds(T, m, n, r, dup, pad, shift):
 
 @pytest.mark.parametrize("sdtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("T,m,n,r,dup,want_gc,tile", [
+    (8192, 256, 64, 24, True, True, None),       # 16 slices, duplicates
+    (8192, 1280, 96, 40, False, False, None),    # five column blocks
+    (8192, 1024, 300, 256, True, False, "256"),  # large tile: 32 slices
+    (4608, 264, 40, 9, False, True, None),       # the fewest slices that take this kernel
+])
+def test_step_cols_with_more_than_eight_k_slices(sdtype, T, m, n, r, dup, want_gc, tile):
+    """The column-form step when K is split into more than eight slices: reduction and Adam run
+    in the kernel that spreads the slices over its wavefronts, writing Adam's output to U."""
+    if tile:
+        grass.set_test_option(grass.TEST_GEMM_TILE, int(tile))
+    assert grass.cgrad_plan(T, m, r, grass.BF16)[1] > 8
+    run_step_cols(torch.bfloat16, sdtype, T, m, n, r, dup, want_gc, tile)
+
+
+@pytest.mark.parametrize("sdtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,m,n,r,dup,want_gc,tile", [
     (512, 688, 256, 64, True, True, None),      # gate/up-shaped, duplicates
     (300, 130, 50, 17, False, False, None),     # nothing divides anything (m % 4 != 0: separate kernels)
     (1056, 520, 264, 260, True, False, "256"),  # large tile
-    (4096, 64, 32, 8, False, True, None),       # many K slices for a small output
+    (4096, 64, 32, 8, False, True, None),       # several K slices for a small output
 ])
 def test_step_cols_equals_the_separate_calls_and_the_oracle(sdtype, T, m, n, r, dup, want_gc, tile):
     """The column-form step in one call against the oracle (compressed gradient of the exchanged
@@ -950,7 +994,10 @@ def run_step_cols(dtype, sdtype, T, m, n, r, dup, want_gc, tile):
     ref.scatter_update_cols(Wo, idx, rho, 0.25, Uo)
     state_tol = 1e-2 if sdtype == torch.bfloat16 else 2e-5
     assert rel_fro(to_f64(M), M0) <= state_tol and rel_fro(to_f64(V), V0) <= state_tol
-    assert rel_fro(to_f64(U), Uo) <= (5e-2 if sdtype == torch.bfloat16 else 1e-3)
+    # U = -lr m^ / (sqrt(v^) + eps): with fp32 moments it carries the relative error of G_C and
+    # a few fp32 roundings; with bf16 moments the oracle rounds the same values the same way, and
+    # what is left is the rare element whose moment falls on the other side of a rounding boundary
+    assert rel_fro(to_f64(U), Uo) <= (5e-2 if sdtype == torch.bfloat16 else 2e-5)
     sel = np.unique(idx)
     assert rel_fro(to_f64(W)[:, sel], Wo[:, sel]) <= TOL_BF16
     rest = np.setdiff1d(np.arange(n), sel)
