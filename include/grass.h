@@ -131,6 +131,29 @@ grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_m
                                uint64_t refresh_id, int32_t* idx, float* rho, void* ws,
                                size_t ws_bytes, void* stream);
 
+/* grass_select_rows for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same arithmetic, same idx and rho bit for bit; the scratch the kernels need
+ * (status word, prefix sums and hit counters, or the sampling tree) lives in a static device
+ * array inside the library: grass_select_static_capacity() bytes (1 MiB) on every GPU the
+ * library runs on, held until the process ends.  The call allocates nothing and frees nothing.
+ * Limit: grass_select_workspace(m, r, method, replacement) must not exceed the capacity
+ * (m up to 65536 rows for every rule); larger problems return GRASS_ERR_WORKSPACE and launch
+ * nothing: use grass_select_rows for them.
+ * `status`: NULL, or a device int32 that receives what grass_select_rows leaves in the first
+ * 4 bytes of its workspace (GRASS_OK, or GRASS_ERR_NONFINITE with the placeholder selection).
+ * All calls on one GPU share that GPU's array: calls that may overlap in time (different
+ * streams, different threads) race; calls on one stream are ordered and each call initialises
+ * what it reads, so nothing of an earlier call is seen.  The first call on a device looks up
+ * the array's address (hipGetSymbolAddress): make it outside any stream capture.
+ * Errors: as grass_select_rows; WORKSPACE for sizes beyond the capacity; DEVICE if the address
+ * lookup or a launch fails. */
+size_t grass_select_static_capacity(void);
+grass_status grass_select_rows_static(const float* sumsq, int64_t m, int64_t r,
+                                      grass_method method, int replacement, grass_scale scale,
+                                      uint64_t seed, uint64_t refresh_id, int32_t* idx, float* rho,
+                                      int32_t* status, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Compressed gradient (Section 3.1, "Efficient Gradient Projection"; Algorithm 1
  * line "G_C <- P^T grad"):

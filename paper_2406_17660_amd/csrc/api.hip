@@ -88,10 +88,9 @@ size_t grass_select_workspace(int64_t m, int64_t r, grass_method method, int rep
     return select_workspace_bytes(m, r, method, replacement);
 }
 
-grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_method method,
-                               int replacement, grass_scale scale, uint64_t seed,
-                               uint64_t refresh_id, int32_t* idx, float* rho, void* ws,
-                               size_t ws_bytes, void* stream) {
+static grass_status check_select(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                                 int replacement, grass_scale scale, const int32_t* idx,
+                                 const float* rho) {
     if (m < 0 || r < 0) return GRASS_ERR_SHAPE;
     if (!present(sumsq, m) || !present(idx, r) || !present(rho, r)) return GRASS_ERR_NULL;
     if (method < GRASS_SEL_TOPR || method > GRASS_SEL_MULTI_NORM2) return GRASS_ERR_DTYPE;
@@ -101,10 +100,33 @@ grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_m
     const bool with_repl = method != GRASS_SEL_TOPR && replacement;
     if (!with_repl && r > m) return GRASS_ERR_SHAPE;
     if (r > 0 && m == 0) return GRASS_ERR_SHAPE;
+    return GRASS_OK;
+}
+
+grass_status grass_select_rows(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                               int replacement, grass_scale scale, uint64_t seed,
+                               uint64_t refresh_id, int32_t* idx, float* rho, void* ws,
+                               size_t ws_bytes, void* stream) {
+    const grass_status st = check_select(sumsq, m, r, method, replacement, scale, idx, rho);
+    if (st != GRASS_OK) return st;
     if (!ws || ws_bytes < select_workspace_bytes(m, r, method, replacement))
         return GRASS_ERR_WORKSPACE;
     return launch_select(sumsq, m, r, method, replacement, scale, seed, refresh_id, idx, rho, ws,
                          as_stream(stream));
+}
+
+size_t grass_select_static_capacity(void) { return select_static_scratch_bytes(); }
+
+grass_status grass_select_rows_static(const float* sumsq, int64_t m, int64_t r,
+                                      grass_method method, int replacement, grass_scale scale,
+                                      uint64_t seed, uint64_t refresh_id, int32_t* idx, float* rho,
+                                      int32_t* status, void* stream) {
+    const grass_status st = check_select(sumsq, m, r, method, replacement, scale, idx, rho);
+    if (st != GRASS_OK) return st;
+    if (select_workspace_bytes(m, r, method, replacement) > select_static_scratch_bytes())
+        return GRASS_ERR_WORKSPACE;  // beyond the built-in scratch: use grass_select_rows
+    return launch_select_static(sumsq, m, r, method, replacement, scale, seed, refresh_id, idx, rho,
+                                status, as_stream(stream));
 }
 
 size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt,

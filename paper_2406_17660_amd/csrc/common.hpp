@@ -80,6 +80,13 @@ grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_metho
                            int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
                            int32_t* idx, float* rho, void* ws, hipStream_t s);
 size_t select_workspace_bytes(int64_t m, int64_t r, grass_method method, int replacement);
+// The same selection with the library's own static device scratch in place of `ws`; `status`:
+// the caller's device status word, or nullptr.
+size_t select_static_scratch_bytes();
+grass_status launch_select_static(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                                  int replacement, grass_scale scale, uint64_t seed,
+                                  uint64_t refresh_id, int32_t* idx, float* rho, int32_t* status,
+                                  hipStream_t s);
 // M and V have dtype sdt (fp32, or bf16 moments rounded once per step).
 grass_status launch_adam_rows(const float* GC, int64_t ldgc, void* M, void* V, grass_dtype sdt,
                               int64_t r, int64_t n, float lr, float b1, float b2, float eps,

@@ -18,7 +18,15 @@
 //
 // Selection arithmetic is integer (or correctly rounded IEEE double sqrt / divide) so
 // that the indices are reproducible bit for bit.
+#include <atomic>
+
 #include "common.hpp"
+
+// Scratch memory of grass_select_rows_static, the entry point for callers that cannot
+// allocate: one copy per GPU, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr size_t kStaticScratchBytes = size_t{1} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace grass {
 namespace {
@@ -445,11 +453,12 @@ size_t select_workspace_bytes(int64_t m, int64_t r, grass_method method, int rep
     return kHeaderBytes + tree_bytes(tree_shape(m));
 }
 
-grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_method method,
-                           int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
-                           int32_t* idx, float* rho, void* ws, hipStream_t s) {
-    int32_t* status = static_cast<int32_t*>(ws);
-    char* body = static_cast<char*>(ws) + kHeaderBytes;
+// `status`: the device status word; `body`: select_workspace_bytes(...) - kHeaderBytes bytes of
+// device scratch (prefix sums and hit counters, or the tree), 256-byte aligned.
+static grass_status launch_select_kernels(const float* sumsq, int64_t m, int64_t r,
+                                          grass_method method, int replacement, grass_scale scale,
+                                          uint64_t seed, uint64_t refresh_id, int32_t* idx,
+                                          float* rho, int32_t* status, char* body, hipStream_t s) {
     if (method == GRASS_SEL_TOPR) {
         select_topr_kernel<<<1, kThreads, 0, s>>>(sumsq, m, r, idx, rho, status);
         return launch_status();
@@ -479,6 +488,51 @@ grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_metho
             sumsq, m, r, method, rescale, seed, refresh_id, idx, rho, status, ws_tree, shape);
     }
     return launch_status();
+}
+
+grass_status launch_select(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                           int replacement, grass_scale scale, uint64_t seed, uint64_t refresh_id,
+                           int32_t* idx, float* rho, void* ws, hipStream_t s) {
+    return launch_select_kernels(sumsq, m, r, method, replacement, scale, seed, refresh_id, idx, rho,
+                                 static_cast<int32_t*>(ws), static_cast<char*>(ws) + kHeaderBytes, s);
+}
+
+size_t select_static_scratch_bytes() { return kStaticScratchBytes; }
+
+// Address of this device's copy of `scratch`, resolved once per device (with that device
+// current) and kept; every later call only reads the table.
+static grass_status static_scratch_address(char** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<char*> address[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GRASS_ERR_DEVICE;
+    char* p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym)
+            return GRASS_ERR_DEVICE;
+        p = static_cast<char*>(sym);
+        address[dev].store(p, std::memory_order_release);  // two first callers store the same value
+    }
+    *out = p;
+    return GRASS_OK;
+}
+
+grass_status launch_select_static(const float* sumsq, int64_t m, int64_t r, grass_method method,
+                                  int replacement, grass_scale scale, uint64_t seed,
+                                  uint64_t refresh_id, int32_t* idx, float* rho, int32_t* status,
+                                  hipStream_t s) {
+    if (select_workspace_bytes(m, r, method, replacement) > kStaticScratchBytes)
+        return GRASS_ERR_WORKSPACE;  // checked by the caller too; never launch past the array
+    char* base = nullptr;
+    const grass_status st = static_scratch_address(&base);
+    if (st != GRASS_OK) return st;
+    // Nothing in the scratch has to start at zero: the kernels initialise the prefix sums, the
+    // hit counters and every level of the tree (padding included) before they read them, so
+    // what the previous call left behind is never seen.
+    return launch_select_kernels(sumsq, m, r, method, replacement, scale, seed, refresh_id, idx, rho,
+                                 status ? status : reinterpret_cast<int32_t*>(base),
+                                 base + kHeaderBytes, s);
 }
 
 }  // namespace grass

@@ -29,7 +29,7 @@ EXPORTS = [
     "grass_grad_row_stats_workspace", "grass_grad_row_stats", "grass_scatter_update_cols",
     "grass_cgrad_group_workspace", "grass_compressed_grad_group",
     "grass_adam_rows_state", "grass_adam_scatter_state", "grass_cgrad_plan",
-    "grass_set_test_option",
+    "grass_set_test_option", "grass_select_static_capacity", "grass_select_rows_static",
     "grass_adam_step_scalars", "grass_adam_scatter_replayable",
     "grass_step_group_workspace", "grass_step_group",
     "grass_step_cols_workspace", "grass_step_cols",
@@ -68,6 +68,9 @@ def lib():
     L.grass_select_workspace.argtypes = [i64, i64, i32, i32]
     L.grass_select_workspace.restype = sz
     L.grass_select_rows.argtypes = [vp, i64, i64, i32, i32, i32, u64, u64, vp, vp, vp, sz, vp]
+    L.grass_select_static_capacity.argtypes = []
+    L.grass_select_static_capacity.restype = sz
+    L.grass_select_rows_static.argtypes = [vp, i64, i64, i32, i32, i32, u64, u64, vp, vp, vp, vp]
     L.grass_cgrad_workspace.argtypes = [i64, i64, i64, i64, i32, i32]
     L.grass_cgrad_workspace.restype = sz
     L.grass_compressed_grad.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, i64, vp, vp,
@@ -110,6 +113,7 @@ def lib():
                                               vp, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS:
         if name not in ("grass_status_string", "grass_select_workspace", "grass_cgrad_workspace",
+                        "grass_select_static_capacity",
                         "grass_dense_workspace", "grass_grad_row_stats_workspace",
                         "grass_cgrad_group_workspace", "grass_step_group_workspace",
                         "grass_step_cols_workspace"):
@@ -189,6 +193,26 @@ def select_rows(sumsq, r, method, replacement, scale, seed, refresh_id, idx, rho
                                    int(bool(replacement)), scale, seed, refresh_id,
                                    _vec(idx, torch.int32), _vec(rho, torch.float32), wp, wb,
                                    _stream()), "grass_select_rows")
+    return idx, rho
+
+
+def select_static_capacity() -> int:
+    return int(lib().grass_select_static_capacity())
+
+
+def select_rows_static(sumsq, r, method, replacement, scale, seed, refresh_id, idx, rho, status=None):
+    """grass_select_rows with the library's built-in scratch (no workspace, no allocation);
+    status: optional int32 device tensor of one element that receives the status word."""
+    m = sumsq.shape[0]
+    assert idx.shape == (r,) and rho.shape == (r,)
+    sp = None
+    if status is not None:
+        assert status.is_cuda and status.dtype == torch.int32 and status.numel() == 1
+        sp = C.c_void_p(status.data_ptr())
+    _check(lib().grass_select_rows_static(_vec(sumsq, torch.float32), m, r, method,
+                                          int(bool(replacement)), scale, seed, refresh_id,
+                                          _vec(idx, torch.int32), _vec(rho, torch.float32), sp,
+                                          _stream()), "grass_select_rows_static")
     return idx, rho
 
 
