@@ -87,6 +87,31 @@ def test_select_validation():
     assert f(FAKE, 8, 2, grass.SEL_MULTI_NORM, 1, 0, 0, 0, FAKE, FAKE, FAKE, 8, None) == grass.ERR_WORKSPACE
 
 
+def test_select_static_validation():
+    """The no-allocation form validates like grass_select_rows and refuses, on the host and
+    before any HIP call, what its built-in scratch cannot hold."""
+    f = grass.lib().grass_select_rows_static
+    cap = grass.select_static_capacity()
+    assert cap == 1 << 20
+    ok = (FAKE, 4096, 1024, grass.SEL_MULTI_NORM, 1, grass.SCALE_PAPER, 1, 0, FAKE, FAKE, None, None)
+
+    def call(**kw):
+        names = ("sumsq", "m", "r", "method", "replacement", "scale", "seed", "refresh_id", "idx",
+                 "rho", "status", "stream")
+        return f(*[kw.get(n, v) for n, v in zip(names, ok)])
+    assert call(sumsq=None) == grass.ERR_NULL
+    assert call(idx=None) == grass.ERR_NULL
+    assert call(m=-1) == grass.ERR_SHAPE
+    assert call(replacement=0, r=5000) == grass.ERR_SHAPE
+    assert call(method=9) == grass.ERR_DTYPE
+    assert call(method=grass.SEL_TOPR, scale=grass.SCALE_INV_SQRT_RQ) == grass.ERR_DTYPE
+    for m, repl in ((100000, 1), (200000, 0)):
+        assert grass.select_workspace(m, 10, grass.SEL_MULTI_NORM, repl) > cap
+        assert call(m=m, r=10, replacement=repl) == grass.ERR_WORKSPACE
+    for repl in (0, 1):  # 65536 rows fit for every rule
+        assert grass.select_workspace(65536, 1024, grass.SEL_MULTI_NORM2, repl) <= cap
+
+
 def test_compressed_grad_validation():
     L = grass.lib()
     f = L.grass_compressed_grad
