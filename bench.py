@@ -57,6 +57,15 @@ def parse():
                    help="with --block: capture the regular step into a HIP graph and replay it")
     p.add_argument("--concurrent-groups", action="store_true",
                    help="with --block: every group of layers on a HIP stream of its own")
+    p.add_argument("--settle-launches", type=int, default=400,
+                   help="cap of the untimed settle phase (steps run until the GEMM's time stops falling)")
+    p.add_argument("--summarise", metavar="DIR", default=None,
+                   help="no benchmark: turn the rocprofv3 output under DIR (see bench_summarise.py) "
+                        "into the summaries under profiles/")
+    p.add_argument("--clock-trace", action="store_true",
+                   help="no benchmark line: sample the GPU clock (rocm-smi) while the 7B attention "
+                        "layer's kernels and the matrix-core probes run back to back, and print a "
+                        "markdown table (the evidence behind the power-bound reading of the GEMM)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
     p.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -132,15 +141,200 @@ def cpu_baseline(cfg, layer, dY, X, state, W, seconds):
                       f"adam_rows + scatter_update at full size ({t_tail:.2f} s)"}
 
 
-def measured_traffic(layer_name, T):
-    """HBM bytes per launch of the GEMM kernel as measured with rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE (profiles/gemm_traffic.json, written from those runs); None if not recorded
-    for this workload."""
+def measured_traffic(key, T):
+    """(bytes, where from): HBM bytes per launch of the dominant kernel as measured with rocprofv3
+    --pmc FETCH_SIZE / WRITE_SIZE in an earlier profiler run of this command (the counters cannot
+    be read from inside the process).  profiles/gemm_traffic.json is written from such runs by
+    `bench.py --summarise`; (None, None) if nothing is recorded for this workload."""
     path = os.path.join(ROOT, "profiles", "gemm_traffic.json")
     if not os.path.exists(path):
+        return None, None
+    rec = json.load(open(path)).get(f"{key}:T={T}")
+    if not rec:
+        return None, None
+    return rec["bytes_per_launch"], (f"{rec['source']} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                                     "earlier profiler run of this workload; not measured in this run)")
+
+
+def settle(run_steps, cap):
+    """Untimed steps until the chip has reached the clock it sustains under this load: after an
+    idle period the first tens of GEMM launches run at a lower clock.  Steps are issued in
+    batches of 10 with events around their GEMM kernels; the phase ends when a batch is no
+    faster than the one before it (within 0.5 %) twice in a row, or at `cap` launches.
+    Returns (launches, first batch's mean GEMM ms, last batch's)."""
+    done, prev, first, calm = 0, None, None, 0
+    while done < cap:
+        events = [(ev(), ev()) for _ in range(10)]
+        run_steps(10, events)
+        torch.cuda.synchronize()
+        cur = float(np.mean([a.elapsed_time(b) for a, b in events]))
+        done += 10
+        first = cur if first is None else first
+        if prev is not None and cur >= prev * 0.995:
+            calm += 1
+            if calm == 2:
+                break
+        else:
+            calm = 0
+        prev = cur
+    return done, first, prev if prev is not None else first
+
+
+def layer_figures(cfg, layer, steps=40):
+    """Regular-step figures of one more layer of the configuration (secondary measurements for
+    the `detail` object): step time, the GEMM kernel's rate, the step's HBM rate, and the naive
+    route (full gradient, then a row gather) beside the compressed gradient."""
+    L = cfg.layers[layer]
+    T, m, n, r = cfg.T, L.m, L.n, cfg.r
+    dY = workloads.make_dY(cfg, layer, 0, "cuda")
+    X = workloads.make_X(cfg, layer, 0, "cuda")
+    W = workloads.make_W(cfg, layer, "cuda")
+    st = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha,
+                    adam=AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps), seed=workloads.BASE_SEED,
+                    store_GC=False)
+    st.refresh(dY, X, reset_state=True)
+    for _ in range(10):
+        st.step(dY, X, W)
+    gemm_events = [(ev(), ev()) for _ in range(steps)]
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for t in range(steps):
+        st.step(dY, X, W, gemm_events[t])
+    b.record()
+    torch.cuda.synchronize()
+    step_ms = a.elapsed_time(b) / steps
+    gemm_ms = float(np.mean([x.elapsed_time(y) for x, y in gemm_events]))
+    flops = 2.0 * r * T * n
+    esz = 2 if cfg.dtype == torch.bfloat16 else 4
+    step_bytes = esz * T * (m + n) + r * n * (4 * st.M.element_size() + 2 * esz)
+    call_ms, _ = time_calls(lambda: st.compressed_grad(dY, X), 10, warmup=2)
+    dense_ms, _ = time_calls(lambda: st.full_gradient(dY, X), 3, warmup=1)
+    tmp = torch.empty((r, n), dtype=torch.float32, device="cuda")
+    gather_ms, _ = time_calls(lambda: grass.gather_rows(st.G, st.idx, st.rho, tmp), 10)
+    tile, slices = grass.cgrad_plan(T, n, r, st.dt)
+    return {"layer": L.name, "m": m, "n": n, "T": T, "r": r, "regular_step_ms": step_ms,
+            "layer_steps_per_s": 1e3 / step_ms, "gemm_kernel_ms": gemm_ms,
+            "gemm_kernel_tflops": flops / (gemm_ms * 1e-3) / 1e12,
+            "gemm_kernel_frac_mfma": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+            "step_algorithmic_GBs": step_bytes / (step_ms * 1e-3) / 1e9,
+            "step_frac_hbm": step_bytes / (step_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "flop_per_input_byte": flops / (esz * T * (m + n)), "gemm_tile": tile, "k_slices": slices,
+            "compressed_grad_call_ms": call_ms, "naive_full_grad_ms": dense_ms,
+            "naive_gather_ms": gather_ms,
+            "speedup_vs_naive_full_G_then_gather": (dense_ms + gather_ms) / call_ms}
+
+
+def clock_trace(cfg):
+    """What clock the chip sustains under each kind of load of the 7B attention layer step.
+    rocm-smi is polled from a thread while each load runs back to back for about three seconds;
+    prints a markdown table with the rate each load reached and the shader clocks seen."""
+    import re
+    import subprocess
+    import threading
+    from paper_2406_17660_amd import probe as mfma_probe
+
+    dev = "cuda"
+    L = cfg.layers[0]
+    T, m, n, r = cfg.T, L.m, L.n, cfg.r
+    dY = workloads.make_dY(cfg, 0, 0, dev)
+    X = workloads.make_X(cfg, 0, 0, dev)
+    W = workloads.make_W(cfg, 0, dev)
+    adam = AdamHyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps)
+    st = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
+                    seed=workloads.BASE_SEED, store_GC=False)
+    st.refresh(dY, X)
+    dYt = dY.t().contiguous()
+    st_t = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
+                      seed=workloads.BASE_SEED, layout=grass.DY_MxT)
+    st_t.idx.copy_(st.idx)
+    st_t.rho.copy_(st.rho)
+    g = torch.Generator(device=dev)
+    g.manual_seed(workloads.BASE_SEED + 99)
+    vals = torch.randn(32768, generator=g, device=dev)
+    left = (torch.arange(32768, device=dev) // 2048) % 8 < 4
+    vals = torch.where(left, vals * 0.1, vals).to(torch.bfloat16)
+
+    samples, stop = [], [False]
+
+    def sampler():
+        while not stop[0]:
+            t = time.time()
+            try:
+                o = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True,
+                                   text=True, timeout=5).stdout
+            except Exception as e:  # the read-out is best effort
+                o = str(e)
+            samples.append((t, o))
+
+    def sclk_mhz(text):
+        try:
+            card = next(iter(json.loads(text).values()))
+        except Exception:
+            return None
+        for k, v in card.items():
+            if "sclk" in k.lower():
+                hit = re.search(r"(\d+)\s*Mhz", str(v), flags=re.I)
+                if hit:
+                    return int(hit.group(1))
         return None
-    rec = json.load(open(path)).get(f"{layer_name}:T={T}")
-    return rec["bytes_per_launch"] if rec else None
+
+    flops = 2.0 * r * T * n
+    rows = []
+
+    def phase(name, fn, unit_of_work, seconds=3.0):
+        torch.cuda.synchronize()
+        t0, k = time.time(), 0
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        while time.time() - t0 < seconds:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+            k += 20
+        b.record()
+        torch.cuda.synchronize()
+        t1 = time.time()
+        ms = a.elapsed_time(b) / k
+        clocks = [c for c in (sclk_mhz(o) for t, o in samples if t0 + 0.5 <= t <= t1) if c]
+        rows.append((name, ms, unit_of_work(ms), clocks))
+
+    th = threading.Thread(target=sampler, daemon=True)
+    th.start()
+    try:
+        time.sleep(2.5)
+        idle = [c for c in (sclk_mhz(o) for _, o in samples) if c]
+        rows.append(("idle", None, "", idle))
+        st.GC.normal_()
+        phase("Adam + row update alone (grass_adam_scatter, HBM-bound)", lambda: st.adam_scatter(W),
+              lambda ms: "%.0f GB/s" % (24.0 * r * n / (ms * 1e-3) / 1e9))
+        for name, source in (("matrix instruction only, constant operands", mfma_probe.CONSTANTS),
+                             ("matrix instruction only, operands like the GEMM's inputs, in registers", mfma_probe.REGISTERS),
+                             ("the same operands read from LDS fragment by fragment", mfma_probe.LDS)):
+            out = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+            fl = [0.0]
+
+            def one(source=source, out=out, fl=fl):
+                import ctypes as C
+                f = C.c_double(0.0)
+                rc = mfma_probe.lib().mfma_rate_probe(
+                    source, C.c_void_p(vals.data_ptr()), vals.numel() * 2, C.c_void_p(out.data_ptr()),
+                    out.numel(), 2000, C.byref(f), C.c_void_p(torch.cuda.current_stream().cuda_stream))
+                assert rc == 0
+                fl[0] = f.value
+            phase(name, one, lambda ms, fl=fl: "%.0f TFLOP/s" % (fl[0] / (ms * 1e-3) / 1e12))
+        phase("compressed-gradient GEMM alone, dY stored m x T (row-gathering kernel, no gather pass)",
+              lambda: st_t.compressed_grad(dYt, X), lambda ms: "%.0f TFLOP/s (whole call)" % (flops / (ms * 1e-3) / 1e12))
+        phase("regular steps, dY stored T x m (gather 20 %, GEMM 75 %, fused tail 3 % of the time)",
+              lambda: st.step(dY, X, W), lambda ms: "%.0f TFLOP/s over the whole step" % (flops / (ms * 1e-3) / 1e12))
+    finally:
+        stop[0] = True
+        th.join(10)
+    print("| load (about 3 s back to back) | ms per launch | rate | sclk samples | sclk MHz min / median / max |")
+    print("|---|---:|---|---:|---|")
+    for name, ms, rate, clocks in rows:
+        c = ("%d / %d / %d" % (min(clocks), int(np.median(clocks)), max(clocks))) if clocks else "no read-out"
+        print("| %s | %s | %s | %d | %s |" % (name, "" if ms is None else "%.4f" % ms, rate, len(clocks), c))
 
 
 def bench_block(args, cfg):
@@ -187,13 +381,18 @@ def bench_block(args, cfg):
                                f"{cfg.method}{'' if cfg.replacement else '-NR'} row selection, "
                                f"dY stored {args.layout}"
                                f"{', groups on concurrent streams' if args.concurrent_groups else ''}"
-                               f"{', regular steps replayed from a HIP graph' if args.graph else ''}"},
+                               f"{', regular steps replayed from a HIP graph' if args.graph else ''}",
+                   "key": f"{args.block}_block" + ("" if args.layout == "txm" else "_mxt"),
+                   "argv": " ".join(sys.argv[1:])},
         "compressed_grad_tflops_incl_gather_and_reduce_and_adam": flops * args.steps / (ms * 1e-3) / 1e12,
     }))
 
 
 def main():
     args = parse()
+    if args.summarise:
+        import bench_summarise
+        return bench_summarise.main(args.summarise)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the per-layer GRASS step on ONE GPU; "
                  "--gpus N with N > 1 is not supported (no sharding or collectives are built).")
@@ -204,6 +403,8 @@ def main():
     if args.config is None:  # a block brings its model's token batch, rank and selection rule
         args.config = {"60m": 2, "350m": 3, "1b": 4}.get(args.block, 5)
     cfg = workloads.CONFIGS[args.config]
+    if args.clock_trace:
+        return clock_trace(workloads.CONFIGS[5])
     if args.block:
         return bench_block(args, cfg)
     L = cfg.layers[args.layer]
@@ -224,11 +425,17 @@ def main():
                     state_dtype=torch.bfloat16 if args.adam_state == "bf16" else torch.float32,
                     store_GC=False)
 
-    def run(steps, gemm_events=None):
+    def run(steps, gemm_events=None, end_events=None):
         for t in range(steps):
             if t % REFRESH_EVERY == 0:
                 st.refresh(dY, X, reset_state=True)
             st.step(dY, X, W, gemm_events[t] if gemm_events else None)
+            if end_events:
+                end_events[t].record()
+
+    def run_regular(steps, gemm_events):
+        for t in range(steps):
+            st.step(dY, X, W, gemm_events[t])
 
     st.row_statistic(dY, X)  # set-up: allocates the refresh-step workspace outside the timed region
     # One plain device-to-device copy of X (T*n*2 bytes read, as many written): the known-size
@@ -238,18 +445,26 @@ def main():
     del calib
     run(args.warmup)
     torch.cuda.synchronize()
+    settle_launches, settle_first_ms, settle_last_ms = settle(run_regular, args.settle_launches)
     gemm_events = [(ev(), ev()) for _ in range(args.steps)]
+    end_events = [ev() for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start, t_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     wall0 = time.perf_counter()
     t_start.record()
-    run(args.steps, gemm_events)
+    run(args.steps, gemm_events, end_events)
     t_stop.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     total_ms = t_start.elapsed_time(t_stop)
     ms_per_step = total_ms / args.steps
     gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
+    # what follows the GEMM inside the step: the fused split-K reduction + Adam + row update
+    tail_ms = float(np.mean([g[1].elapsed_time(e) for g, e in zip(gemm_events, end_events)]))
+    # regular steps alone (the timed region holds one refresh step, at t = 0)
+    regular = [end_events[t - 1].elapsed_time(end_events[t]) for t in range(1, args.steps)
+               if t % REFRESH_EVERY != 0]
+    regular_ms = float(np.mean(regular)) if regular else ms_per_step
     if grass.select_status(st.ws_sel) != grass.OK:
         sys.exit("selection reported non-finite row statistics")
 
@@ -268,18 +483,58 @@ def main():
                                f"T={T} tokens, r={r}, {cfg.method}"
                                f"{'' if cfg.replacement else '-NR'} selection of {args.side}, dY stored {args.layout}, {args.adam_state} Adam state, "
                                f"refresh every {REFRESH_EVERY} steps",
-                   "m": m, "n": n, "T": T, "r": r},
-        "roofline": {"bound": "mfma",
-                     "kernel": ("tn_gemm_bf16_direct_kernel<false, false, true, true>" if args.layout == "mxt"
-                                else "tn_gemm_bf16_direct_kernel<false, false, false, false>") + " (compressed-gradient GEMM)",
-                     "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS,
-                     "traffic": measured_traffic(L.name, T) if args.layout == "txm" else None,
-                     "flops_per_launch": flops, "avg_launch_ms": gemm_ms},
+                   "m": m, "n": n, "T": T, "r": r, "layer": L.name,
+                   "key": (L.name if cfg.cid == 5 else f"c{cfg.cid}_{L.name}")
+                          + ("" if args.layout == "txm" else "_mxt") + ("" if args.side == "rows" else "_cols"),
+                   "argv": " ".join(sys.argv[1:])},
+        "roofline": None,  # filled in below
+        "settle_launches": settle_launches,
+        "settle_gemm_ms_first_batch": settle_first_ms, "settle_gemm_ms_last_batch": settle_last_ms,
         "host_wall_s": wall,
     }
+    traffic, traffic_source = measured_traffic(out["config"]["key"], T)
+    # Which roofline binds the layer: 2 r T n flops against the T (m + n) input elements that have
+    # to be read once (dY stored T x m: the gather touches every sector of it).  Above the ridge
+    # (2500 TFLOP/s / 8 TB/s = 312 flop/B) the dominant kernel, the GEMM, is priced against the
+    # matrix cores; below it the whole regular step is priced against HBM.
+    esz = 2 if cfg.dtype == torch.bfloat16 else 4
+    input_bytes = esz * T * (m + n)
+    intensity = flops / input_bytes
+    mfma_bound = cfg.dtype == torch.bfloat16 and intensity >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    gemm_name = ("tn_gemm_bf16_direct_kernel<false, false, true, true>" if args.layout == "mxt"
+                 else "tn_gemm_bf16_direct_kernel<false, false, false, false>")
+    # bytes the one-call step has to move: the inputs once, M and V read and written, the r rows
+    # of W read and written (G_C stays in the partial tiles and is never stored)
+    step_bytes = input_bytes + r * st.n * (4 * st.M.element_size() + 2 * esz)
+    if mfma_bound:
+        out["roofline"] = {"bound": "mfma", "kernel": gemm_name + " (compressed-gradient GEMM)",
+                           "achieved": gemm_tflops, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                           "frac": gemm_tflops / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic,
+                           "traffic_source": traffic_source,
+                           "flops_per_launch": flops, "avg_launch_ms": gemm_ms}
+    else:
+        gbs = step_bytes / (regular_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm",
+                           "kernel": "the regular step as launched by grass_step_group / grass_step_cols: "
+                                     "gather of the selected rows, GEMM, fused split-K reduction + Adam + update",
+                           "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": gbs / PEAK_HBM_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                           "bytes_per_launch": step_bytes, "avg_launch_ms": regular_ms,
+                           "flop_per_input_byte": intensity,
+                           "gemm_kernel_tflops": gemm_tflops, "gemm_kernel_ms": gemm_ms,
+                           "gemm_kernel_frac_mfma": gemm_tflops / PEAK_BF16_MFMA_TFLOPS}
+    out["regular_step_ms"] = regular_ms
+    # The step's tail as it runs inside the step sequence (state and weights come from HBM: a
+    # whole GEMM pass lies between two uses): from the event after the GEMM to the end of the step.
+    plan_tile, plan_slices = grass.cgrad_plan(T, st.n, r, st.dt, layout)
+    tail_bytes = r * st.n * (4 * plan_slices + 4 * st.M.element_size() + 2 * esz)
+    out["step_tail"] = {"what": "split-K reduction + Adam + update after the GEMM, inside the step "
+                                "(fused kernel; for column selection plus the column update)",
+                        "ms": tail_ms, "k_slices": plan_slices, "algorithmic_bytes": tail_bytes,
+                        "GBs": tail_bytes / (tail_ms * 1e-3) / 1e9,
+                        "frac_hbm": tail_bytes / (tail_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 
-    if not args.no_extras:
+    if not args.no_extras and cfg.dtype == torch.bfloat16:
         # Context for the fraction above: what kernels of nothing but this matrix instruction
         # sustain on this very machine.  The clock under that load depends on the box and on what
         # the instructions are fed: constants; values distributed like the GEMM's inputs (dY-like
@@ -294,12 +549,13 @@ def main():
         probe = mfma_probe.mfma_rate(source=mfma_probe.CONSTANTS)
         probe_regs = mfma_probe.mfma_rate(source=mfma_probe.REGISTERS, operands=vals)
         probe_lds = mfma_probe.mfma_rate(source=mfma_probe.LDS, operands=vals)
-        out["roofline"]["mfma_only_kernel_tflops_this_box"] = probe
-        out["roofline"]["mfma_only_kernel_normal_operands_tflops"] = probe_regs
-        out["roofline"]["mfma_plus_lds_reads_kernel_normal_operands_tflops"] = probe_lds
-        out["roofline"]["frac_of_mfma_only_kernel"] = gemm_tflops / probe
-        out["roofline"]["frac_of_mfma_only_kernel_normal_operands"] = gemm_tflops / probe_regs
-        out["roofline"]["frac_of_mfma_plus_lds_reads_kernel"] = gemm_tflops / probe_lds
+        out["matrix_core_context"] = {
+            "mfma_only_kernel_tflops_this_box": probe,
+            "mfma_only_kernel_normal_operands_tflops": probe_regs,
+            "mfma_plus_lds_reads_kernel_normal_operands_tflops": probe_lds,
+            "gemm_frac_of_mfma_only_kernel": gemm_tflops / probe,
+            "gemm_frac_of_mfma_only_kernel_normal_operands": gemm_tflops / probe_regs,
+            "gemm_frac_of_mfma_plus_lds_reads_kernel": gemm_tflops / probe_lds}
 
     if not args.no_extras and args.side == "rows" and args.layout == "txm":
         detail = {}
@@ -386,6 +642,22 @@ def main():
                                      + med + detail["regular_step_ms"])
         detail["amortised_step_ms_K200"] = (199 * detail["regular_step_ms"]
                                             + detail["refresh_step_ms"]) / 200
+        # What a plain stream of the Adam kernel's size reaches when its data is cold: a + b -> c
+        # over r x n fp32 arrays (12 B per element), eight sets cycled.  Kernels of tens of
+        # microseconds do not reach the rates of the 1 GiB streams above.
+        trio = [tuple(torch.empty((r, n), dtype=torch.float32, device=dev).normal_() for _ in range(3))
+                for _ in range(8)]
+
+        def cold_add():
+            turn[0] += 1
+            x_, y_, z_ = trio[turn[0] % len(trio)]
+            torch.add(x_, y_, out=z_)
+        med, _ = time_calls(cold_add, 40, warmup=8)
+        detail["hbm_measured_cold_add_same_size_GBs"] = 12.0 * r * n / (med * 1e-3) / 1e9
+        del trio
+        if args.config == 5 and args.layer == 0 and T == cfg.T:
+            # the other three layers of the configuration, in the same launch configuration
+            detail["other_layers"] = [layer_figures(cfg, k) for k in range(1, len(cfg.layers))]
         detail["paper_context"] = ("paper: 13B LLaMA half-precision pretraining on one 40 GB "
                                    "A100; no per-layer timing is published")
         out["detail"] = detail

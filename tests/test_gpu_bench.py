@@ -34,10 +34,26 @@ def test_layer_bench_line_has_every_field_of_the_contract():
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
     assert abs(r["achieved"] - r["flops_per_launch"] / (r["avg_launch_ms"] * 1e-3) / 1e12) < 1e-6 * r["achieved"]
-    assert "traffic" in r  # measured bytes exist for the full-size workload only
+    assert "traffic" in r and "traffic_source" in r  # measured bytes exist for the full-size workload only
+    assert 10 <= d["settle_launches"] <= 400 and d["settle_gemm_ms_last_batch"] > 0
+    t = d["step_tail"]
+    assert t["ms"] > 0 and abs(t["GBs"] - t["algorithmic_bytes"] / (t["ms"] * 1e-3) / 1e9) < 1e-6 * t["GBs"]
+    assert d["regular_step_ms"] > 0
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == d["unit"] and c["cores"] >= 1 and c["value"] > 0
     assert isinstance(c["sample"], str) and c["sample"]
+
+
+def test_layer_bench_line_of_a_memory_bound_configuration():
+    """The narrow layers of the small models are priced against HBM: the whole regular step."""
+    d = run_bench("--config", "2", "--layer", "0", "--tokens", "8192", "--steps", "5", "--warmup", "2",
+                  "--no-cpu-baseline", "--no-extras")
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
+    assert abs(r["achieved"] - r["bytes_per_launch"] / (r["avg_launch_ms"] * 1e-3) / 1e9) < 1e-6 * r["achieved"]
+    assert r["bytes_per_launch"] == 2 * 8192 * (512 + 512) + 128 * 512 * 20
+    assert d["step_tail"]["k_slices"] > 8 and d["config"]["key"] == "c2_attn_qkvo"
 
 
 def test_block_bench_line():

@@ -29,6 +29,61 @@ def test_philox_known_answers():
         assert [int(x) for x in out] == v[6:10]
 
 
+def philox4x32_10_from_the_round_definition(ctr, key):
+    """Philox4x32-10 restated from the round function of Salmon et al. (SC'11, Section 3.3 and
+    Table 2) with Python integers: one round multiplies counter words 0 and 2 by the two
+    multipliers (full 64-bit products), crosses the halves over, and xors the high halves with
+    the other two words and the round key; the key is bumped by the Weyl constants between
+    rounds.  The Weyl constants are not typed in: they are the golden ratio and sqrt(3) - 1 as
+    32-bit fractions, computed here with integer square roots."""
+    from math import isqrt
+    w0 = (isqrt(5 << 64) - (1 << 32)) // 2          # floor(2^32 (sqrt(5) - 1) / 2)
+    w1 = isqrt(3 << 64) - (1 << 32)                 # floor(2^32 (sqrt(3) - 1))
+    assert (w0, w1) == (0x9E3779B9, 0xBB67AE85)
+    m0, m1 = 0xD2511F53, 0xCD9E8D57                  # the paper's multipliers for 4 x 32
+    c, k = [int(x) for x in ctr], [int(x) for x in key]
+    for rnd in range(10):
+        if rnd:
+            k = [(k[0] + w0) & 0xFFFFFFFF, (k[1] + w1) & 0xFFFFFFFF]
+        p0, p1 = m0 * c[0], m1 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k[1], p0 & 0xFFFFFFFF]
+    return c
+
+
+def test_philox_equals_a_big_integer_restatement_of_the_round_definition():
+    rows = [[int(x, 16) for x in l.split()] for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    for v in rows:  # the restatement reproduces the published vectors by itself
+        assert philox4x32_10_from_the_round_definition(v[0:4], v[4:6]) == v[6:10]
+    rng = np.random.default_rng(1976)
+    for _ in range(300):
+        ctr = [int(x) for x in rng.integers(0, 1 << 32, 4)]
+        key = [int(x) for x in rng.integers(0, 1 << 32, 2)]
+        assert [int(x) for x in ref.philox4x32_10(ctr, key)] == philox4x32_10_from_the_round_definition(ctr, key)
+
+
+def test_third_known_answer_vector_is_keyed_by_the_digits_of_pi():
+    """The published vectors use the fractional hexadecimal digits of pi as the third counter
+    and key; that part of the fixture can be derived instead of recalled.  pi from Machin's
+    formula in integer arithmetic."""
+    bits = 192 + 64
+
+    def arctan_inv(x):  # 2^bits * arctan(1 / x)
+        total, term, n, sign = 0, (1 << bits) // x, 1, 1
+        while term:
+            total += sign * (term // n)
+            term //= x * x
+            n += 2
+            sign = -sign
+        return total
+    pi = 4 * (4 * arctan_inv(5) - arctan_inv(239))
+    frac = (pi - (3 << bits)) >> 64  # the first 192 fractional bits
+    words = [(frac >> (160 - 32 * i)) & 0xFFFFFFFF for i in range(6)]
+    rows = [[int(x, 16) for x in l.split()] for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert rows[2][:6] == words
+
+
 def test_draw_word_packing():
     seed, refresh, j = 0x0123456789ABCDEF, 0xFEDCBA9876543210, 0x1122334455667788
     out = ref.philox4x32_10([j & 0xFFFFFFFF, j >> 32, refresh & 0xFFFFFFFF, refresh >> 32],
