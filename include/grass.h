@@ -417,12 +417,14 @@ grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* 
  *   GRASS_TEST_PACK_MXT      1: dY stored m x T goes through the packing pass instead of the
  *                            row-gathering GEMM
  *   GRASS_TEST_NO_PAIRS      1: the row-gathering GEMM loads one K tile per request
+ *   GRASS_TEST_MAX_K_SLICES  k > 0: the token dimension is split into at most k slices
  * Errors: DTYPE for an unknown option. */
 typedef enum {
     GRASS_TEST_GEMM_TILE = 0,
     GRASS_TEST_FUSED_STATS = 1,
     GRASS_TEST_PACK_MXT = 2,
-    GRASS_TEST_NO_PAIRS = 3
+    GRASS_TEST_NO_PAIRS = 3,
+    GRASS_TEST_MAX_K_SLICES = 4
 } grass_test_option;
 grass_status grass_set_test_option(grass_test_option option, int value);
 

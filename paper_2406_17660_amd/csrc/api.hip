@@ -10,7 +10,7 @@ using namespace grass;
 
 namespace {
 
-constexpr int kNumTestOptions = 4;
+constexpr int kNumTestOptions = 5;
 std::atomic<int> g_test_options[kNumTestOptions];  // zero-initialised: the library decides
 
 constexpr int64_t kMaxGridRows = 65535;  // rows are carried in blockIdx.y

@@ -67,14 +67,21 @@ Plan make_plan(int64_t T, int64_t rows, int64_t n, bool needs_pack) {
     const int64_t tiles = static_cast<int64_t>(p.tiles_m) * p.tiles_n;
     // Split K so that the workgroups fill whole rounds of the machine (256 CUs x workgroups
     // per CU) without paying too much for the partial tiles every slice adds.  In units of
-    // the GEMM's time at full occupancy, c slices cost about 1 / fill(c) + c * 1400 / T: a
-    // slice writes and re-reads 8 bytes per output element at ~4 TB/s while the GEMM spends
-    // 2 T flops per output element at ~1.4 PFLOP/s (a slice of at most 16 MB stays in the
-    // caches and costs about a third of that).  Each slice keeps at least 8 K tiles.
+    // the GEMM's time at full occupancy, c slices cost about 1 / fill(c) + c * k / T.  For
+    // outputs of more than 16 MB per slice (the 7B / 13B layers) k = 1400: a slice writes and
+    // re-reads 8 bytes per output element at ~4 TB/s while the GEMM spends 2 T flops per output
+    // element at ~1.4 PFLOP/s.  The short, wide products of the small models are bound by
+    // memory, not by the matrix cores, so an unfilled round costs them less and a slice
+    // relatively more; k is then fitted to sweeps of the slice count on their layer shapes
+    // (T = 65536): 2400 for the large tile (1024 x 1024 at r = 256: 42 slices, 81 us per step,
+    // against 64 slices, 92 us) and 800 for the small one (512 x 512 at r = 128: 94 slices).
+    // Each slice keeps at least 8 K tiles.
     const int64_t slots = 256 * Cfg::kWgPerCu;
-    const int64_t smax = ktiles / 8 > 0 ? (ktiles / 8 < 128 ? ktiles / 8 : 128) : 1;
+    int64_t smax = ktiles / 8 > 0 ? (ktiles / 8 < 128 ? ktiles / 8 : 128) : 1;
+    if (const int cap = test_option(GRASS_TEST_MAX_K_SLICES)) smax = cap > 0 && cap < smax ? cap : smax;
     const bool cached = p.Mp * p.Np * 4 <= kCachedSliceBytes;
-    const double per_slice = (cached ? 400.0 : 1400.0) / static_cast<double>(T > 0 ? T : 1);
+    const double k = cached ? (Cfg::BM == 256 ? 2400.0 : 800.0) : 1400.0;
+    const double per_slice = k / static_cast<double>(T > 0 ? T : 1);
     int64_t s = 1;
     double best = 1e300;
     for (int64_t c = 1; c <= smax && tiles > 0; ++c) {

@@ -19,7 +19,7 @@ F32, BF16 = 0, 1
 SEL_TOPR, SEL_UNIFORM, SEL_MULTI_NORM, SEL_MULTI_NORM2 = 0, 1, 2, 3
 SCALE_PAPER, SCALE_ONE, SCALE_INV_SQRT_RQ = 0, 1, 2
 DY_TxM, DY_MxT = 0, 1
-TEST_GEMM_TILE, TEST_FUSED_STATS, TEST_PACK_MXT, TEST_NO_PAIRS = 0, 1, 2, 3
+TEST_GEMM_TILE, TEST_FUSED_STATS, TEST_PACK_MXT, TEST_NO_PAIRS, TEST_MAX_K_SLICES = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "grass_status_string", "grass_row_stats", "grass_select_workspace", "grass_select_rows",

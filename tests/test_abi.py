@@ -366,6 +366,12 @@ def test_plan_query_and_test_options():
     finally:
         grass.set_test_option(grass.TEST_GEMM_TILE, 0)
     assert grass.cgrad_plan(1056, 264, 260, grass.BF16)[0] == 128
+    grass.set_test_option(grass.TEST_MAX_K_SLICES, 6)
+    try:
+        assert grass.cgrad_plan(65536, 512, 128, grass.BF16) == (128, 6)
+    finally:
+        grass.set_test_option(grass.TEST_MAX_K_SLICES, 0)
+    assert grass.cgrad_plan(65536, 512, 128, grass.BF16)[1] > 8
     L = grass.lib()
     assert L.grass_set_test_option(17, 1) == grass.ERR_DTYPE
     t, k = C.c_int(0), C.c_int(0)
