@@ -425,11 +425,12 @@ def main():
                     state_dtype=torch.bfloat16 if args.adam_state == "bf16" else torch.float32,
                     store_GC=False)
 
-    def run(steps, gemm_events=None, end_events=None):
+    def run(steps, gemm_events=None, end_events=None, tail_events=None):
         for t in range(steps):
             if t % REFRESH_EVERY == 0:
                 st.refresh(dY, X, reset_state=True)
-            st.step(dY, X, W, gemm_events[t] if gemm_events else None)
+            st.step(dY, X, W, gemm_events[t] if gemm_events else None,
+                    tail_events[t] if tail_events else None)
             if end_events:
                 end_events[t].record()
 
@@ -448,19 +449,25 @@ def main():
     settle_launches, settle_first_ms, settle_last_ms = settle(run_regular, args.settle_launches)
     gemm_events = [(ev(), ev()) for _ in range(args.steps)]
     end_events = [ev() for _ in range(args.steps)]
+    # the fused tail's own start and end (row selection; the column form has no such hook)
+    tail_events = [(ev(), ev()) for _ in range(args.steps)] if args.side == "rows" else None
     torch.cuda.synchronize()
     t_start, t_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     wall0 = time.perf_counter()
     t_start.record()
-    run(args.steps, gemm_events, end_events)
+    run(args.steps, gemm_events, end_events, tail_events)
     t_stop.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     total_ms = t_start.elapsed_time(t_stop)
     ms_per_step = total_ms / args.steps
     gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
-    # what follows the GEMM inside the step: the fused split-K reduction + Adam + row update
-    tail_ms = float(np.mean([g[1].elapsed_time(e) for g, e in zip(gemm_events, end_events)]))
+    # what follows the GEMM inside the step: the fused split-K reduction + Adam + row update.
+    # Its own dispatch times where the library can stamp them; else (and in addition) the
+    # interval from the end of the GEMM to the end of the step, which includes the launch gap.
+    tail_gap_ms = float(np.mean([g[1].elapsed_time(e) for g, e in zip(gemm_events, end_events)]))
+    tail_ms = (float(np.mean([a.elapsed_time(b) for a, b in tail_events])) if tail_events
+               else tail_gap_ms)
     # regular steps alone (the timed region holds one refresh step, at t = 0)
     regular = [end_events[t - 1].elapsed_time(end_events[t]) for t in range(1, args.steps)
                if t % REFRESH_EVERY != 0]
@@ -530,7 +537,10 @@ def main():
     tail_bytes = r * st.n * (4 * plan_slices + 4 * st.M.element_size() + 2 * esz)
     out["step_tail"] = {"what": "split-K reduction + Adam + update after the GEMM, inside the step "
                                 "(fused kernel; for column selection plus the column update)",
-                        "ms": tail_ms, "k_slices": plan_slices, "algorithmic_bytes": tail_bytes,
+                        "ms": tail_ms, "timed_by": ("the kernel dispatch's own start and end" if tail_events
+                                                    else "events after the GEMM and at the end of the step"),
+                        "ms_from_end_of_gemm_to_end_of_step": tail_gap_ms,
+                        "k_slices": plan_slices, "algorithmic_bytes": tail_bytes,
                         "GBs": tail_bytes / (tail_ms * 1e-3) / 1e9,
                         "frac_hbm": tail_bytes / (tail_ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 

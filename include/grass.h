@@ -185,9 +185,12 @@ grass_status grass_cgrad_plan(int64_t T, int64_t n, int64_t rows, grass_dtype dt
                               grass_dy_layout layout, int* tile, int* k_slices);
 
 /* grass_compressed_grad with a timing hook: the two hipEvent_t handles (passed as
- * void*, either may be NULL) are recorded on `stream` immediately before and after
- * the matrix-multiply kernel, so that a caller can time that kernel apart from the
- * gather and reduction passes around it.  Everything else is identical. */
+ * void*; created by the caller; either may be NULL) receive the start and the end of the
+ * matrix-multiply kernel, so that a caller can time that kernel apart from the gather and
+ * reduction passes around it.  For the large-tile kernel the runtime stamps the events with
+ * the kernel dispatch's own start and end (the interval a profiler's kernel trace reports);
+ * for the other kernels they are recorded on `stream` immediately before and after the
+ * launch.  Everything else is identical. */
 grass_status grass_compressed_grad_timed(const void* dY, grass_dy_layout layout, int64_t ldy,
                                          const void* X, int64_t ldx, grass_dtype dt, int64_t T,
                                          int64_t m, int64_t n, int64_t r, const int32_t* idx,
@@ -362,6 +365,20 @@ grass_status grass_step_group(int count, const grass_step_layer* layers, grass_d
                               float eps, int64_t t, const float* step_scalars, float alpha,
                               void* ws, size_t ws_bytes, void* stream, void* ev_gemm_start,
                               void* ev_gemm_stop);
+
+/* grass_step_group with a second pair of timing hooks: ev_tail_start / ev_tail_stop (hipEvent_t
+ * as void*, either may be NULL) receive the start and the end of the kernel that follows the
+ * matrix multiply (split-K reduction + Adam + row update; with several layers, the launch that
+ * serves them together, or the last layer's when the layers run one after the other), stamped
+ * with that dispatch's own times.  For a benchmark that wants the step's tail as it runs inside
+ * the step sequence.  Everything else is grass_step_group. */
+grass_status grass_step_group_timed(int count, const grass_step_layer* layers,
+                                    grass_dy_layout layout, const void* X, int64_t ldx,
+                                    grass_dtype dt, int64_t T, int64_t n, grass_dtype sdt,
+                                    grass_dtype wdt, float lr, float beta1, float beta2, float eps,
+                                    int64_t t, const float* step_scalars, float alpha, void* ws,
+                                    size_t ws_bytes, void* stream, void* ev_gemm_start,
+                                    void* ev_gemm_stop, void* ev_tail_start, void* ev_tail_stop);
 
 /* The regular step in column form, in one call (Section 4.1 projects the smaller dimension of
  * G; for a layer with m > n that is the input dimension, so r of the n COLUMNS of W are

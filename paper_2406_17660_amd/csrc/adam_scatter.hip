@@ -666,25 +666,30 @@ bool reduce_adam_scatter_ok(const StepTail& t, int64_t n, const float* GC, int64
 template <typename WT, typename ST, bool kToU = false>
 static void reduce_adam_scatter_typed(const TailSets& sets, int count, int64_t rmax, int slices,
                                       int64_t Mp, int64_t Np, int64_t n, const AdamParams& p,
-                                      float alpha, hipStream_t s) {
+                                      float alpha, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
     if (slices <= 8) {
         dim3 grid = grid_for(n, rmax, 4);
         grid.z = static_cast<unsigned>(count);
-        reduce_adam_scatter_few_kernel<WT, ST, kToU><<<grid, kThreads, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+        launch_stamped(reduce_adam_scatter_few_kernel<WT, ST, kToU>, grid, dim3(kThreads), 0, s, e0, e1,
+                       sets, slices, Mp, Np, n, p, alpha);
         return;
     }
     const dim3 grid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(rmax),
                     static_cast<unsigned>(count));
     if (slices <= 32)
-        reduce_adam_scatter_kernel<WT, ST, kToU, 4><<<grid, 4 * 64, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+        launch_stamped(reduce_adam_scatter_kernel<WT, ST, kToU, 4>, grid, dim3(4 * 64), 0, s, e0, e1,
+                       sets, slices, Mp, Np, n, p, alpha);
     else if (slices <= 64)
-        reduce_adam_scatter_kernel<WT, ST, kToU, 8><<<grid, 8 * 64, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+        launch_stamped(reduce_adam_scatter_kernel<WT, ST, kToU, 8>, grid, dim3(8 * 64), 0, s, e0, e1,
+                       sets, slices, Mp, Np, n, p, alpha);
     else
-        reduce_adam_scatter_kernel<WT, ST, kToU, 16><<<grid, 16 * 64, 0, s>>>(sets, slices, Mp, Np, n, p, alpha);
+        launch_stamped(reduce_adam_scatter_kernel<WT, ST, kToU, 16>, grid, dim3(16 * 64), 0, s, e0, e1,
+                       sets, slices, Mp, Np, n, p, alpha);
 }
 
 grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
-                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s) {
+                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s,
+                                        hipEvent_t e0, hipEvent_t e1) {
     int64_t rmax = 0;
     for (int i = 0; i < count; ++i) rmax = sets.set[i].r > rmax ? sets.set[i].r : rmax;
     if (count < 1 || rmax == 0 || n == 0) return GRASS_OK;
@@ -694,14 +699,14 @@ grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int sli
     if (sets.set[0].U) {  // column form: W is not touched here
         for (int i = 0; i < count; ++i)
             if (!sets.set[i].U) return GRASS_ERR_SHAPE;  // one form per launch
-        if (sf) reduce_adam_scatter_typed<uint16_t, float, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
-        else reduce_adam_scatter_typed<uint16_t, uint16_t, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+        if (sf) reduce_adam_scatter_typed<uint16_t, float, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
+        else reduce_adam_scatter_typed<uint16_t, uint16_t, true>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
         return launch_status();
     }
-    if (wf && sf) reduce_adam_scatter_typed<float, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
-    else if (wf) reduce_adam_scatter_typed<float, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
-    else if (sf) reduce_adam_scatter_typed<uint16_t, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
-    else reduce_adam_scatter_typed<uint16_t, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s);
+    if (wf && sf) reduce_adam_scatter_typed<float, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
+    else if (wf) reduce_adam_scatter_typed<float, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
+    else if (sf) reduce_adam_scatter_typed<uint16_t, float>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
+    else reduce_adam_scatter_typed<uint16_t, uint16_t>(sets, count, rmax, slices, Mp, Np, n, p, t.alpha, s, e0, e1);
     return launch_status();
 }
 

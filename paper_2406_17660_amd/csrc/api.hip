@@ -287,6 +287,18 @@ grass_status grass_step_group(int count, const grass_step_layer* layers, grass_d
                               float eps, int64_t t, const float* step_scalars, float alpha,
                               void* ws, size_t ws_bytes, void* stream, void* ev_gemm_start,
                               void* ev_gemm_stop) {
+    return grass_step_group_timed(count, layers, layout, X, ldx, dt, T, n, sdt, wdt, lr, beta1, beta2,
+                                  eps, t, step_scalars, alpha, ws, ws_bytes, stream, ev_gemm_start,
+                                  ev_gemm_stop, nullptr, nullptr);
+}
+
+grass_status grass_step_group_timed(int count, const grass_step_layer* layers,
+                                    grass_dy_layout layout, const void* X, int64_t ldx,
+                                    grass_dtype dt, int64_t T, int64_t n, grass_dtype sdt,
+                                    grass_dtype wdt, float lr, float beta1, float beta2, float eps,
+                                    int64_t t, const float* step_scalars, float alpha, void* ws,
+                                    size_t ws_bytes, void* stream, void* ev_gemm_start,
+                                    void* ev_gemm_stop, void* ev_tail_start, void* ev_tail_stop) {
     if (count < 1 || count > GRASS_MAX_GROUP) return GRASS_ERR_SHAPE;
     if (!layers) return GRASS_ERR_NULL;
     GemmSegment seg[GRASS_MAX_GROUP];
@@ -321,7 +333,9 @@ grass_status grass_step_group(int count, const grass_step_layer* layers, grass_d
     }
     return launch_tn_gemm_segments(seg, count, layout, X, ldx, dt, T, n, GRASS_F32, ws,
                                    as_stream(stream), static_cast<hipEvent_t>(ev_gemm_start),
-                                   static_cast<hipEvent_t>(ev_gemm_stop));
+                                   static_cast<hipEvent_t>(ev_gemm_stop),
+                                   static_cast<hipEvent_t>(ev_tail_start),
+                                   static_cast<hipEvent_t>(ev_tail_stop));
 }
 
 size_t grass_step_cols_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_dtype dt) {

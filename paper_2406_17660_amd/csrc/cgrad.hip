@@ -279,7 +279,8 @@ grass_status run_tail_unfused(const GemmSegment& q, int64_t n, hipStream_t s) {
 grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy_layout layout,
                                      const void* X, int64_t ldx, grass_dtype dt, int64_t T,
                                      int64_t n, grass_dtype odt, void* ws, hipStream_t s,
-                                     hipEvent_t ev_start, hipEvent_t ev_stop) {
+                                     hipEvent_t ev_start, hipEvent_t ev_stop,
+                                     hipEvent_t ev_tail_start, hipEvent_t ev_tail_stop) {
     int64_t total = 0;  // panel columns in use
     for (int i = 0; i < count; ++i) {
         if (seg[i].rows > 65535) return GRASS_ERR_SHAPE;
@@ -302,10 +303,12 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
                     ldx, T, g.rows, n, g.idx, g.rho, static_cast<uint16_t*>(g.C), g.ldc);
         }
         if (ev_stop) (void)hipEventRecord(ev_stop, s);
+        if (ev_tail_start) (void)hipEventRecord(ev_tail_start, s);
         for (int i = 0; i < count; ++i) {
             const grass_status st = run_tail_unfused(seg[i], n, s);
             if (st != GRASS_OK) return st;
         }
+        if (ev_tail_stop) (void)hipEventRecord(ev_tail_stop, s);
         return launch_status();
     }
 
@@ -318,9 +321,12 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         const Plan joint = plan_for(choose_tile(T, total, n), T, total, n, pack);
         if (joint.Mp * joint.Np * 4 > kCachedSliceBytes) {
             for (int i = 0; i < count; ++i) {
+                // (timing hooks: the first set's GEMM and the last set's tail)
+                const bool first = i == 0, last = i + 1 == count;
                 const grass_status st = launch_tn_gemm_segments(
-                    seg + i, 1, layout, X, ldx, dt, T, n, odt, ws, s, i == 0 ? ev_start : nullptr,
-                    i + 1 == count ? ev_stop : nullptr);
+                    seg + i, 1, layout, X, ldx, dt, T, n, odt, ws, s, first ? ev_start : nullptr,
+                    first ? ev_stop : nullptr, last ? ev_tail_start : nullptr,
+                    last ? ev_tail_stop : nullptr);
                 if (st != GRASS_OK) return st;
             }
             return GRASS_OK;
@@ -490,24 +496,27 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
     g.splits = p.splits;
     g.ktiles_per_split = p.ktiles_per_split;
 
-    if (ev_start) (void)hipEventRecord(ev_start, s);
     const unsigned grid = static_cast<unsigned>(chunk * kNumXcd);
     hipError_t le;
-    if (tile == kTile256) {
+    if (tile == kTile256) {  // the events are stamped with this dispatch's own start and end
         if (a_pairs)
-            tn_gemm_bf16_direct_kernel<false, false, true, true><<<grid, 256, 0, s>>>(g);
+            launch_stamped(tn_gemm_bf16_direct_kernel<false, false, true, true>, dim3(grid), dim3(256), 0, s,
+                           ev_start, ev_stop, g);
         else if (a_rows_form)
-            tn_gemm_bf16_direct_kernel<false, false, true><<<grid, 256, 0, s>>>(g);
+            launch_stamped(tn_gemm_bf16_direct_kernel<false, false, true>, dim3(grid), dim3(256), 0, s,
+                           ev_start, ev_stop, g);
         else if (gathered)
-            tn_gemm_bf16_direct_kernel<false><<<grid, 256, 0, s>>>(g);
+            launch_stamped(tn_gemm_bf16_direct_kernel<false>, dim3(grid), dim3(256), 0, s, ev_start, ev_stop, g);
         else
-            tn_gemm_bf16_direct_kernel<true><<<grid, 256, 0, s>>>(g);
+            launch_stamped(tn_gemm_bf16_direct_kernel<true>, dim3(grid), dim3(256), 0, s, ev_start, ev_stop, g);
         le = hipSuccess;
-    } else
+    } else {
+        if (ev_start) (void)hipEventRecord(ev_start, s);
         le = gathered ? launch_gemm_kernel<Cfg128, false>(g, grid, s)
                       : launch_gemm_kernel<Cfg128, true>(g, grid, s);
+        if (le == hipSuccess && ev_stop) (void)hipEventRecord(ev_stop, s);
+    }
     if (le != hipSuccess) return GRASS_ERR_DEVICE;
-    if (ev_stop) (void)hipEventRecord(ev_stop, s);
     int slices = p.splits;
     if (T_main < T) {  // rows [T_main, T) as one more slice, computed with 128 x 128 tiles
         GemmArgs t = g;
@@ -543,7 +552,8 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             if (q.tail->U) {  // column form: its own launch, followed by the column update
                 TailSets single;
                 single.set[0] = one;
-                grass_status st = launch_reduce_adam_scatter(single, 1, slices, p.Mp, p.Np, n, *q.tail, s);
+                grass_status st = launch_reduce_adam_scatter(single, 1, slices, p.Mp, p.Np, n, *q.tail, s,
+                                                             ev_tail_start, ev_tail_stop);
                 if (st != GRASS_OK) return st;
                 st = launch_scatter_cols(q.tail->W, q.tail->wdt, q.tail->w_rows, q.tail->ldw, q.idx,
                                          q.rho, q.tail->alpha, q.tail->U, q.rows, s);
@@ -568,14 +578,16 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             else
                 splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
                     part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+            if (q.tail && ev_tail_start) (void)hipEventRecord(ev_tail_start, s);
             const grass_status st = run_tail_unfused(q, n, s);
             if (st != GRASS_OK) return st;
+            if (q.tail && ev_tail_stop) (void)hipEventRecord(ev_tail_stop, s);
         }
         off += (q.rows + 7) / 8 * 8;
     }
     if (ntails > 0) {
         const grass_status st = launch_reduce_adam_scatter(tails, ntails, slices, p.Mp, p.Np, n,
-                                                           *tail_common, s);
+                                                           *tail_common, s, ev_tail_start, ev_tail_stop);
         if (st != GRASS_OK) return st;
     }
     return launch_status();

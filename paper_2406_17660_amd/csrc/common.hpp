@@ -2,6 +2,7 @@
 // reductions and scans, launch-error mapping.  Nothing here is used by the CPU oracle.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/grass.h"
@@ -165,8 +166,22 @@ struct TailSets {
 // The fused tail for `count` row sets in one launch.  The sets share the partial-tile geometry,
 // n, the dtypes, the form (row or column) and Adam's scalars, which are taken from `t` (its M, V,
 // W, U are not read).  In column form the caller launches the column update afterwards.
+// ev_start / ev_stop: optional events that receive the kernel's own start and stop times.
 grass_status launch_reduce_adam_scatter(const TailSets& sets, int count, int slices, int64_t Mp,
-                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s);
+                                        int64_t Np, int64_t n, const StepTail& t, hipStream_t s,
+                                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+
+// A kernel launch that, given events, has the runtime stamp them with the start and the end of
+// this very dispatch (what a profiler's kernel trace reports), instead of events recorded as
+// separate commands before and after it, which add the gaps between commands to the interval.
+template <typename Kernel, typename... Args>
+inline void launch_stamped(Kernel kernel, dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t s,
+                           hipEvent_t ev_start, hipEvent_t ev_stop, Args... args) {
+    if (ev_start || ev_stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, s, ev_start, ev_stop, 0, args...);
+    else
+        kernel<<<grid, block, lds_bytes, s>>>(args...);
+}
 
 // The same product for several row sets that share X (one packed panel, one GEMM).
 struct GemmSegment {
@@ -186,10 +201,15 @@ struct GemmSegment {
 };
 size_t gemm_group_workspace_bytes(int64_t T, const int64_t* rows, int count, int64_t n,
                                   grass_dtype dt, grass_dy_layout layout);
+// ev_start / ev_stop: stamped with the start and the end of the matrix-multiply kernel (the
+// large-tile kernel's own dispatch; for the other kernels, recorded before and after the
+// launches); ev_tail_start / ev_tail_stop: the same for the fused tail of a regular step.
 grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy_layout layout,
                                      const void* X, int64_t ldx, grass_dtype dt, int64_t T,
                                      int64_t n, grass_dtype odt, void* ws, hipStream_t s,
-                                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr,
+                                     hipEvent_t ev_tail_start = nullptr,
+                                     hipEvent_t ev_tail_stop = nullptr);
 
 // Row statistic of G = dY^T X without storing G (fused into the GEMM when the shape allows).
 size_t grad_row_stats_workspace_bytes(int64_t T, int64_t m, int64_t n, grass_dtype dt,

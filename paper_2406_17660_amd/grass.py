@@ -31,7 +31,7 @@ EXPORTS = [
     "grass_adam_rows_state", "grass_adam_scatter_state", "grass_cgrad_plan",
     "grass_set_test_option", "grass_select_static_capacity", "grass_select_rows_static",
     "grass_adam_step_scalars", "grass_adam_scatter_replayable",
-    "grass_step_group_workspace", "grass_step_group",
+    "grass_step_group_workspace", "grass_step_group", "grass_step_group_timed",
     "grass_step_cols_workspace", "grass_step_cols",
 ]
 
@@ -92,6 +92,7 @@ def lib():
     L.grass_step_group_workspace.restype = sz
     L.grass_step_group.argtypes = [i32, vp, i32, vp, i64, i32, i64, i64, i32, i32, f32, f32, f32,
                                    f32, i64, vp, f32, vp, sz, vp, vp, vp]
+    L.grass_step_group_timed.argtypes = L.grass_step_group.argtypes + [vp, vp]
     L.grass_step_cols_workspace.argtypes = [i64, i64, i64, i64, i32]
     L.grass_step_cols_workspace.restype = sz
     L.grass_step_cols.argtypes = [vp, i64, vp, i64, i32, i64, i64, i64, i64, vp, vp, vp, i64, vp, vp,
@@ -307,9 +308,11 @@ def step_group_workspace(T, n, rs, dtype, layout=DY_TxM) -> int:
 
 
 def step_group(dYs, X, idxs, rhos, Ms, Vs, Ws, lr, beta1, beta2, eps, t, alpha, ws, layout=DY_TxM,
-               GCs=None, step_scalars=None, gemm_events=None):
+               GCs=None, step_scalars=None, gemm_events=None, tail_events=None):
     """The regular step (compressed gradient, Adam, row update) of several layers sharing X in
-    one call; GCs: optional list with a tensor (G_C is stored there) or None per layer."""
+    one call; GCs: optional list with a tensor (G_C is stored there) or None per layer;
+    gemm_events / tail_events: optional (start, stop) torch.cuda.Event pairs (recorded once, so
+    that their handles exist) for the matrix-multiply kernel and for the fused tail."""
     count = len(dYs)
     pX, T, n, ldx = _mat(X)
     arr = (StepLayer * count)()
@@ -335,9 +338,15 @@ def step_group(dYs, X, idxs, rhos, Ms, Vs, Ws, lr, beta1, beta2, eps, t, alpha, 
     sc = C.c_void_p(step_scalars.data_ptr()) if step_scalars is not None else None
     e0, e1 = ((C.c_void_p(e.cuda_event) for e in gemm_events) if gemm_events is not None
               else (None, None))
-    _check(lib().grass_step_group(count, arr, layout, pX, ldx, _dtype(X), T, n, sdt, wdt, lr, beta1,
-                                  beta2, eps, t, sc, alpha, wp, wb, _stream(), e0, e1),
-           "grass_step_group")
+    if tail_events is None:
+        _check(lib().grass_step_group(count, arr, layout, pX, ldx, _dtype(X), T, n, sdt, wdt, lr,
+                                      beta1, beta2, eps, t, sc, alpha, wp, wb, _stream(), e0, e1),
+               "grass_step_group")
+    else:
+        t0, t1 = (C.c_void_p(e.cuda_event) for e in tail_events)
+        _check(lib().grass_step_group_timed(count, arr, layout, pX, ldx, _dtype(X), T, n, sdt, wdt,
+                                            lr, beta1, beta2, eps, t, sc, alpha, wp, wb, _stream(),
+                                            e0, e1, t0, t1), "grass_step_group_timed")
 
 
 def step_cols_workspace(T, m, n, r, dtype) -> int:

@@ -141,7 +141,7 @@ class GrassLayer:
         return grass.adam_scatter(self.GC, self.M, self.V, a.lr, a.beta1, a.beta2, a.eps,
                                   self.adam_t, W, self.idx, self.rho, self.alpha)
 
-    def step(self, dY, X, W, gemm_events=None):
+    def step(self, dY, X, W, gemm_events=None, tail_events=None):
         """The regular step in one library call (grass_step_group, or grass_step_cols when
         columns are selected): the reduction of the product and Adam are one kernel, which
         for selected rows also updates W."""
@@ -154,4 +154,5 @@ class GrassLayer:
                                    GC=self.GC if self.store_GC else None, gemm_events=gemm_events)
         grass.step_group([dY], X, [self.idx], [self.rho], [self.M], [self.V], [W], a.lr, a.beta1,
                          a.beta2, a.eps, self.adam_t, self.alpha, self.ws_gemm, self.layout,
-                         GCs=[self.GC] if self.store_GC else None, gemm_events=gemm_events)
+                         GCs=[self.GC] if self.store_GC else None, gemm_events=gemm_events,
+                         tail_events=tail_events)
