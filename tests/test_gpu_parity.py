@@ -285,7 +285,7 @@ def test_scatter_update_and_fused_adam_scatter(wdtype, m, n, r, dup, ldw):
             assert rel_fro(got[sel] - W0[sel], Wo[sel] - W0[sel]) <= 1e-4  # fp32 cancellation
         else:
             slack = 4 * 2.0 ** -24 * (np.abs(W0[sel]) + np.abs(Wo[sel] - W0[sel]))  # fp32 sum
-            assert (np.abs(got[sel] - Wo[sel]) <= 1.01 * bf16_ulp(Wo[sel]) + slack).all()
+            assert (np.abs(got[sel] - Wo[sel]) <= 0.501 * bf16_ulp(Wo[sel]) + slack).all()
         assert np.array_equal(to_np(Wg)[rest], W0_bits[rest])  # other rows untouched, bit for bit
         assert rel_fro(to_f64(Mg), Mo) <= TOL_F32 and rel_fro(to_f64(Vg), Vo) <= TOL_F32
     assert torch.equal(W1, W2) and torch.equal(M1, M2) and torch.equal(V1, V2)
@@ -406,7 +406,7 @@ def test_scatter_update_cols(wdtype, m, n, r, dup, ldw):
     assert rel_fro(got[:, sel], Wo[:, sel]) <= tol_for(wdtype)
     slack = 4 * 2.0 ** -24 * (np.abs(W0[:, sel]) + np.abs(Wo[:, sel] - W0[:, sel]))
     if wdtype == torch.bfloat16:
-        assert (np.abs(got[:, sel] - Wo[:, sel]) <= 1.01 * bf16_ulp(Wo[:, sel]) + slack).all()
+        assert (np.abs(got[:, sel] - Wo[:, sel]) <= 0.501 * bf16_ulp(Wo[:, sel]) + slack).all()
     else:
         assert (np.abs(got[:, sel] - Wo[:, sel]) <= 2.0 ** -23 * np.abs(Wo[:, sel]) + slack).all()
     rest = np.setdiff1d(np.arange(n), sel)
@@ -1002,3 +1002,30 @@ def run_step_cols(dtype, sdtype, T, m, n, r, dup, want_gc, tile):
     assert rel_fro(to_f64(W)[:, sel], Wo[:, sel]) <= TOL_BF16
     rest = np.setdiff1d(np.arange(n), sel)
     assert np.array_equal(to_np(W)[:, rest], W0_bits[:, rest])
+
+
+def test_step_group_timing_hooks_change_nothing_but_fill_the_events():
+    """grass_step_group_timed: the same step bit for bit, and two intervals that are positive and
+    ordered (the matrix multiply ends before the fused tail starts)."""
+    T, n, m, r = 4096, 512, 300, 130
+    X = randn((T, n), torch.bfloat16, 300)
+    dY = randn((T, m), torch.bfloat16, 301, scale=0.1)
+    idx, rho = make_idx(m, r, 302, duplicates=True)
+    d_idx, d_rho = torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)
+    ws = grass.workspace(grass.step_group_workspace(T, n, [r], grass.BF16))
+    out = []
+    for timed in (False, True):
+        _, M, V = adam_inputs(r, n, 303, n)
+        W = randn((m, n), torch.bfloat16, 304, scale=0.02)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for e in ev:
+            e.record()
+        kw = dict(gemm_events=(ev[0], ev[1]), tail_events=(ev[2], ev[3])) if timed else {}
+        grass.step_group([dY], X, [d_idx], [d_rho], [M], [V], [W], LR, B1, B2, EPS, 2, 0.25, ws, **kw)
+        torch.cuda.synchronize()
+        if timed:
+            assert 0 < ev[0].elapsed_time(ev[1]) < 50 and 0 < ev[2].elapsed_time(ev[3]) < 50
+            assert ev[1].elapsed_time(ev[2]) >= 0
+        out.append((M, V, W))
+    for a, b in zip(*out):
+        assert torch.equal(a, b)

@@ -75,12 +75,10 @@ def check_on_lattice(dY, Xh, idx, rho, picked, js, cols, GC, M, V, W, W0, cfg, m
         shaky[idx[j]] |= row
     W0l = W0[np.ix_(picked, cols)]
     slack = 4 * 2.0 ** -24 * (np.abs(W0l) + np.abs(Wo[picked] - W0l))
-    ok = np.abs(gotW - Wo[picked]) <= 0.51 * bf16_ulp(Wo[picked]) + slack
-    # one rounding to bf16: half an ulp, except where the fp32 sum lands within its own
-    # rounding error of a rounding boundary (then a whole ulp)
-    ok1 = np.abs(gotW - Wo[picked]) <= 1.01 * bf16_ulp(Wo[picked]) + slack
-    assert (ok1 | shaky[picked]).all() and shaky[picked].mean() < 0.02
-    assert (ok | shaky[picked]).mean() > 0.98
+    # one rounding to bf16: half an ulp of the result; `slack` covers the fp32 rounding of the sum
+    # before it (which can also decide on which side of a rounding boundary the sum falls)
+    ok = np.abs(gotW - Wo[picked]) <= 0.501 * bf16_ulp(Wo[picked]) + slack
+    assert (ok | shaky[picked]).all() and shaky[picked].mean() < 0.02
 
 
 def run_layer(cfg, layer, method, replacement, stat_law, min_slices, max_slices, check_stat=True,
@@ -121,7 +119,7 @@ def run_layer(cfg, layer, method, replacement, stat_law, min_slices, max_slices,
     assert np.array_equal(st.rho.cpu().numpy(), rho)
     assert not bool(torch.isnan(st.GC).any())
 
-    picked, js, cols = lattice(idx, r, n, max(r // 19, 1), 173 if n > 2000 else 37)
+    picked, js, cols = lattice(idx, r, n, max(r // 37, 1), 61 if n > 2000 else 17)
     check_on_lattice(dY, Xh, idx, rho, picked, js, cols, st.GC, st.M, st.V, W, W0, cfg, m)
     sel = np.unique(idx)
     rest = np.setdiff1d(np.arange(m), sel)
@@ -207,7 +205,7 @@ def test_query_key_value_group_at_65536_tokens(cid, slices):
                      cfg.alpha, ws, GCs=GCs)
     torch.cuda.synchronize()
     for i in range(3):
-        picked, js, cols = lattice(idxs[i], r, n, max(r // 11, 1), 97 if n > 1000 else 37)
+        picked, js, cols = lattice(idxs[i], r, n, max(r // 23, 1), 41 if n > 1000 else 17)
         check_on_lattice(dYs[i], Xh, idxs[i], rhos[i], picked, js, cols, GCs[i], Ms[i], Vs[i], Ws[i],
                          W0s[i][0], cfg, m)
         rest = np.setdiff1d(np.arange(m), np.unique(idxs[i]))

@@ -271,7 +271,7 @@ def test_config5_full_size_sampled(layer):
     for j, row in zip(js, np.abs(want) < 1e-4 * np.abs(want).mean(axis=1, keepdims=True)):
         shaky[idx[j]] |= row
     slack = 4 * 2.0 ** -24 * (np.abs(W0[np.ix_(picked, cols)]) + np.abs(Wo[picked] - W0[np.ix_(picked, cols)]))
-    ok = np.abs(gotW[np.ix_(picked, cols)] - Wo[picked]) <= 1.01 * bf16_ulp(Wo[picked]) + slack
+    ok = np.abs(gotW[np.ix_(picked, cols)] - Wo[picked]) <= 0.501 * bf16_ulp(Wo[picked]) + slack
     assert (ok | shaky[picked]).all() and shaky[picked].mean() < 0.02
     sel = np.unique(idx)
     rest = np.setdiff1d(np.arange(m), sel)
@@ -309,9 +309,10 @@ def test_config5_full_size_sampled(layer):
     gotW = to_f64(Wg)
     assert rel_fro(to_f64(Mg), M) <= TOL_F32 and rel_fro(to_f64(Vg), V) <= TOL_F32
     assert rel_fro(gotW[sel], Wo[sel]) <= TOL_BF16
-    # one bf16 rounding, plus the fp32 rounding of the sum (matters where W and its update cancel)
+    # one bf16 rounding (half an ulp), plus the fp32 rounding of the sum (matters where W and its
+    # update cancel)
     slack = 4 * 2.0 ** -24 * (np.abs(W0[sel]) + np.abs(Wo[sel] - W0[sel]))
-    assert (np.abs(gotW[sel] - Wo[sel]) <= 1.01 * bf16_ulp(Wo[sel]) + slack).all()
+    assert (np.abs(gotW[sel] - Wo[sel]) <= 0.501 * bf16_ulp(Wo[sel]) + slack).all()
     assert np.array_equal(to_np(Wg)[rest], W0_bits[rest])
 
 
