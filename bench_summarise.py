@@ -71,7 +71,8 @@ def kernel_trace(folder, line, key, argv):
                      f"{roof['peak']:.0f} (avg launch {roof['avg_launch_ms']:.4f} ms)")
     if "step_tail" in line:
         t = line["step_tail"]
-        facts.append(f"step tail (events) = {t['ms'] * 1e3:.1f} us = {t['GBs']:.0f} GB/s")
+        facts.append(f"step tail by bench.py's stamped events = {t['ms'] * 1e3:.1f} us (under the profiler these "
+                     "read a few us more than the profiler's own kernel times below; without it they agree)")
     if "settle_launches" in line:
         facts.append(f"settle phase: {line['settle_launches']} launches, GEMM {line['settle_gemm_ms_first_batch']:.4f} -> "
                      f"{line['settle_gemm_ms_last_batch']:.4f} ms")
