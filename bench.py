@@ -57,6 +57,11 @@ def parse():
                    help="with --block: capture the regular step into a HIP graph and replay it")
     p.add_argument("--concurrent-groups", action="store_true",
                    help="with --block: every group of layers on a HIP stream of its own")
+    p.add_argument("--refresh", choices=["one-product", "two-products"], default="one-product",
+                   help="refresh steps: the full gradient formed once and kept, its selected rows "
+                        "being the step's compressed gradient (Algorithm 1 as printed), or the "
+                        "statistic taken in the GEMM epilogue without storing G and the compressed "
+                        "gradient recomputed as on a regular step")
     p.add_argument("--settle-launches", type=int, default=400,
                    help="cap of the untimed settle phase (steps run until the GEMM's time stops falling)")
     p.add_argument("--summarise", metavar="DIR", default=None,
@@ -355,7 +360,7 @@ def bench_block(args, cfg):
                      seed=workloads.BASE_SEED, layout=layout,
                      concurrent_groups=args.concurrent_groups, store_GC=False)
     sched = RewarmSchedule(base_lr=cfg.lr, K=REFRESH_EVERY, rewarm=REFRESH_EVERY)
-    blk.refresh(dY, X)  # set-up: refresh-step workspaces are allocated outside the timed region
+    blk.refresh_step(dY, X, W)  # set-up: refresh-step workspaces are allocated outside the timed region
     for _ in range(max(args.warmup, 1)):
         blk.step(dY, X, W)
     torch.cuda.synchronize()
@@ -427,10 +432,13 @@ def main():
 
     def run(steps, gemm_events=None, end_events=None, tail_events=None):
         for t in range(steps):
-            if t % REFRESH_EVERY == 0:
-                st.refresh(dY, X, reset_state=True)
-            st.step(dY, X, W, gemm_events[t] if gemm_events else None,
-                    tail_events[t] if tail_events else None)
+            if t % REFRESH_EVERY == 0 and args.refresh == "one-product":
+                st.refresh_step(dY, X, W, reset_state=True)  # no compressed-gradient GEMM in it
+            else:
+                if t % REFRESH_EVERY == 0:
+                    st.refresh(dY, X, reset_state=True)
+                st.step(dY, X, W, gemm_events[t] if gemm_events else None,
+                        tail_events[t] if tail_events else None)
             if end_events:
                 end_events[t].record()
 
@@ -438,7 +446,12 @@ def main():
         for t in range(steps):
             st.step(dY, X, W, gemm_events[t])
 
-    st.row_statistic(dY, X)  # set-up: allocates the refresh-step workspace outside the timed region
+    # set-up: the refresh-step workspaces are allocated outside the timed region
+    if args.refresh == "one-product":
+        st.refresh_step(dY, X, W)
+        st.step(dY, X, W)
+    else:
+        st.row_statistic(dY, X)
     # One plain device-to-device copy of X (T*n*2 bytes read, as many written): the known-size
     # transfer against which the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated.
     calib = torch.empty_like(X)
@@ -461,13 +474,18 @@ def main():
     wall = time.perf_counter() - wall0
     total_ms = t_start.elapsed_time(t_stop)
     ms_per_step = total_ms / args.steps
-    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in gemm_events]))
+    # steps whose events were recorded: all of them, or the regular ones
+    timed = [t for t in range(args.steps)
+             if not (t % REFRESH_EVERY == 0 and args.refresh == "one-product")]
+    if not timed:
+        sys.exit("--steps 1 with --refresh one-product times no compressed-gradient GEMM")
+    gemm_ms = float(np.mean([gemm_events[t][0].elapsed_time(gemm_events[t][1]) for t in timed]))
     # what follows the GEMM inside the step: the fused split-K reduction + Adam + row update.
     # Its own dispatch times where the library can stamp them; else (and in addition) the
     # interval from the end of the GEMM to the end of the step, which includes the launch gap.
-    tail_gap_ms = float(np.mean([g[1].elapsed_time(e) for g, e in zip(gemm_events, end_events)]))
-    tail_ms = (float(np.mean([a.elapsed_time(b) for a, b in tail_events])) if tail_events
-               else tail_gap_ms)
+    tail_gap_ms = float(np.mean([gemm_events[t][1].elapsed_time(end_events[t]) for t in timed]))
+    tail_ms = (float(np.mean([tail_events[t][0].elapsed_time(tail_events[t][1]) for t in timed]))
+               if tail_events else tail_gap_ms)
     # regular steps alone (the timed region holds one refresh step, at t = 0)
     regular = [end_events[t - 1].elapsed_time(end_events[t]) for t in range(1, args.steps)
                if t % REFRESH_EVERY != 0]
@@ -531,6 +549,11 @@ def main():
                            "gemm_kernel_tflops": gemm_tflops, "gemm_kernel_ms": gemm_ms,
                            "gemm_kernel_frac_mfma": gemm_tflops / PEAK_BF16_MFMA_TFLOPS}
     out["regular_step_ms"] = regular_ms
+    out["refresh_step_ms"] = t_start.elapsed_time(end_events[0])
+    out["refresh_step"] = ("full gradient formed once and kept (fp32), row norms from it, selection, the "
+                           "selected rows of it as G_C, Adam + update" if args.refresh == "one-product" else
+                           "row norms in the epilogue of the full-gradient GEMM (G not stored), selection, "
+                           "then a regular step")
     # The step's tail as it runs inside the step sequence (state and weights come from HBM: a
     # whole GEMM pass lies between two uses): from the event after the GEMM to the end of the step.
     plan_tile, plan_slices = grass.cgrad_plan(T, st.n, r, st.dt, layout)
@@ -646,12 +669,16 @@ def main():
         detail["speedup_vs_naive_full_G_then_gather"] = (med_dense + med_g) / detail[
             "compressed_grad_call_ms"]
         detail["regular_step_ms"] = detail["compressed_grad_call_ms"] + detail["adam_scatter_ms"]
-        # a refresh step = statistic + selection + zeroing the state + the regular step
+        # a refresh step with two products = statistic + selection + zeroing the state + the
+        # regular step (sum of the parts); with one product: measured as a whole
         med, _ = time_calls(lambda: (st.M.zero_(), st.V.zero_()), it)
-        detail["refresh_step_ms"] = (detail["refresh_statistic_fused_ms"] + detail["select_rows_ms"]
-                                     + med + detail["regular_step_ms"])
+        detail["refresh_step_two_products_ms"] = (detail["refresh_statistic_fused_ms"]
+                                                  + detail["select_rows_ms"] + med
+                                                  + detail["regular_step_ms"])
+        med, _ = time_calls(lambda: st.refresh_step(dY, X, W), 5, warmup=1)
+        detail["refresh_step_one_product_ms"] = med
         detail["amortised_step_ms_K200"] = (199 * detail["regular_step_ms"]
-                                            + detail["refresh_step_ms"]) / 200
+                                            + detail["refresh_step_one_product_ms"]) / 200
         # What a plain stream of the Adam kernel's size reaches when its data is cold: a + b -> c
         # over r x n fp32 arrays (12 B per element), eight sets cycled.  Kernels of tens of
         # microseconds do not reach the rates of the 1 GiB streams above.

@@ -320,8 +320,12 @@ grass_status grass_grad_row_stats(const void* dY, grass_dy_layout layout, int64_
                                   int64_t n, float* sumsq, void* ws, size_t ws_bytes,
                                   void* stream);
 
-/* Row gather used by the naive comparator: out[j, :] = rho[j] * G[idx[j], :]
- * (fp32 out, r x n, leading dimension ldo).  Errors: NULL, SHAPE, DTYPE. */
+/* Row gather: out[j, :] = rho[j] * G[idx[j], :] (fp32 out, r x n, leading dimension ldo).
+ * This is P^T G read from a stored full gradient: the second half of the naive comparator,
+ * and the compressed gradient of a refresh step of Algorithm 1, where the full gradient has
+ * just been formed for compute_P anyway (grass_dense_grad into an fp32 G, grass_row_stats,
+ * grass_select_rows, this call, grass_adam_scatter: one matrix product for the whole step).
+ * Errors: NULL, SHAPE, DTYPE. */
 grass_status grass_gather_rows(const void* G, grass_dtype gdt, int64_t m, int64_t n, int64_t ldg,
                                const int32_t* idx, const float* rho, int64_t r, float* out,
                                int64_t ldo, void* stream);

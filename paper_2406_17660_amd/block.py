@@ -90,6 +90,7 @@ class GrassBlock:
                                          device)
         self.t = 0
         self.graph = None
+        self.G32 = self.ws_dense = None  # refresh_step(): allocated on first use
 
     def refresh(self, dY, X, statistics=None):
         """compute_P (+ update_state) for every layer.  dY: {name: tensor}, X: {group: tensor};
@@ -99,6 +100,27 @@ class GrassBlock:
             for name in g:
                 self.layers[name].refresh(dY[name], X[g], reset_state=self.reset_state,
                                           statistic=(statistics or {}).get(name))
+
+    def refresh_step(self, dY, X, W, lr=None, statistics=None):
+        """The refresh step of every layer with one matrix product per layer (see
+        GrassLayer.refresh_step): the full gradient of a layer is kept while P is computed and
+        its selected rows are the compressed gradient of this step.  One fp32 buffer of the
+        largest layer's size serves all layers in turn."""
+        if self.G32 is None:
+            dev = next(iter(W.values())).device
+            ls = self.layers.values()
+            self.G32 = torch.empty(max(l.m * l.n for l in ls), dtype=torch.float32, device=dev)
+            self.ws_dense = grass.workspace(
+                max(grass.dense_workspace(l.T, l.m, l.n, l.dt, l.layout) for l in ls), dev)
+            for l in ls:
+                l.share_refresh_buffers(self.G32, self.ws_dense)
+        for g in self.groups:
+            for name in g:
+                l = self.layers[name]
+                if lr is not None:
+                    l.adam = AdamHyper(lr, self.adam.beta1, self.adam.beta2, self.adam.eps)
+                l.refresh_step(dY[name], X[g], W[name], reset_state=self.reset_state,
+                               statistic=(statistics or {}).get(name))
 
     def _step_group(self, g, dY, X, W, lr, step_scalars=None):
         """One library call for the group: grouped G_C, Adam and the row updates."""
@@ -136,10 +158,12 @@ class GrassBlock:
             main.wait_event(joined)
 
     def train_step(self, dY, X, W, schedule: RewarmSchedule, statistics=None):
-        """Step t of Algorithm 1 under `schedule`: refresh when t = 0 mod K, then update."""
+        """Step t of Algorithm 1 under `schedule`: when t = 0 mod K the refresh step (P from
+        the full gradient, whose selected rows are also this step's compressed gradient), else
+        the regular step."""
         if schedule.is_refresh(self.t):
-            self.refresh(dY, X, statistics)
-        if self.graph is not None:
+            self.refresh_step(dY, X, W, schedule.lr(self.t), statistics)
+        elif self.graph is not None:
             self.replay(schedule.lr(self.t))
         else:
             self.step(dY, X, W, schedule.lr(self.t))

@@ -69,6 +69,7 @@ class GrassLayer:
         self.store_GC = store_GC  # False: the one-call step does not write G_C at all
         self.ws_dense = None  # allocated on first refresh: only refresh steps need it
         self.G = None
+        self.G32 = self.ws_dense32 = None  # refresh_step(): the kept full gradient
         self.ws_stats = None
         self.materialise_G = materialise_G
         self.adam_t = 0
@@ -108,7 +109,8 @@ class GrassLayer:
             self.row_statistic(dY, X)
         else:
             assert statistic.dtype == torch.float32 and tuple(statistic.shape) == (self.m,)
-            self.sumsq.copy_(statistic)
+            if statistic is not self.sumsq:
+                self.sumsq.copy_(statistic)
         grass.select_rows(self.sumsq, self.r, self.method, self.replacement, self.scale, self.seed,
                           self.refresh_id, self.idx, self.rho, self.ws_sel)
         self.refresh_id += 1
@@ -116,6 +118,33 @@ class GrassLayer:
             self.M.zero_()
             self.V.zero_()
             self.adam_t = 0
+
+    def share_refresh_buffers(self, G32, ws_dense):
+        """Use the caller's buffers for refresh_step(): G32 holds at least m * n fp32 values and
+        ws_dense at least grass.dense_workspace(T, m, n, ...) bytes.  The layers of a block take
+        their refresh steps one after the other and can share one pair."""
+        assert G32.dtype == torch.float32 and G32.numel() >= self.m * self.n
+        self.G32 = G32.reshape(-1)[:self.m * self.n].view(self.m, self.n)
+        self.ws_dense32 = ws_dense
+
+    def refresh_step(self, dY, X, W, reset_state=True, statistic=None):
+        """A whole refresh step of Algorithm 1 with one matrix product: the full gradient is
+        formed once (fp32, kept until the step ends), P is computed from its row norms, and
+        the step's compressed gradient P^T G is read from that same G (rho[j] times row idx[j])
+        instead of being recomputed from dY and X; Adam and the update of W follow as in a
+        regular step.  Costs m * n * 4 bytes of scratch during refresh steps only.
+        `statistic` as in refresh()."""
+        dYo, Xo = self._operands(dY, X)
+        if self.G32 is None:
+            self.G32 = torch.empty((self.m, self.n), dtype=torch.float32, device=Xo.device)
+            self.ws_dense32 = grass.workspace(
+                grass.dense_workspace(self.T, self.m, self.n, self.dt, self.layout), Xo.device)
+        grass.dense_grad(dYo, Xo, self.G32, self.ws_dense32, self.layout)
+        if statistic is None:
+            grass.row_stats(self.G32, self.sumsq)
+        self.refresh(None, None, reset_state, self.sumsq if statistic is None else statistic)
+        grass.gather_rows(self.G32, self.idx, self.rho, self.GC)
+        return self.adam_scatter(W)
 
     # -- regular step -----------------------------------------------------------------
     def compressed_grad(self, dY, X, gemm_events=None):

@@ -39,6 +39,9 @@ def test_layer_bench_line_has_every_field_of_the_contract():
     t = d["step_tail"]
     assert t["ms"] > 0 and abs(t["GBs"] - t["algorithmic_bytes"] / (t["ms"] * 1e-3) / 1e9) < 1e-6 * t["GBs"]
     assert d["regular_step_ms"] > 0
+    # the refresh step (one full-gradient product at 4x the flops) is the first timed step
+    assert d["refresh_step_ms"] > d["regular_step_ms"] and "kept" in d["refresh_step"]
+    assert d["detail"]["refresh_step_one_product_ms"] < d["detail"]["refresh_step_two_products_ms"]
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == d["unit"] and c["cores"] >= 1 and c["value"] > 0
     assert isinstance(c["sample"], str) and c["sample"]
@@ -54,6 +57,12 @@ def test_layer_bench_line_of_a_memory_bound_configuration():
     assert abs(r["achieved"] - r["bytes_per_launch"] / (r["avg_launch_ms"] * 1e-3) / 1e9) < 1e-6 * r["achieved"]
     assert r["bytes_per_launch"] == 2 * 8192 * (512 + 512) + 128 * 512 * 20
     assert d["step_tail"]["k_slices"] > 8 and d["config"]["key"] == "c2_attn_qkvo"
+
+
+def test_layer_bench_with_the_two_product_refresh_step():
+    d = run_bench("--tokens", "4096", "--steps", "3", "--warmup", "1", "--refresh", "two-products",
+                  "--no-cpu-baseline", "--no-extras")
+    assert d["refresh_step_ms"] > d["regular_step_ms"] and "not stored" in d["refresh_step"]
 
 
 def test_block_bench_line():

@@ -61,7 +61,7 @@ class OracleLayer:
 
 def run_config(cfg, layer, T, steps, refresh_every, method=None, replacement=None,
                scale=grass.SCALE_PAPER, g_dtype=None, materialise_G=False,
-               state_dtype=torch.float32):
+               state_dtype=torch.float32, one_product_refresh=False):
     L = cfg.layers[layer]
     method = method or cfg.method
     replacement = cfg.replacement if replacement is None else replacement
@@ -104,12 +104,19 @@ def run_config(cfg, layer, T, steps, refresh_every, method=None, replacement=Non
             # rounded once to the type the selection reads (nothing the GPU computed goes into
             # the oracle).
             ss32 = ref_ss.astype(np.float32)
-            st.refresh(dY, X, statistic=torch.from_numpy(ss32).to(DEV))
+            if one_product_refresh:
+                # the whole refresh step from one full gradient: its kept fp32 copy gives the
+                # statistic's squares and, through the selected rows, this step's G_C
+                st.refresh_step(dY, X, W, statistic=torch.from_numpy(ss32).to(DEV))
+                assert rel_fro(to_f64(st.G32), G) <= 2e-5
+            else:
+                st.refresh(dY, X, statistic=torch.from_numpy(ss32).to(DEV))
             assert grass.select_status(st.ws_sel) == grass.OK
             orc.refresh(ss32)
             assert np.array_equal(st.idx.cpu().numpy(), orc.idx), f"rows differ at step {t}"
             assert np.array_equal(st.rho.cpu().numpy(), orc.rho)
-        st.step(dY, X, W)
+        if not (one_product_refresh and t % refresh_every == 0):
+            st.step(dY, X, W)
         orc.step(dYh, Xh)
         touched.update(orc.idx.tolist())
         shaky = np.abs(orc.GC) < 1e-4 * np.abs(orc.GC).mean(axis=1, keepdims=True)
@@ -154,6 +161,22 @@ def test_config2_llama60m_multinorm_nr(layer, scale):
     two runs stores G in bf16 on refresh steps, the other takes the statistic in the GEMM."""
     run_config(workloads.CONFIGS[2], layer, 2048, 10, 5, scale=scale,
                materialise_G=(scale == grass.SCALE_PAPER))
+
+
+@pytest.mark.parametrize("config,layer,T", [(2, 0, 2048), (2, 2, 2048), (3, 1, 1024), (4, 2, 512)])
+def test_refresh_step_from_one_full_gradient(config, layer, T):
+    """Algorithm 1's refresh step with the full gradient formed once and kept: P from its row
+    norms, the step's compressed gradient from its selected rows (no second product)."""
+    cfg = workloads.CONFIGS[config]
+    st, orc = run_config(cfg, layer, T=T, steps=7, refresh_every=3, one_product_refresh=True)
+    # the statistic the kept gradient gives on its own (the run selected from the oracle's)
+    dY = workloads.make_dY(cfg, layer, 6, DEV, T=T)
+    X = workloads.make_X(cfg, layer, 6, DEV, T=T)
+    W = workloads.make_W(cfg, layer, DEV)
+    st.refresh_step(dY, X, W)
+    ref_ss = ref.row_stats(ref.full_grad(to_np(dY), to_np(X)))
+    assert rel_fro(st.sumsq.cpu().numpy(), ref_ss) <= TOL_F32
+    check_own_selection(st.idx.cpu().numpy(), ref_ss, st.r, st.method, st.replacement)
 
 
 @pytest.mark.parametrize("layer", [0, 2])
@@ -350,8 +373,9 @@ def test_config5_full_size_row_gathering_gemm_sampled():
 
 
 # ------------------------------------------------------------------------------ column projection
+@pytest.mark.parametrize("one_product_refresh", [False, True])
 @pytest.mark.parametrize("method,replacement", [("topr", False), ("multi_norm", True)])
-def test_column_projection_steps(method, replacement):
+def test_column_projection_steps(method, replacement, one_product_refresh):
     """A gate/up-shaped layer (m > n) with the r selected COLUMNS of W trained: the row form of
     the transposed layer.  The oracle runs the same exchange and the column update."""
     from paper_2406_17660_amd.layer import GrassLayer
@@ -383,13 +407,18 @@ def test_column_projection_steps(method, replacement):
             assert status == grass.OK
             check_own_selection(own_idx.cpu().numpy(), ref_ss, r, st.method, replacement)
             ss32 = ref_ss.astype(np.float32)  # both sides select from the oracle's statistic
-            st.refresh(dY, X, statistic=torch.from_numpy(ss32).to(DEV))
+            if one_product_refresh:  # G^T kept, its selected rows are this step's G_C
+                st.refresh_step(dY, X, W, statistic=torch.from_numpy(ss32).to(DEV))
+                assert rel_fro(to_f64(st.G32), Gt) <= 2e-5
+            else:
+                st.refresh(dY, X, statistic=torch.from_numpy(ss32).to(DEV))
             assert grass.select_status(st.ws_sel) == grass.OK
             idx, rho, _ = ref.select_rows(ss32, r, REF_METHOD[method], replacement,
                                           ref.SCALE_PAPER, 5, 0)
             assert np.array_equal(st.idx.cpu().numpy(), idx)
             assert np.array_equal(st.rho.cpu().numpy(), rho)
-        st.step(dY, X, W)
+        if not (one_product_refresh and t == 0):
+            st.step(dY, X, W)
         GC = ref.compressed_grad(Xh, dYh, idx, rho)  # r x m
         assert rel_fro(to_f64(st.GC), GC) <= 2e-5
         U = ref.adam_rows(GC, M, V, float(F(adam.lr)), float(F(adam.beta1)), float(F(adam.beta2)),
