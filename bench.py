@@ -478,12 +478,24 @@ def main():
     timed = [t for t in range(args.steps)
              if not (t % REFRESH_EVERY == 0 and args.refresh == "one-product")]
     if not timed:
-        sys.exit("--steps 1 with --refresh one-product times no compressed-gradient GEMM")
+        # --steps 1: the one timed step is the refresh step, which runs no compressed-gradient
+        # GEMM.  Time that kernel and the tail on a few regular steps after the timed region.
+        timed = list(range(5))
+        gemm_events = [(ev(), ev()) for _ in timed]
+        end_events_r = [ev() for _ in timed]
+        tail_events = [(ev(), ev()) for _ in timed] if tail_events else None
+        for t in timed:
+            st.step(dY, X, W, gemm_events[t], tail_events[t] if tail_events else None)
+            end_events_r[t].record()
+        torch.cuda.synchronize()
+        tail_end = end_events_r
+    else:
+        tail_end = end_events
     gemm_ms = float(np.mean([gemm_events[t][0].elapsed_time(gemm_events[t][1]) for t in timed]))
     # what follows the GEMM inside the step: the fused split-K reduction + Adam + row update.
     # Its own dispatch times where the library can stamp them; else (and in addition) the
     # interval from the end of the GEMM to the end of the step, which includes the launch gap.
-    tail_gap_ms = float(np.mean([gemm_events[t][1].elapsed_time(end_events[t]) for t in timed]))
+    tail_gap_ms = float(np.mean([gemm_events[t][1].elapsed_time(tail_end[t]) for t in timed]))
     tail_ms = (float(np.mean([tail_events[t][0].elapsed_time(tail_events[t][1]) for t in timed]))
                if tail_events else tail_gap_ms)
     # regular steps alone (the timed region holds one refresh step, at t = 0)

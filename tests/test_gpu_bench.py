@@ -65,6 +65,14 @@ def test_layer_bench_with_the_two_product_refresh_step():
     assert d["refresh_step_ms"] > d["regular_step_ms"] and "not stored" in d["refresh_step"]
 
 
+def test_layer_bench_of_a_single_step_still_prices_the_gemm():
+    """One timed step is the refresh step (no compressed-gradient product in it): the GEMM and the
+    tail are then timed on regular steps after the timed region."""
+    d = run_bench("--tokens", "4096", "--steps", "1", "--warmup", "1", "--no-cpu-baseline", "--no-extras")
+    assert d["steps"] == 1 and abs(d["refresh_step_ms"] - d["ms_per_step"]) < 0.05 * d["ms_per_step"]
+    assert d["roofline"]["avg_launch_ms"] > 0 and d["step_tail"]["ms"] > 0
+
+
 def test_block_bench_line():
     d = run_bench("--block", "60m", "--tokens", "2048", "--steps", "4", "--warmup", "1")
     assert d["unit"] == "block-steps/s" and d["n_gpus"] == 1 and d["value"] > 0
