@@ -314,6 +314,29 @@ def test_config5_full_size_sampled(layer):
     assert bool(torch.isnan(st2.GC).all())  # and G_C was indeed not stored
     del st2, W2
 
+    # bench.py's refresh step: the full gradient formed once and kept in fp32, the rows selected
+    # from the same seeded statistic, G_C read from the selected rows of the kept gradient.
+    # Against the oracle's values of the lattice above (from the inputs alone).
+    st3 = GrassLayer(m, n, r, T, cfg.dtype, cfg.method, cfg.replacement, alpha=cfg.alpha, adam=adam,
+                     seed=workloads.BASE_SEED)
+    W3 = workloads.make_W(cfg, layer, DEV)
+    st3.refresh_step(dY, X, W3, statistic=torch.from_numpy(ss).to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(st3.idx, st.idx) and torch.equal(st3.rho, st.rho) and st3.adam_t == 1
+    assert rel_fro(to_f64(st3.G32[torch.from_numpy(rows).to(DEV)]), G_rows) <= 2e-5
+    kept_ss = torch.empty(m, device=DEV)
+    grass.row_stats(st3.G32, kept_ss)
+    assert rel_fro(kept_ss.cpu().numpy()[rows], ref.row_stats(G_rows)) <= TOL_F32
+    got3 = to_f64(st3.GC)[np.ix_(js, cols)]
+    assert rel_fro(got3, want) <= 2e-5 and np.abs(got3 - want).max() <= 1e-4 * np.abs(want).max()
+    assert rel_fro(to_f64(st3.M)[np.ix_(js, cols)], M) <= 2e-5
+    assert rel_fro(to_f64(st3.V)[np.ix_(js, cols)], V) <= 2e-5
+    gotW3 = to_f64(W3)
+    ok = np.abs(gotW3[np.ix_(picked, cols)] - Wo[picked]) <= 0.501 * bf16_ulp(Wo[picked]) + slack
+    assert (ok | shaky[picked]).all()
+    assert np.array_equal(to_np(W3)[rest], W0_bits[rest])
+    del st3, W3, kept_ss
+
     # Adam and the row update in full at this size, on a seeded compressed gradient
     g = torch.Generator(device=DEV)
     g.manual_seed(workloads.BASE_SEED + 77 + layer)
