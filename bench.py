@@ -217,7 +217,7 @@ def layer_figures(cfg, layer, steps=40):
     dense_ms, _ = time_calls(lambda: st.full_gradient(dY, X), 3, warmup=1)
     tmp = torch.empty((r, n), dtype=torch.float32, device="cuda")
     gather_ms, _ = time_calls(lambda: grass.gather_rows(st.G, st.idx, st.rho, tmp), 10)
-    tile, slices = grass.cgrad_plan(T, n, r, st.dt)
+    tile, slices = grass.cgrad_plan(T, n, r, st.dt, m=m)
     return {"layer": L.name, "m": m, "n": n, "T": T, "r": r, "regular_step_ms": step_ms,
             "layer_steps_per_s": 1e3 / step_ms, "gemm_kernel_ms": gemm_ms,
             "gemm_kernel_tflops": flops / (gemm_ms * 1e-3) / 1e12,
@@ -568,7 +568,7 @@ def main():
                            "then a regular step")
     # The step's tail as it runs inside the step sequence (state and weights come from HBM: a
     # whole GEMM pass lies between two uses): from the event after the GEMM to the end of the step.
-    plan_tile, plan_slices = grass.cgrad_plan(T, st.n, r, st.dt, layout)
+    plan_tile, plan_slices = grass.cgrad_plan(T, st.n, r, st.dt, layout, m=st.m)
     tail_bytes = r * st.n * (4 * plan_slices + 4 * st.M.element_size() + 2 * esz)
     out["step_tail"] = {"what": "split-K reduction + Adam + update after the GEMM, inside the step "
                                 "(fused kernel; for column selection plus the column update)",

@@ -172,17 +172,21 @@ grass_status grass_compressed_grad(const void* dY, grass_dy_layout layout, int64
                                    const float* rho, float* GC, int64_t ldgc, void* ws,
                                    size_t ws_bytes, void* stream);
 
-/* How the product above is planned for a panel of `rows` gathered rows (r for one matrix; for
- * a group call the sum of its r[i], each rounded up to a multiple of 8): `*tile` receives the
- * edge of the output tile (256, 128, or 64 for fp32 inputs) and `*k_slices` the number of
- * slices the token dimension is split into (their partial products are what the split-K
- * reduction, or the fused tail of grass_step_group / grass_step_cols, adds up; above 8 slices
- * those kernels spread the slices over the wavefronts of a workgroup).  A pure host function,
- * for callers that want to know what a shape costs and for tests that must reach every kernel.
- * Operands whose base or leading dimension is not 16-byte aligned fall back to the 128 tile at
- * launch whatever this reports.  Errors: NULL, SHAPE, DTYPE. */
-grass_status grass_cgrad_plan(int64_t T, int64_t n, int64_t rows, grass_dtype dt,
-                              grass_dy_layout layout, int* tile, int* k_slices);
+/* How the product above is planned for `count` sets of gathered rows that share X (count = 1:
+ * one matrix), `rows` rows in all (r for one matrix; for a group call the sum of its r[i], each
+ * rounded up to a multiple of 8; the sets are taken to be of equal size), m the row length of
+ * dY (0: not given).  `*tile` receives the edge of the output tile (256, 128, or 64 for fp32
+ * inputs), or 0 for narrow layers (bf16, T x m storage, m <= 512, r <= 128 per set, n <= 512, T
+ * a multiple of 16), whose gather runs inside the matrix-multiply kernel (128 x 256 tiles, no
+ * packed panel); `*k_slices` the number of slices the token dimension is split into (their
+ * partial products are what the split-K reduction, or the fused tail of grass_step_group /
+ * grass_step_cols, adds up; above 8 slices those kernels spread the slices over the wavefronts
+ * of a workgroup).  A pure host function, for callers that want to know what a shape costs and
+ * for tests that must reach every kernel.  Operands whose base or leading dimension is not
+ * 16-byte aligned take the packed route with the 128 tile at launch whatever this reports.
+ * Errors: NULL, SHAPE, DTYPE. */
+grass_status grass_cgrad_plan(int64_t T, int64_t m, int64_t n, int64_t rows, int count,
+                              grass_dtype dt, grass_dy_layout layout, int* tile, int* k_slices);
 
 /* grass_compressed_grad with a timing hook: the two hipEvent_t handles (passed as
  * void*; created by the caller; either may be NULL) receive the start and the end of the
@@ -439,13 +443,16 @@ grass_status grass_adam_scatter_replayable(const float* GC, int64_t ldgc, void* 
  *                            row-gathering GEMM
  *   GRASS_TEST_NO_PAIRS      1: the row-gathering GEMM loads one K tile per request
  *   GRASS_TEST_MAX_K_SLICES  k > 0: the token dimension is split into at most k slices
+ *   GRASS_TEST_NO_NARROW_GATHER  1: narrow layers take the packed route like all others (forcing
+ *                            the tile with GRASS_TEST_GEMM_TILE does the same)
  * Errors: DTYPE for an unknown option. */
 typedef enum {
     GRASS_TEST_GEMM_TILE = 0,
     GRASS_TEST_FUSED_STATS = 1,
     GRASS_TEST_PACK_MXT = 2,
     GRASS_TEST_NO_PAIRS = 3,
-    GRASS_TEST_MAX_K_SLICES = 4
+    GRASS_TEST_MAX_K_SLICES = 4,
+    GRASS_TEST_NO_NARROW_GATHER = 5
 } grass_test_option;
 grass_status grass_set_test_option(grass_test_option option, int value);
 

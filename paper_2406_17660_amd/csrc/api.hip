@@ -10,7 +10,7 @@ using namespace grass;
 
 namespace {
 
-constexpr int kNumTestOptions = 5;
+constexpr int kNumTestOptions = 6;
 std::atomic<int> g_test_options[kNumTestOptions];  // zero-initialised: the library decides
 
 constexpr int64_t kMaxGridRows = 65535;  // rows are carried in blockIdx.y
@@ -136,13 +136,14 @@ size_t grass_cgrad_workspace(int64_t T, int64_t m, int64_t n, int64_t r, grass_d
     return gemm_workspace_bytes(T, r, n, dt, layout, true);
 }
 
-grass_status grass_cgrad_plan(int64_t T, int64_t n, int64_t rows, grass_dtype dt,
-                              grass_dy_layout layout, int* tile, int* k_slices) {
+grass_status grass_cgrad_plan(int64_t T, int64_t m, int64_t n, int64_t rows, int count,
+                              grass_dtype dt, grass_dy_layout layout, int* tile, int* k_slices) {
     if (!tile || !k_slices) return GRASS_ERR_NULL;
-    if (T < 0 || n < 0 || rows < 0 || !small(T) || !small(n) || rows > kMaxGridRows)
+    if (T < 0 || m < 0 || n < 0 || rows < 0 || !small(T) || !small(m) || !small(n) ||
+        rows > kMaxGridRows || count < 1 || count > GRASS_MAX_GROUP)
         return GRASS_ERR_SHAPE;
     if (!dtype_ok(dt) || !layout_ok(layout)) return GRASS_ERR_DTYPE;
-    gemm_plan_summary(T, rows, n, dt, layout, tile, k_slices);
+    gemm_plan_summary(T, m, rows, count, n, dt, layout, tile, k_slices);
     return GRASS_OK;
 }
 

@@ -30,6 +30,7 @@
 #include "pack_kernels.hpp"
 #include "gemm_small.hpp"
 #include "gemm_large.hpp"
+#include "gemm_gather_narrow.hpp"
 #include "reduce_kernels.hpp"
 
 namespace grass {
@@ -122,6 +123,51 @@ TileId choose_tile(int64_t T, int64_t rows, int64_t n) {
 
 Plan plan_for(TileId id, int64_t T, int64_t rows, int64_t n, bool pack) {
     return id == kTile256 ? make_plan<Shape256>(T, rows, n, pack) : make_plan<Cfg128>(T, rows, n, pack);
+}
+
+// ---- narrow layers: the gather inside the GEMM (gemm_gather_narrow.hpp)
+// Shapes the kernel takes, apart from what is asked of every set and of the addresses: at most two
+// column tiles (beyond that each tile re-reads the rows of dY once more and the packed route wins:
+// 66 against 62 us at n = 1376), whole K tiles.
+bool narrow_shape_ok(int64_t T, int64_t n, grass_dtype dt, grass_dy_layout layout) {
+    return test_option(GRASS_TEST_NO_NARROW_GATHER) == 0 && test_option(GRASS_TEST_GEMM_TILE) == 0 &&
+           dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kNarrowBK && T % kNarrowBK == 0 &&
+           n >= 8 && n % 8 == 0 && n <= 2 * kNarrowBN;
+}
+// one set: a single row tile, rows of dY that fit a stage
+bool narrow_set_ok(int64_t rows, int64_t m_src) {
+    return rows > 0 && rows <= kNarrowBM && m_src >= 8 && m_src % 8 == 0 && m_src <= kNarrowMaxM;
+}
+struct NarrowPlan {
+    int64_t Mp, Np;
+    int tiles_n, splits, ktiles_per_split;
+};
+// `tiles_m` row tiles in all, `panel_rows` rows of partial tiles per slice, `in_cols` = the row
+// lengths of all inputs together (sum of m over the sets, plus n).  Slices: about two workgroups
+// per compute unit (what the kernel's LDS use allows), as long as the partial tiles stay under a
+// quarter of the input bytes (measured at the 60M shapes, T = 65536: 512 x 512 at r = 128 takes
+// 26 us with 128 slices, 30 - 33 with 96, 170 or 256; the q/k/v group 66 us with 85 slices, 82
+// with 42), every slice keeps at least four K tiles, and the workspace holds them.
+NarrowPlan narrow_plan(int64_t T, int64_t n, int tiles_m, int64_t panel_rows, int64_t in_cols,
+                       size_t cap_bytes) {
+    NarrowPlan p;
+    p.tiles_n = static_cast<int>((n + kNarrowBN - 1) / kNarrowBN);
+    p.Np = static_cast<int64_t>(p.tiles_n) * kNarrowBN;
+    p.Mp = (panel_rows + 7) / 8 * 8;
+    const int64_t ktiles = T / kNarrowBK, tiles = static_cast<int64_t>(tiles_m) * p.tiles_n;
+    const int64_t slice_bytes = p.Mp * p.Np * 4;
+    int64_t s = tiles > 0 ? (512 + tiles - 1) / tiles : 1;
+    const int64_t by_traffic = T * in_cols * 2 / 4 / (slice_bytes > 0 ? slice_bytes : 1);
+    const int64_t by_space = static_cast<int64_t>(cap_bytes) / (slice_bytes > 0 ? slice_bytes : 1);
+    s = s < by_traffic ? s : by_traffic;
+    s = s < by_space ? s : by_space;
+    s = s < ktiles / 4 ? s : ktiles / 4;
+    s = s < 128 ? s : 128;
+    if (const int cap = test_option(GRASS_TEST_MAX_K_SLICES)) s = cap > 0 && cap < s ? cap : s;
+    s = s < 1 ? 1 : s;
+    p.ktiles_per_split = static_cast<int>((ktiles + s - 1) / s);
+    p.splits = static_cast<int>((ktiles + p.ktiles_per_split - 1) / p.ktiles_per_split);
+    return p;
 }
 
 template <typename Cfg, bool kDense>
@@ -225,11 +271,19 @@ size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
     return (wa > wb ? wa : wb) + aligned_x_bytes(T, n) + 256;
 }
 
-void gemm_plan_summary(int64_t T, int64_t rows, int64_t n, grass_dtype dt, grass_dy_layout layout,
-                       int* tile, int* k_slices) {
+void gemm_plan_summary(int64_t T, int64_t m, int64_t rows, int count, int64_t n, grass_dtype dt,
+                       grass_dy_layout layout, int* tile, int* k_slices) {
     if (dt == GRASS_F32) {  // the fp32 kernel: 64 x 64 tiles, K not split
         *tile = 64;
         *k_slices = 1;
+        return;
+    }
+    if (m > 0 && count >= 1 && narrow_shape_ok(T, n, dt, layout) &&
+        narrow_set_ok((rows / count + 7) / 8 * 8, m)) {  // the sets taken to be of equal size
+        const size_t cap = gemm_workspace_bytes(T, rows, n, dt, layout, true) - 256;
+        const NarrowPlan p = narrow_plan(T, n, count, rows, m * count + n, cap);
+        *tile = 0;
+        *k_slices = p.splits;
         return;
     }
     const TileId id = T >= kFastBK && rows >= 8 && n >= 8 ? choose_tile(T, rows, n) : kTile128;
@@ -271,6 +325,69 @@ grass_status run_tail_unfused(const GemmSegment& q, int64_t n, hipStream_t s) {
     return launch_adam_scatter(static_cast<const float*>(q.C), q.ldc, t.M, t.V, t.sdt, q.rows, n,
                                t.lr, t.beta1, t.beta2, t.eps, t.t, t.W, t.wdt, t.ldw, q.idx, q.rho,
                                t.alpha, s, t.step_scalars);
+}
+
+// What follows the matrix product for every set: the split-K reduction into the set's output,
+// or, for a regular step, the fused reduction + Adam + update straight from the partial tiles
+// [slices][Mp][Np] (the sets lie one after the other along the rows, each starting at a
+// multiple of 8).
+grass_status finish_segments(const GemmSegment* seg, int count, const float* partial, int slices,
+                             int64_t Mp, int64_t Np, int64_t n, grass_dtype odt, hipStream_t s,
+                             hipEvent_t ev_tail_start, hipEvent_t ev_tail_stop) {
+    int64_t off = 0;
+    TailSets tails;  // sets whose reduction, Adam and row update run as one kernel (one launch)
+    int ntails = 0;
+    const StepTail* tail_common = nullptr;
+    for (int i = 0; i < count; ++i) {
+        const GemmSegment& q = seg[i];
+        if (q.rows > 0 && q.tail && odt == GRASS_F32 &&
+            reduce_adam_scatter_ok(*q.tail, n, q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc)) {
+            // straight from the partial tiles; launched after the loop, together
+            const TailSet one{partial + off * Np, q.rows, q.tail->M, q.tail->V, q.tail->W,
+                              q.tail->ldw, q.idx, q.rho,
+                              q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc, q.tail->U};
+            if (q.tail->U) {  // column form: its own launch, followed by the column update
+                TailSets single;
+                single.set[0] = one;
+                grass_status st = launch_reduce_adam_scatter(single, 1, slices, Mp, Np, n, *q.tail, s,
+                                                             ev_tail_start, ev_tail_stop);
+                if (st != GRASS_OK) return st;
+                st = launch_scatter_cols(q.tail->W, q.tail->wdt, q.tail->w_rows, q.tail->ldw, q.idx,
+                                         q.rho, q.tail->alpha, q.tail->U, q.rows, s);
+                if (st != GRASS_OK) return st;
+            } else {
+                tails.set[ntails++] = one;
+                tail_common = q.tail;
+            }
+        } else if (q.rows > 0) {
+            const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
+            const float* part = partial + off * Np;
+            if (slices > kManySlices && Np % 128 == 0) {
+                if (odt == GRASS_F32)
+                    splitk_reduce_many_kernel<float><<<rgrid, 256, 0, s>>>(
+                        part, slices, Mp, Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
+                else
+                    splitk_reduce_many_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
+                        part, slices, Mp, Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+            } else if (odt == GRASS_F32)
+                splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(
+                    part, slices, Mp, Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
+            else
+                splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
+                    part, slices, Mp, Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
+            if (q.tail && ev_tail_start) (void)hipEventRecord(ev_tail_start, s);
+            const grass_status st = run_tail_unfused(q, n, s);
+            if (st != GRASS_OK) return st;
+            if (q.tail && ev_tail_stop) (void)hipEventRecord(ev_tail_stop, s);
+        }
+        off += (q.rows + 7) / 8 * 8;
+    }
+    if (ntails > 0) {
+        const grass_status st = launch_reduce_adam_scatter(tails, ntails, slices, Mp, Np, n,
+                                                           *tail_common, s, ev_tail_start, ev_tail_stop);
+        if (st != GRASS_OK) return st;
+    }
+    return launch_status();
 }
 
 // C_i = scale_i * (A_i^T X) for `count` row sets that share X.  The sets are packed side by
@@ -331,6 +448,60 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
             }
             return GRASS_OK;
         }
+    }
+    // Narrow layers (every set a single row tile of short dY rows): the gather runs inside the
+    // GEMM, no panel is written.
+    bool narrow = gathered && narrow_shape_ok(T, n, dt, layout) && aligned_to(X, 16) && ldx % 8 == 0 &&
+                  ldx >= n && (kNarrowBK + 1) * ldx * 2 < (int64_t{1} << 32);
+    for (int i = 0; i < count && narrow; ++i)
+        narrow = seg[i].idx && narrow_set_ok(seg[i].rows, seg[i].src_rows) && aligned_to(seg[i].dY, 16) &&
+                 seg[i].ldy % 8 == 0 && seg[i].ldy >= seg[i].src_rows &&
+                 (kNarrowBK + 1) * seg[i].ldy * 2 < (int64_t{1} << 32);
+    if (narrow) {
+        char* base = static_cast<char*>(ws);
+        base += (256 - reinterpret_cast<uintptr_t>(base) % 256) % 256;
+        NarrowArgs a;
+        int64_t in_cols = n;
+        int off = 0;
+        for (int i = 0; i < count; ++i) {
+            a.set[i] = NarrowSet{static_cast<const uint16_t*>(seg[i].dY), seg[i].ldy, seg[i].idx,
+                                 static_cast<int>(seg[i].rows), static_cast<int>(seg[i].src_rows / 8), off, i};
+            off += static_cast<int>((seg[i].rows + 7) / 8 * 8);
+            in_cols += seg[i].src_rows;
+        }
+        // the workspace every caller has been asked for holds at least this much (same formula)
+        const size_t cap = gemm_workspace_bytes(T, total, n, dt, layout, true) - 256;
+        const NarrowPlan np = narrow_plan(T, n, count, off, in_cols, cap);
+        a.count = count;
+        a.X = static_cast<const uint16_t*>(X);
+        a.ldx = ldx;
+        a.n = n;
+        a.P = reinterpret_cast<float*>(base);
+        a.Mp = np.Mp;
+        a.Np = np.Np;
+        a.ktiles = T / kNarrowBK;
+        a.tiles_m = count;
+        a.tiles_n = np.tiles_n;
+        a.splits = np.splits;
+        a.ktiles_per_split = np.ktiles_per_split;
+        const int64_t items = static_cast<int64_t>(count) * np.tiles_n * np.splits;
+        const unsigned grid = static_cast<unsigned>((items + kNumXcd - 1) / kNumXcd * kNumXcd);
+        {   // more than 64 KB of LDS: the attribute is set once per device (see launch_gemm_kernel)
+            static std::atomic<bool> raised[64];
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess) return GRASS_ERR_DEVICE;
+            if (dev < 0 || dev >= 64 || !raised[dev].load(std::memory_order_acquire)) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(tn_gemm_gather_narrow_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kNarrowLdsBytes) != hipSuccess)
+                    return GRASS_ERR_DEVICE;
+                if (dev >= 0 && dev < 64) raised[dev].store(true, std::memory_order_release);
+            }
+        }
+        launch_stamped(tn_gemm_gather_narrow_kernel, dim3(grid), dim3(256), kNarrowLdsBytes, s, ev_start,
+                       ev_stop, a);
+        return finish_segments(seg, count, a.P, np.splits, np.Mp, np.Np, n, odt, s, ev_tail_start,
+                               ev_tail_stop);
     }
     const void* dY0 = seg[0].dY;  // read directly by the GEMM only when nothing is packed
     const int64_t ldy0 = seg[0].ldy;
@@ -537,60 +708,7 @@ grass_status launch_tn_gemm_segments(const GemmSegment* seg, int count, grass_dy
         ++slices;
     }
 
-    int64_t off = 0;
-    TailSets tails;  // sets whose reduction, Adam and row update run as one kernel (one launch)
-    int ntails = 0;
-    const StepTail* tail_common = nullptr;
-    for (int i = 0; i < count; ++i) {
-        const GemmSegment& q = seg[i];
-        if (q.rows > 0 && q.tail && odt == GRASS_F32 &&
-            reduce_adam_scatter_ok(*q.tail, n, q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc)) {
-            // straight from the partial tiles; launched after the loop, together
-            const TailSet one{partial + off * p.Np, q.rows, q.tail->M, q.tail->V, q.tail->W,
-                              q.tail->ldw, q.idx, q.rho,
-                              q.c_wanted ? static_cast<float*>(q.C) : nullptr, q.ldc, q.tail->U};
-            if (q.tail->U) {  // column form: its own launch, followed by the column update
-                TailSets single;
-                single.set[0] = one;
-                grass_status st = launch_reduce_adam_scatter(single, 1, slices, p.Mp, p.Np, n, *q.tail, s,
-                                                             ev_tail_start, ev_tail_stop);
-                if (st != GRASS_OK) return st;
-                st = launch_scatter_cols(q.tail->W, q.tail->wdt, q.tail->w_rows, q.tail->ldw, q.idx,
-                                         q.rho, q.tail->alpha, q.tail->U, q.rows, s);
-                if (st != GRASS_OK) return st;
-            } else {
-                tails.set[ntails++] = one;
-                tail_common = q.tail;
-            }
-        } else if (q.rows > 0) {
-            const dim3 rgrid(static_cast<unsigned>((n + 255) / 256), static_cast<unsigned>(q.rows));
-            const float* part = partial + off * p.Np;
-            if (slices > kManySlices && p.Np % 128 == 0) {
-                if (odt == GRASS_F32)
-                    splitk_reduce_many_kernel<float><<<rgrid, 256, 0, s>>>(
-                        part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
-                else
-                    splitk_reduce_many_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
-                        part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
-            } else if (odt == GRASS_F32)
-                splitk_reduce_kernel<float><<<rgrid, 256, 0, s>>>(
-                    part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<float*>(q.C), q.ldc);
-            else
-                splitk_reduce_kernel<uint16_t><<<rgrid, 256, 0, s>>>(
-                    part, slices, p.Mp, p.Np, q.rows, n, q.rho, static_cast<uint16_t*>(q.C), q.ldc);
-            if (q.tail && ev_tail_start) (void)hipEventRecord(ev_tail_start, s);
-            const grass_status st = run_tail_unfused(q, n, s);
-            if (st != GRASS_OK) return st;
-            if (q.tail && ev_tail_stop) (void)hipEventRecord(ev_tail_stop, s);
-        }
-        off += (q.rows + 7) / 8 * 8;
-    }
-    if (ntails > 0) {
-        const grass_status st = launch_reduce_adam_scatter(tails, ntails, slices, p.Mp, p.Np, n,
-                                                           *tail_common, s, ev_tail_start, ev_tail_stop);
-        if (st != GRASS_OK) return st;
-    }
-    return launch_status();
+    return finish_segments(seg, count, partial, slices, p.Mp, p.Np, n, odt, s, ev_tail_start, ev_tail_stop);
 }
 
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,

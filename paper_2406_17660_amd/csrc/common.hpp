@@ -113,9 +113,10 @@ grass_status launch_gather_rows(const void* G, grass_dtype gdt, int64_t n, int64
 // dense: idx = rho = nullptr).  Output dtype odt, leading dimension ldc.
 size_t gemm_workspace_bytes(int64_t T, int64_t mrows, int64_t n, grass_dtype dt,
                             grass_dy_layout layout, bool gathered);
-// Tile edge and number of K slices the launcher plans for a gathered panel of `rows` rows.
-void gemm_plan_summary(int64_t T, int64_t rows, int64_t n, grass_dtype dt, grass_dy_layout layout,
-                       int* tile, int* k_slices);
+// Tile edge and number of K slices the launcher plans for `count` gathered sets of `rows` rows in
+// all (m: row length of dY, 0 when not known; tile 0 = the kernel that gathers inside the GEMM).
+void gemm_plan_summary(int64_t T, int64_t m, int64_t rows, int count, int64_t n, grass_dtype dt,
+                       grass_dy_layout layout, int* tile, int* k_slices);
 grass_status launch_tn_gemm(const void* dY, grass_dy_layout layout, int64_t ldy, const void* X,
                             int64_t ldx, grass_dtype dt, int64_t T, int64_t mrows, int64_t n,
                             const int32_t* idx, const float* rho, void* C, grass_dtype odt,

@@ -20,6 +20,7 @@ SEL_TOPR, SEL_UNIFORM, SEL_MULTI_NORM, SEL_MULTI_NORM2 = 0, 1, 2, 3
 SCALE_PAPER, SCALE_ONE, SCALE_INV_SQRT_RQ = 0, 1, 2
 DY_TxM, DY_MxT = 0, 1
 TEST_GEMM_TILE, TEST_FUSED_STATS, TEST_PACK_MXT, TEST_NO_PAIRS, TEST_MAX_K_SLICES = 0, 1, 2, 3, 4
+TEST_NO_NARROW_GATHER = 5
 
 EXPORTS = [
     "grass_status_string", "grass_row_stats", "grass_select_workspace", "grass_select_rows",
@@ -106,7 +107,7 @@ def lib():
     L.grass_grad_row_stats_workspace.argtypes = [i64, i64, i64, i32, i32, i64, i64]
     L.grass_grad_row_stats_workspace.restype = sz
     L.grass_grad_row_stats.argtypes = [vp, i32, i64, vp, i64, i32, i64, i64, i64, vp, vp, sz, vp]
-    L.grass_cgrad_plan.argtypes = [i64, i64, i64, i32, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    L.grass_cgrad_plan.argtypes = [i64, i64, i64, i64, i32, i32, i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     L.grass_set_test_option.argtypes = [i32, i32]
     L.grass_cgrad_group_workspace.argtypes = [i64, i64, i32, vp, i32, i32]
     L.grass_cgrad_group_workspace.restype = sz
@@ -226,10 +227,11 @@ def cgrad_workspace(T, m, n, r, dtype, layout=DY_TxM) -> int:
     return int(lib().grass_cgrad_workspace(T, m, n, r, dtype, layout))
 
 
-def cgrad_plan(T, n, rows, dtype, layout=DY_TxM):
-    """(tile edge, number of K slices) the library plans for a gathered panel of `rows` rows."""
+def cgrad_plan(T, n, rows, dtype, layout=DY_TxM, m=0, count=1):
+    """(tile edge, number of K slices) the library plans for `count` gathered sets of `rows` rows
+    in all; m: row length of dY (0: not given).  Tile 0: the gather runs inside the GEMM."""
     tile, slices = C.c_int(0), C.c_int(0)
-    _check(lib().grass_cgrad_plan(T, n, rows, dtype, layout, C.byref(tile), C.byref(slices)),
+    _check(lib().grass_cgrad_plan(T, m, n, rows, count, dtype, layout, C.byref(tile), C.byref(slices)),
            "grass_cgrad_plan")
     return tile.value, slices.value
 

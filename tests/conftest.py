@@ -32,5 +32,5 @@ def _library_decides_again_after_each_test():
     from paper_2406_17660_amd import grass
     if grass._lib is not None:
         for option in (grass.TEST_GEMM_TILE, grass.TEST_FUSED_STATS, grass.TEST_PACK_MXT,
-                       grass.TEST_NO_PAIRS, grass.TEST_MAX_K_SLICES):
+                       grass.TEST_NO_PAIRS, grass.TEST_MAX_K_SLICES, grass.TEST_NO_NARROW_GATHER):
             grass.set_test_option(option, 0)

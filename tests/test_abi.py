@@ -372,12 +372,32 @@ def test_plan_query_and_test_options():
     finally:
         grass.set_test_option(grass.TEST_MAX_K_SLICES, 0)
     assert grass.cgrad_plan(65536, 512, 128, grass.BF16)[1] > 8
+    # narrow layers (row length of dY given): the gather runs inside the GEMM, tile code 0
+    assert grass.cgrad_plan(65536, 512, 128, grass.BF16, m=512) == (0, 128)
+    assert grass.cgrad_plan(65536, 512, 384, grass.BF16, m=512, count=3) == (0, 84)
+    assert grass.cgrad_plan(65536, 512, 256, grass.BF16, m=1376, count=2)[0] == 256  # rows of dY too long
+    assert grass.cgrad_plan(65536, 1376, 128, grass.BF16, m=512)[0] == 128          # too many column tiles
+    assert grass.cgrad_plan(65536, 512, 264, grass.BF16, m=512)[0] != 0             # more than one row tile
+    assert grass.cgrad_plan(65528, 512, 128, grass.BF16, m=512)[0] != 0             # ragged K
+    assert grass.cgrad_plan(65536, 512, 128, grass.BF16, grass.DY_MxT, m=512)[0] != 0
+    for option, value in ((grass.TEST_NO_NARROW_GATHER, 1), (grass.TEST_GEMM_TILE, 128)):
+        grass.set_test_option(option, value)
+        try:
+            assert grass.cgrad_plan(65536, 512, 128, grass.BF16, m=512) == (128, 94)
+        finally:
+            grass.set_test_option(option, 0)
+    grass.set_test_option(grass.TEST_MAX_K_SLICES, 9)
+    try:
+        assert grass.cgrad_plan(65536, 512, 128, grass.BF16, m=512) == (0, 9)
+    finally:
+        grass.set_test_option(grass.TEST_MAX_K_SLICES, 0)
     L = grass.lib()
     assert L.grass_set_test_option(17, 1) == grass.ERR_DTYPE
     t, k = C.c_int(0), C.c_int(0)
-    assert L.grass_cgrad_plan(64, 64, 8, grass.BF16, 0, None, C.byref(k)) == grass.ERR_NULL
-    assert L.grass_cgrad_plan(-1, 64, 8, grass.BF16, 0, C.byref(t), C.byref(k)) == grass.ERR_SHAPE
-    assert L.grass_cgrad_plan(64, 64, 8, 7, 0, C.byref(t), C.byref(k)) == grass.ERR_DTYPE
+    assert L.grass_cgrad_plan(64, 0, 64, 8, 1, grass.BF16, 0, None, C.byref(k)) == grass.ERR_NULL
+    assert L.grass_cgrad_plan(-1, 0, 64, 8, 1, grass.BF16, 0, C.byref(t), C.byref(k)) == grass.ERR_SHAPE
+    assert L.grass_cgrad_plan(64, 0, 64, 8, 0, grass.BF16, 0, C.byref(t), C.byref(k)) == grass.ERR_SHAPE
+    assert L.grass_cgrad_plan(64, 0, 64, 8, 1, 7, 0, C.byref(t), C.byref(k)) == grass.ERR_DTYPE
 
 
 def test_grad_row_stats_validation():

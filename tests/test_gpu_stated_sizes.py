@@ -85,8 +85,9 @@ def run_layer(cfg, layer, method, replacement, stat_law, min_slices, max_slices,
               T=None):
     L = cfg.layers[layer]
     T, m, n, r = T or cfg.T, L.m, L.n, cfg.r
-    tile, slices = grass.cgrad_plan(T, n, r, grass.BF16)
+    tile, slices = grass.cgrad_plan(T, n, r, grass.BF16, m=m)
     assert min_slices <= slices <= max_slices, (tile, slices)
+    assert (tile == 0) == (cfg.cid == 2 and layer == 0)  # the 60M 512 x 512 layers gather inside the GEMM
     dY = workloads.make_dY(cfg, layer, 0, DEV, T=T)
     X = workloads.make_X(cfg, layer, 0, DEV, T=T)
     W = workloads.make_W(cfg, layer, DEV)
@@ -180,8 +181,9 @@ def test_query_key_value_group_at_65536_tokens(cid, slices):
     L = cfg.layers[0]
     T, m, n, r = cfg.T, L.m, L.n, cfg.r
     total = 3 * ((r + 7) // 8 * 8)
-    tile, k_slices = grass.cgrad_plan(T, n, total, grass.BF16)
+    tile, k_slices = grass.cgrad_plan(T, n, total, grass.BF16, m=m, count=3)
     assert slices[0] <= k_slices <= slices[1], (tile, k_slices)
+    assert (tile == 0) == (cid == 2)  # the 60M group gathers inside the GEMM (one launch, no panel)
     X = workloads.make_X(cfg, 0, 0, DEV)
     Xh = to_np(X)
     rng = np.random.default_rng(700 + cid)
