@@ -95,6 +95,8 @@ def algorithmic_mb(kernel, c, slices):
     T, m, n, r = c["T"], c["m"], c["n"], c["r"]
     if "tn_gemm_bf16" in kernel and "<true" not in kernel.split("tn_gemm_bf16")[1][:30]:
         return "%.0f / %.0f" % (2 * T * (r + n) / 1e6, slices * r * n * 4 / 1e6)
+    if kernel.startswith("tn_gemm_gather_narrow"):  # the gather inside the GEMM: dY and X in, partial tiles out
+        return "%.0f / %.0f" % (2 * T * (m + n) / 1e6, slices * r * n * 4 / 1e6)
     if kernel.startswith("pack_txm"):
         return "%.0f / %.0f" % (2 * T * m / 1e6, 2 * T * r / 1e6)
     if kernel.startswith("reduce_adam_scatter"):
@@ -159,7 +161,8 @@ def hbm_traffic(folder, line, key, argv):
         # the whole regular step: every kernel of it, weighted by its launches per step
         tails = [v[0] for k, v in per_kernel.items() if k.startswith("reduce_adam_scatter")]
         steps = max(tails) if tails else 0
-        step_kernels = ("pack_", "align_rows", "tn_gemm_bf16", "reduce_adam_scatter", "scatter_cols")
+        step_kernels = ("pack_", "align_rows", "tn_gemm_bf16", "tn_gemm_gather_narrow", "reduce_adam_scatter",
+                        "scatter_cols")
         rd = wr = 0.0
         for k, (calls, r_b, w_b) in per_kernel.items():
             if steps and k.startswith(step_kernels) and "<true" not in k[:40]:
