@@ -460,10 +460,24 @@ def main():
     run(args.warmup)
     torch.cuda.synchronize()
     settle_launches, settle_first_ms, settle_last_ms = settle(run_regular, args.settle_launches)
-    gemm_events = [(ev(), ev()) for _ in range(args.steps)]
+    # Which roofline binds the layer: 2 r T n flops against the T (m + n) input elements that have
+    # to be read once (dY stored T x m: the gather touches every sector of it).  Above the ridge
+    # (2500 TFLOP/s / 8 TB/s = 312 flop/B) the dominant kernel, the GEMM, is priced against the
+    # matrix cores; below it the whole regular step is priced against HBM.
+    esz = 2 if cfg.dtype == torch.bfloat16 else 4
+    flops = 2.0 * r * T * st.n  # st.n = width of the compressed gradient (n, or m for side=cols)
+    input_bytes = esz * T * (m + n)
+    intensity = flops / input_bytes
+    mfma_bound = cfg.dtype == torch.bfloat16 and intensity >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    # Per-kernel events inside the timed region only where the dominant kernel is what is priced:
+    # a launch that carries events costs the host tens of microseconds, which a step of a narrow
+    # layer (two kernels of 10 - 50 us) does not hide.  Those layers are priced on the whole step;
+    # their kernels are timed in a pass of their own after the timed region.
+    instrument = mfma_bound
+    want_tail = args.side == "rows"  # the fused tail's own start and end (no such hook in column form)
+    gemm_events = [(ev(), ev()) for _ in range(args.steps)] if instrument else None
     end_events = [ev() for _ in range(args.steps)]
-    # the fused tail's own start and end (row selection; the column form has no such hook)
-    tail_events = [(ev(), ev()) for _ in range(args.steps)] if args.side == "rows" else None
+    tail_events = [(ev(), ev()) for _ in range(args.steps)] if instrument and want_tail else None
     torch.cuda.synchronize()
     t_start, t_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     wall0 = time.perf_counter()
@@ -476,14 +490,17 @@ def main():
     ms_per_step = total_ms / args.steps
     # steps whose events were recorded: all of them, or the regular ones
     timed = [t for t in range(args.steps)
-             if not (t % REFRESH_EVERY == 0 and args.refresh == "one-product")]
+             if instrument and not (t % REFRESH_EVERY == 0 and args.refresh == "one-product")]
+    kernel_times_from = "the timed region"
     if not timed:
-        # --steps 1: the one timed step is the refresh step, which runs no compressed-gradient
-        # GEMM.  Time that kernel and the tail on a few regular steps after the timed region.
-        timed = list(range(5))
+        # No kernel events in the timed region (a layer priced on its whole step, or --steps 1,
+        # whose one step is the refresh step and runs no compressed-gradient GEMM): time the GEMM
+        # and the tail on regular steps after the timed region.
+        timed = list(range(30 if not instrument else 5))
+        kernel_times_from = f"{len(timed)} regular steps after the timed region"
         gemm_events = [(ev(), ev()) for _ in timed]
         end_events_r = [ev() for _ in timed]
-        tail_events = [(ev(), ev()) for _ in timed] if tail_events else None
+        tail_events = [(ev(), ev()) for _ in timed] if want_tail else None
         for t in timed:
             st.step(dY, X, W, gemm_events[t], tail_events[t] if tail_events else None)
             end_events_r[t].record()
@@ -505,7 +522,6 @@ def main():
     if grass.select_status(st.ws_sel) != grass.OK:
         sys.exit("selection reported non-finite row statistics")
 
-    flops = 2.0 * r * T * st.n  # st.n = width of the compressed gradient (n, or m for side=cols)
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
         "metric": "GRASS layer steps/s (refresh every 200 steps included)",
@@ -530,14 +546,6 @@ def main():
         "host_wall_s": wall,
     }
     traffic, traffic_source = measured_traffic(out["config"]["key"], T)
-    # Which roofline binds the layer: 2 r T n flops against the T (m + n) input elements that have
-    # to be read once (dY stored T x m: the gather touches every sector of it).  Above the ridge
-    # (2500 TFLOP/s / 8 TB/s = 312 flop/B) the dominant kernel, the GEMM, is priced against the
-    # matrix cores; below it the whole regular step is priced against HBM.
-    esz = 2 if cfg.dtype == torch.bfloat16 else 4
-    input_bytes = esz * T * (m + n)
-    intensity = flops / input_bytes
-    mfma_bound = cfg.dtype == torch.bfloat16 and intensity >= PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     gemm_name = ("tn_gemm_bf16_direct_kernel<false, false, true, true>" if args.layout == "mxt"
                  else "tn_gemm_bf16_direct_kernel<false, false, false, false>")
     # bytes the one-call step has to move: the inputs once, M and V read and written, the r rows
@@ -572,7 +580,8 @@ def main():
     tail_bytes = r * st.n * (4 * plan_slices + 4 * st.M.element_size() + 2 * esz)
     out["step_tail"] = {"what": "split-K reduction + Adam + update after the GEMM, inside the step "
                                 "(fused kernel; for column selection plus the column update)",
-                        "ms": tail_ms, "timed_by": ("the kernel dispatch's own start and end" if tail_events
+                        "ms": tail_ms, "timed_over": kernel_times_from,
+                        "timed_by": ("the kernel dispatch's own start and end" if tail_events
                                                     else "events after the GEMM and at the end of the step"),
                         "ms_from_end_of_gemm_to_end_of_step": tail_gap_ms,
                         "k_slices": plan_slices, "algorithmic_bytes": tail_bytes,
