@@ -127,8 +127,9 @@ Plan plan_for(TileId id, int64_t T, int64_t rows, int64_t n, bool pack) {
 
 // ---- narrow layers: the gather inside the GEMM (gemm_gather_narrow.hpp)
 // Shapes the kernel takes, apart from what is asked of every set and of the addresses: at most two
-// column tiles (beyond that each tile re-reads the rows of dY once more and the packed route wins:
-// 66 against 62 us at n = 1376), whole K tiles.
+// column tiles (beyond that each tile re-reads and re-gathers the rows of dY once more and the
+// packed route wins: the step of a 512 x 1376 layer at r = 128, T = 65536 takes 83 us this way
+// against 74), whole K tiles.
 bool narrow_shape_ok(int64_t T, int64_t n, grass_dtype dt, grass_dy_layout layout) {
     return test_option(GRASS_TEST_NO_NARROW_GATHER) == 0 && test_option(GRASS_TEST_GEMM_TILE) == 0 &&
            dt == GRASS_BF16 && layout == GRASS_DY_TxM && T >= kNarrowBK && T % kNarrowBK == 0 &&

@@ -13,8 +13,9 @@ namespace {
 // to 512 values are 16 KB, three such stages plus the X stages still leave room for two
 // workgroups per compute unit.  At m = 1376 a stage is 44 KB, one workgroup per unit keeps too
 // few bytes in flight, and the separate gather pass (many small workgroups) followed by the
-// large-tile GEMM is faster (measured: 104 against 97 us for the 60M gate/up pair; 26 against 37
-// us for its 512 x 512 layers, 66 against 97 us for the q/k/v group).
+// large-tile GEMM is faster (measured at T = 65536, r = 128, gather pass + GEMM against this
+// kernel: 97 against 104 us for a pair of 1376-wide sets; 37 against 26 us for a 512 x 512 layer,
+// 97 against 66 us for three of them sharing X).
 //
 // Work: an output tile is 128 selected rows of one set x 256 columns; four wavefronts, each
 // 128 x 64 (eight 32 x 32 accumulator fragments).  K advances in tiles of 16 tokens through a
