@@ -2,16 +2,19 @@
 """Benchmark of the GRASS layer step on one MI355X.
 
 One "step" is one pass of Algorithm 1 for one linear layer over one synthetic token batch
-that is already resident in HBM: on steps with t = 0 (mod K, K = 200 as in the paper's
-pretraining runs) the refresh work (row statistic of the full gradient, taken in the epilogue
-of the full-gradient GEMM so that G itself is not stored; selection; state reset), and on
-every step the compressed gradient, Adam on r x n, and the scatter into W.  The
-timed region starts at t = 0, so it always contains exactly one refresh per 200 steps.
+that is already resident in HBM.  On steps with t = 0 (mod K, K = 200 as in the paper's
+pretraining runs) it is the refresh step: the full gradient formed once and kept in fp32, its
+row norms, the selection, the state reset, the selected rows of the kept gradient as G_C, Adam
+and the scatter into W (--refresh two-products: row norms in the GEMM epilogue without storing
+G, then a regular step).  On every other step: the compressed gradient, Adam on r x n, and the
+scatter into W.  The timed region starts at t = 0, so it always contains exactly one refresh
+step per 200 steps.
 
 Prints ONE JSON line: metric, value (layer steps per second), ms_per_step, the workload, a
-`roofline` object for the dominant kernel (the compressed-gradient GEMM, timed with HIP events
-around its launches) and a `cpu_baseline` object (the fp64 oracle on the host cores, on a bounded
-sample).  Only one GPU is supported.
+`roofline` object (for layers above the ridge the compressed-gradient GEMM against the matrix
+cores, timed by events stamped with the kernel's own start and end; for the others the whole
+regular step against HBM) and a `cpu_baseline` object (the fp64 oracle on the host cores, on a
+bounded sample).  Only one GPU is supported.
 """
 import argparse
 import json
