@@ -102,6 +102,23 @@ def test_groups_sharing_activations(T, n, ms, rs):
         check(got, packed, ref.compressed_grad(to_np(dY), to_np(X), idx, rho))
 
 
+def test_rows_in_any_order():
+    """The selected rows need not come sorted (the selection kernels emit them sorted; a caller's
+    own list may not be): a shuffled list with repeats."""
+    T, m, n, r = 2048, 512, 256, 128
+    dY = randn((T, m), BF, 90, scale=0.1)
+    X = randn((T, n), BF, 91)
+    rng = np.random.default_rng(92)
+    idx = rng.integers(0, m, r).astype(np.int32)
+    idx[5] = idx[100] = idx[0]
+    rho = rng.uniform(0.5, 2.0, r).astype(np.float32)
+    assert grass.cgrad_plan(T, n, r, grass.BF16, m=m)[0] == 0
+    got = to_f64(gpu_cgrad(dY, X, torch.from_numpy(idx).to(DEV), torch.from_numpy(rho).to(DEV)))
+    want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+    assert rel_fro(got, want) <= 2e-5 and np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+    assert np.array_equal(got[5] / rho[5], got[0] / rho[0]) or rel_fro(got[5] / rho[5], got[0] / rho[0]) < 1e-6
+
+
 def test_what_does_not_fit_takes_the_packed_route():
     """Eligibility is decided per call: rows of dY that are too long, too many rows in a set, a
     third column tile, a ragged token count, m x T storage and misaligned operands all give the
