@@ -42,3 +42,34 @@ def test_both_parts_multiply():
     t = 61  # 51 steps into the cosine span of 100; 1 step after the update at t = 60
     want = 4e-3 * (0.1 + 0.9 * 0.5 * (1 + math.cos(math.pi * 0.51))) * (2 / 4)
     assert s.lr(t) == pytest.approx(want)
+
+
+def test_train_step_takes_the_refresh_step_or_the_regular_step():
+    """Call order of GrassBlock.train_step (host logic only: the block is built on the CPU and
+    its three ways of taking a step are replaced by recorders): the refresh step at t = 0 mod K
+    with that step's learning rate and nothing else on that step, the regular step otherwise,
+    the captured graph's replay in its place once one exists."""
+    import torch
+
+    from paper_2406_17660_amd.block import GrassBlock
+
+    blk = GrassBlock({"q": (64, 32), "k": (64, 32), "o": (32, 32)}, [("q", "k")], r=8, T=64,
+                     dtype=torch.bfloat16, device="cpu")
+    assert blk.groups == [("q", "k"), ("o",)]
+    calls = []
+    blk.refresh_step = lambda dY, X, W, lr=None, statistics=None: calls.append(("refresh_step", lr, statistics))
+    blk.step = lambda dY, X, W, lr=None, step_scalars=None: calls.append(("step", lr))
+    blk.replay = lambda lr: calls.append(("replay", lr))
+    sched = RewarmSchedule(base_lr=1.0, warmup=0, total=10**9, min_ratio=1.0, K=3, rewarm=3)
+    for _ in range(5):
+        blk.train_step(None, None, None, sched)
+    assert [c[0] for c in calls] == ["refresh_step", "step", "step", "refresh_step", "step"]
+    assert [c[1] for c in calls] == pytest.approx([1 / 3, 2 / 3, 1.0, 1 / 3, 2 / 3])
+    assert blk.t == 5
+    blk.graph = object()  # a captured step exists: regular steps replay it, refresh steps stay eager
+    calls.clear()
+    stats = {"q": "s"}
+    for _ in range(3):
+        blk.train_step(None, None, None, sched, statistics=stats)
+    assert [c[0] for c in calls] == ["replay", "refresh_step", "replay"]
+    assert calls[1][2] is stats
