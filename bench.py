@@ -74,6 +74,11 @@ def parse():
                    help="no benchmark line: sample the GPU clock (rocm-smi) while the 7B attention "
                         "layer's kernels and the matrix-core probes run back to back, and print a "
                         "markdown table (the evidence behind the power-bound reading of the GEMM)")
+    p.add_argument("--adam-cold", action="store_true",
+                   help="run nothing but grass_adam_scatter on state that is not in the caches (eight "
+                        "sets of G_C, M, V, W cycled) and a plain a + b -> c stream of the same element "
+                        "count, 200 launches each, and print one JSON line: the command behind "
+                        "profiles/adam_scatter_cold_*.md")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip the naive comparator etc.")
     p.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -345,6 +350,48 @@ def clock_trace(cfg):
         print("| %s | %s | %s | %d | %s |" % (name, "" if ms is None else "%.4f" % ms, rate, len(clocks), c))
 
 
+def bench_adam_cold(args, cfg):
+    """grass_adam_scatter alone, cold: what a profiler needs to see that kernel by itself."""
+    L = cfg.layers[args.layer]
+    m, n, r = L.m, L.n, cfg.r
+    dev = "cuda"
+    g = torch.Generator(device=dev)
+    g.manual_seed(workloads.BASE_SEED + 7)
+    idx = torch.sort(torch.randint(0, m, (r,), generator=g, device=dev, dtype=torch.int32)).values
+    rho = torch.ones(r, device=dev)
+    sdt = torch.bfloat16 if args.adam_state == "bf16" else torch.float32
+    sets = [(torch.randn((r, n), generator=g, device=dev), torch.zeros((r, n), dtype=sdt, device=dev),
+             torch.zeros((r, n), dtype=sdt, device=dev), workloads.make_W(cfg, args.layer, dev))
+            for _ in range(8)]
+    trio = [tuple(torch.randn((r, n), generator=g, device=dev) for _ in range(3)) for _ in range(8)]
+    esz = 2 if cfg.dtype == torch.bfloat16 else 4
+    adam_bytes = r * n * (4 + 4 * sets[0][1].element_size() + 2 * esz)
+
+    def adam(k):
+        g_, m_, v_, w_ = sets[k % 8]
+        grass.adam_scatter(g_, m_, v_, cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, 1 + k, w_, idx, rho, cfg.alpha)
+
+    def add(k):
+        x_, y_, z_ = trio[k % 8]
+        torch.add(x_, y_, out=z_)
+
+    out = {"workload": f"config {cfg.cid} layer {L.name}: r={r}, n={n}, W {m}x{n}, {args.adam_state} moments; "
+                       "eight sets cycled (0.8 GB: nothing stays in the 256 MB last-level cache)"}
+    for name, fn, nbytes in (("adam_scatter_cold", adam, adam_bytes), ("plain_add_cold_same_elements", add, 12 * r * n)):
+        for k in range(16):
+            fn(k)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for k in range(200):
+            fn(k)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 200  # back to back: includes the launch gaps
+        out[name] = {"launches": 200, "ms_per_launch_back_to_back": ms, "bytes": nbytes,
+                     "GBs": nbytes / (ms * 1e-3) / 1e9, "frac_hbm": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    print(json.dumps(out))
+
+
 def bench_block(args, cfg):
     """Amortised block steps/s: every layer of one block, refresh every 200 steps, the
     re-warm-up schedule supplying the learning rate.  A secondary measurement: the headline
@@ -413,6 +460,8 @@ def main():
     cfg = workloads.CONFIGS[args.config]
     if args.clock_trace:
         return clock_trace(workloads.CONFIGS[5])
+    if args.adam_cold:
+        return bench_adam_cold(args, cfg)
     if args.block:
         return bench_block(args, cfg)
     L = cfg.layers[args.layer]
