@@ -73,6 +73,13 @@ def test_layer_bench_of_a_single_step_still_prices_the_gemm():
     assert d["roofline"]["avg_launch_ms"] > 0 and d["step_tail"]["ms"] > 0
 
 
+def test_adam_cold_mode_prints_its_two_rates():
+    d = run_bench("--adam-cold", "--config", "2", "--layer", "0")
+    for key in ("adam_scatter_cold", "plain_add_cold_same_elements"):
+        assert d[key]["launches"] == 200 and d[key]["GBs"] > 0
+    assert d["adam_scatter_cold"]["bytes"] == 128 * 512 * 24
+
+
 def test_block_bench_line():
     d = run_bench("--block", "60m", "--tokens", "2048", "--steps", "4", "--warmup", "1")
     assert d["unit"] == "block-steps/s" and d["n_gpus"] == 1 and d["value"] > 0
