@@ -102,6 +102,46 @@ def test_groups_sharing_activations(T, n, ms, rs):
         check(got, packed, ref.compressed_grad(to_np(dY), to_np(X), idx, rho))
 
 
+def _sweep(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        sets = int(rng.choice([1, 1, 2, 3, 8]))
+        ms = tuple(int(rng.integers(1, 65)) * 8 for _ in range(sets))
+        rs = tuple(int(rng.integers(1, min(128, 4 * m) + 1)) for m in ms)
+        cases.append((k, int(rng.integers(1, 129)) * 16, int(rng.integers(1, 65)) * 8, ms, rs,
+                      int(rng.choice([0, 8, 24])), int(rng.choice([0, 8]))))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,n,ms,rs,pad_y,pad_x", _sweep(32, 17660))
+def test_seeded_shape_sweep(k, T, n, ms, rs, pad_y, pad_x):
+    """Seeded random shapes inside the kernel's limits (T a multiple of 16 up to 2048, widths and
+    row lengths multiples of 8 up to 512, up to 128 unsorted rows per set with repeats, one to
+    eight sets, padded leading dimensions) against the oracle."""
+    rng = np.random.default_rng(1000 + k)
+    X = randn((T, n), BF, 200 + k, ld=n + pad_x)
+    dYs = [randn((T, m), BF, 300 + 10 * k + i, scale=0.1, ld=m + pad_y) for i, m in enumerate(ms)]
+    idxs = [rng.integers(0, m, r).astype(np.int32) for m, r in zip(ms, rs)]
+    rhos = [rng.uniform(0.5, 2.0, r).astype(np.float32) for r in rs]
+    total = sum((r + 7) // 8 * 8 for r in rs)
+    assert grass.cgrad_plan(T, n, total if len(ms) > 1 else rs[0], grass.BF16, m=max(ms), count=len(ms))[0] == 0
+    GCs = [torch.full((r, n), float("nan"), dtype=torch.float32, device=DEV) for r in rs]
+    d_idx = [torch.from_numpy(a).to(DEV) for a in idxs]
+    d_rho = [torch.from_numpy(a).to(DEV) for a in rhos]
+    if len(ms) == 1:
+        ws = grass.workspace(grass.cgrad_workspace(T, ms[0], n, rs[0], grass.BF16))
+        grass.compressed_grad(dYs[0], X, d_idx[0], d_rho[0], GCs[0], ws)
+    else:
+        ws = grass.workspace(grass.cgrad_group_workspace(T, n, rs, grass.BF16))
+        grass.compressed_grad_group(dYs, X, d_idx, d_rho, GCs, ws)
+    for dY, idx, rho, GC in zip(dYs, idxs, rhos, GCs):
+        want = ref.compressed_grad(to_np(dY), to_np(X), idx, rho)
+        got = to_f64(GC)
+        assert np.isfinite(got).all() and rel_fro(got, want) <= 2e-5
+        assert np.abs(got - want).max() <= 1e-4 * np.abs(want).max()
+
+
 def test_rows_in_any_order():
     """The selected rows need not come sorted (the selection kernels emit them sorted; a caller's
     own list may not be): a shuffled list with repeats."""
